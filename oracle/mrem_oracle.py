@@ -1,0 +1,561 @@
+"""Plain CPU oracle for one MREM module step (numpy, fp64).
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product path may import this file:
+it exists so that the HIP kernels can be checked against an independent,
+slow, obviously-correct statement of what the method computes.  It shares no
+code, tables or constants with the HIP sources.
+
+What it follows (paper: "Towards Efficient Post-training Quantization of
+Pre-trained Language Models"):
+
+* Section 3.1, Eq. 1     -- the b-bit uniform quantizer  x^ = s * Pi(x / s),
+                            integer set {-2^(b-1)+1 .. 2^(b-1)-1}, nearest integer.
+* Section 3.1 (text)     -- which tensors are quantized: the two operands of every
+                            matrix multiplication; symmetric everywhere except the
+                            softmax probabilities and the GELU output (asymmetric);
+                            LayerNorm, skip connections and biases stay full precision.
+* Section 3.1.1          -- straight-through estimator for the rounding.
+* Section 4.1, Eq. 3     -- the module objective: sum over the module's layers of the
+                            squared distance between quantized and full-precision
+                            layer outputs; variables are the module's parameters and
+                            all of its quantizer step sizes.
+* Algorithm 2            -- teacher forward, student forward, loss, update of the
+                            parameters, update of the step sizes, both outputs returned.
+* Section 4.2            -- gradients stay inside the module (nothing flows to the
+                            module input).
+* Section 4.2.1, Eq. 4   -- optional convex mix of the two module inputs.
+* Section 5.1.2          -- AdamW-style update, linearly decayed rate; learned step
+                            sizes for the activation quantizers.
+
+Readings taken where the paper is silent (each is a parameter here, the defaults
+are the ones the HIP path implements):
+
+* nearest integer = round-half-to-even;
+* the ratio v = (x - z) / s that decides a code is formed in IEEE fp32
+  (`decide32`); the clip test is closed, Qn <= v <= Qp;
+* asymmetric = unsigned grid {0 .. 2^b-1} with a fixed, not learned, offset z
+  (z = 0 for softmax probabilities);
+* per-output-channel weight steps, per-tensor activation steps;
+* layer output f_l = the hidden state after the second residual + LayerNorm;
+* loss = sum over layers of the mean (or raw sum) of squared differences;
+* erf GELU, biased-variance LayerNorm, scores scaled by 1/sqrt(d), masked keys
+  get probability exactly 0;
+* `act_round`: activations that the method materialises between operators can be
+  rounded to a storage type ('bf16' or 'f32').  With None everything is fp64.
+  This is what "bf16 activations" means in the workloads: the stored tensors
+  (qkv, context, projections, LayerNorm outputs, FFN pre-activation) hold
+  bf16 values, and the quantizer decisions are taken on those stored values.
+
+parity unpinned: none of the functions below -- every one is pinned in
+tests/test_oracle_pins.py (hand-computed fixtures under tests/golden/, closed
+forms, brute force on tiny inputs, torch fp64 autograd of the frozen-residual
+surrogate, torch.optim.AdamW).
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+
+try:  # erf: scipy if present, else math.erf vectorised (both are library routines)
+    from scipy.special import erf as _erf
+except Exception:  # pragma: no cover
+    _erf = np.vectorize(math.erf, otypes=[np.float64])
+
+
+# ----------------------------------------------------------------------------
+# configuration
+# ----------------------------------------------------------------------------
+
+#: order of the eight activation quantizers of a layer (Section 3.1: both
+#: operands of each of the six matrix multiplications; the QKV projection's
+#: three products share one input).
+ACT_Q_NAMES = ("x", "q", "k", "p", "v", "c", "x1", "g")
+AQ_X, AQ_Q, AQ_K, AQ_P, AQ_V, AQ_C, AQ_X1, AQ_G = range(8)
+#: the two asymmetric (unsigned) ones: softmax probabilities and GELU output.
+ACT_Q_UNSIGNED = (False, False, False, True, False, False, False, True)
+
+WEIGHT_NAMES = ("w_qkv", "w_o", "w_1", "w_2")
+STEP_NAMES = ("sw_qkv", "sw_o", "sw_1", "sw_2")
+
+
+@dataclass
+class Config:
+    n_layers: int
+    hidden: int
+    n_heads: int
+    ffn: int
+    w_bits: int = 4            # 0 switches the weight quantizers off
+    a_bits: int = 8            # 0 switches the activation quantizers off
+    act_round: Optional[str] = None   # None | 'f32' | 'bf16'
+    loss_layer_mask: int = -1  # bit l set => layer l contributes to Eq. 3
+    loss_mean: bool = True     # mean over elements (True) or raw sum of squares
+    ln_eps: float = 1e-12
+    beta1: float = 0.9
+    beta2: float = 0.999
+    adam_eps: float = 1e-8
+    weight_decay: float = 0.01  # on the four linear weights only
+    step_floor: float = 1e-8
+
+    @property
+    def head_dim(self) -> int:
+        return self.hidden // self.n_heads
+
+
+def sym_range(bits: int) -> Tuple[int, int]:
+    """Eq. 1: Omega(b) = {-2^(b-1)+1, ..., 2^(b-1)-1}."""
+    qp = 2 ** (bits - 1) - 1
+    return -qp, qp
+
+
+def unsigned_range(bits: int) -> Tuple[int, int]:
+    """Asymmetric reading: the 2^b levels {0, ..., 2^b - 1} shifted by an offset."""
+    return 0, 2 ** bits - 1
+
+
+# ----------------------------------------------------------------------------
+# storage rounding (dtype emulation, no method arithmetic)
+# ----------------------------------------------------------------------------
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """fp64 -> fp32 -> bfloat16 (round-to-nearest-even), returned as fp64."""
+    f = np.asarray(x, dtype=np.float64).astype(np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    u = (u + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)
+    return u.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(x))
+
+
+def round_store(x: np.ndarray, mode: Optional[str]) -> np.ndarray:
+    if mode is None:
+        return np.asarray(x, dtype=np.float64)
+    if mode == "f32":
+        return np.asarray(x, dtype=np.float64).astype(np.float32).astype(np.float64)
+    if mode == "bf16":
+        return round_bf16(x)
+    raise ValueError(f"unknown storage mode {mode!r}")
+
+
+# ----------------------------------------------------------------------------
+# quantizer: Eq. 1 + straight-through estimator (Sections 3.1, 3.1.1)
+# ----------------------------------------------------------------------------
+
+def quant_ratio(x, s, z=0.0, decide32: bool = True) -> np.ndarray:
+    """v = (x - z) / s.  With decide32 the subtraction and the division are IEEE
+    fp32 operations on the fp32 roundings of x, z and s (fp64 evaluation of one
+    fp32 operation followed by rounding to fp32 is the correctly rounded fp32
+    result, because 53 >= 2*24 + 2)."""
+    x = np.asarray(x, dtype=np.float64)
+    s = np.asarray(s, dtype=np.float64)
+    z = np.asarray(z, dtype=np.float64)
+    if not decide32:
+        return (x - z) / s
+    x32 = x.astype(np.float32).astype(np.float64)
+    s32 = s.astype(np.float32).astype(np.float64)
+    z32 = z.astype(np.float32).astype(np.float64)
+    d = (x32 - z32).astype(np.float32).astype(np.float64)
+    return (d / s32).astype(np.float32).astype(np.float64)
+
+
+def fake_quant_forward(x, s, qn: int, qp: int, z=0.0, decide32: bool = True):
+    """Eq. 1 with an optional offset: q = Pi(clamp(v, qn, qp)), x^ = s*q + z.
+
+    Returns (x_hat, q, v, inside) where inside = [qn <= v <= qp] is the
+    straight-through mask.  Pi = nearest integer, ties to even (np.rint)."""
+    v = quant_ratio(x, s, z, decide32)
+    q = np.rint(np.clip(v, qn, qp))
+    inside = (v >= qn) & (v <= qp)
+    s64 = np.asarray(s, dtype=np.float64)
+    z64 = np.asarray(z, dtype=np.float64)
+    if decide32:
+        s64 = s64.astype(np.float32).astype(np.float64)
+        z64 = z64.astype(np.float32).astype(np.float64)
+    x_hat = s64 * q + z64
+    return x_hat, q, v, inside
+
+
+def fake_quant_backward(d_xhat, q, v, inside, reduce_axes=None):
+    """Straight-through backward of x^ = s*(c + stopgrad(Pi(c) - c)) + z with
+    c = clamp(v, qn, qp):
+
+        d x^/d x = 1[inside]                      (Section 3.1.1)
+        d x^/d s = Pi(c) - v * 1[inside]          (learned step, Section 5.1.2)
+
+    reduce_axes: axes summed for ds (None = all: one scalar step)."""
+    d_xhat = np.asarray(d_xhat, dtype=np.float64)
+    dx = d_xhat * inside
+    ds_elem = d_xhat * (q - v * inside)
+    ds = ds_elem.sum() if reduce_axes is None else ds_elem.sum(axis=reduce_axes)
+    return dx, ds
+
+
+def weight_step_init(w, bits: int) -> np.ndarray:
+    """Per-output-channel initial step max_k |w[n,k]| / Qp, one fp32 division."""
+    _, qp = sym_range(bits)
+    a = np.abs(np.asarray(w, dtype=np.float32)).max(axis=1).astype(np.float64)
+    return (a / float(qp)).astype(np.float32).astype(np.float64)
+
+
+def quantize_weight(w, s_w, bits: int):
+    """Eq. 1 per output channel (row) of w[N,K].  Returns integer codes (int64),
+    w_hat, v and the straight-through mask.  The decision is taken in fp32."""
+    qn, qp = sym_range(bits)
+    w_hat, q, v, inside = fake_quant_forward(w, np.asarray(s_w)[:, None], qn, qp, 0.0, True)
+    return q.astype(np.int64), w_hat, v, inside
+
+
+# ----------------------------------------------------------------------------
+# transformer operators (BERT encoder layer, post-LayerNorm)
+# ----------------------------------------------------------------------------
+
+def gelu(u):
+    return 0.5 * u * (1.0 + _erf(u / math.sqrt(2.0)))
+
+
+def gelu_grad(u):
+    return 0.5 * (1.0 + _erf(u / math.sqrt(2.0))) + u * np.exp(-0.5 * u * u) / math.sqrt(2.0 * math.pi)
+
+
+def layernorm_forward(r, gamma, beta, eps):
+    mu = r.mean(axis=-1, keepdims=True)
+    var = ((r - mu) ** 2).mean(axis=-1, keepdims=True)
+    rstd = 1.0 / np.sqrt(var + eps)
+    xhat = (r - mu) * rstd
+    return xhat * gamma + beta, (xhat, rstd)
+
+
+def layernorm_backward(dy, gamma, cache):
+    xhat, rstd = cache
+    dgamma = (dy * xhat).sum(axis=0)
+    dbeta = dy.sum(axis=0)
+    dxhat = dy * gamma
+    dr = rstd * (dxhat - dxhat.mean(axis=-1, keepdims=True)
+                 - xhat * (dxhat * xhat).mean(axis=-1, keepdims=True))
+    return dr, dgamma, dbeta
+
+
+def softmax_rows(a):
+    m = a.max(axis=-1, keepdims=True)
+    e = np.exp(a - m)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def key_mask(seqlens, batch: int, seq: int) -> np.ndarray:
+    """Additive mask [batch,1,1,seq]: 0 for valid keys, -inf for padded keys."""
+    m = np.zeros((batch, 1, 1, seq), dtype=np.float64)
+    if seqlens is not None:
+        for b in range(batch):
+            m[b, 0, 0, int(seqlens[b]):] = -np.inf
+    return m
+
+
+def split_heads(t, batch, seq, n_heads):
+    d = t.shape[-1] // n_heads
+    return t.reshape(batch, seq, n_heads, d).transpose(0, 2, 1, 3)
+
+
+def merge_heads(t):
+    b, h, s, d = t.shape
+    return t.transpose(0, 2, 1, 3).reshape(b * s, h * d)
+
+
+# ----------------------------------------------------------------------------
+# parameters
+# ----------------------------------------------------------------------------
+
+LAYER_FIELDS = ("w_qkv", "b_qkv", "w_o", "b_o", "ln1_g", "ln1_b",
+                "w_1", "b_1", "w_2", "b_2", "ln2_g", "ln2_b",
+                "sw_qkv", "sw_o", "sw_1", "sw_2", "s_a", "z_a")
+TRAINABLE_FIELDS = LAYER_FIELDS[:-1]          # the offsets z_a are fixed
+TEACHER_FIELDS = LAYER_FIELDS[:12]
+
+
+def to_f64(layers: List[Dict[str, np.ndarray]]) -> List[Dict[str, np.ndarray]]:
+    return [{k: np.array(v, dtype=np.float64) for k, v in lp.items()} for lp in layers]
+
+
+# ----------------------------------------------------------------------------
+# one layer, forward and backward
+# ----------------------------------------------------------------------------
+
+class _AQ:
+    """One activation quantizer application: remembers what backward needs."""
+
+    def __init__(self, cfg: Config, lp, idx: int, enabled: bool):
+        self.enabled = enabled and cfg.a_bits > 0
+        self.idx = idx
+        if self.enabled:
+            self.qn, self.qp = (unsigned_range if ACT_Q_UNSIGNED[idx] else sym_range)(cfg.a_bits)
+            self.s = float(lp["s_a"][idx])
+            self.z = float(lp["z_a"][idx]) if ACT_Q_UNSIGNED[idx] else 0.0
+        self.decide32 = cfg.act_round is not None
+
+    def fwd(self, x):
+        if not self.enabled:
+            return x
+        xh, self.q, self.v, self.inside = fake_quant_forward(x, self.s, self.qn, self.qp, self.z, self.decide32)
+        return xh
+
+    def bwd(self, d_xhat):
+        if not self.enabled:
+            return d_xhat, 0.0
+        return fake_quant_backward(d_xhat, self.q, self.v, self.inside)
+
+
+class _WQ:
+    def __init__(self, cfg: Config, w, s_w, enabled: bool):
+        self.enabled = enabled and cfg.w_bits > 0
+        self.w = w
+        if self.enabled:
+            self.codes, self.w_hat, self.v, self.inside = quantize_weight(w, s_w, cfg.w_bits)
+        else:
+            self.w_hat = w
+
+    def bwd(self, d_what):
+        if not self.enabled:
+            return d_what, np.zeros(self.w.shape[0])
+        return fake_quant_backward(d_what, self.codes, self.v, self.inside, reduce_axes=1)
+
+
+def layer_forward(x, lp, cfg: Config, batch: int, seq: int, seqlens=None, quant: bool = True):
+    """One encoder layer on x[T,H] (T = batch*seq).  quant=False is the
+    full-precision teacher (every quantizer is the identity).  Returns the
+    layer output f[T,H] and a cache for layer_backward."""
+    H, nh, d = cfg.hidden, cfg.n_heads, cfg.head_dim
+    R = lambda t: round_store(t, cfg.act_round)
+    c = {"lp": lp, "batch": batch, "seq": seq, "x": x}
+    aq = [_AQ(cfg, lp, i, quant) for i in range(8)]
+    wq = {n: _WQ(cfg, lp[n], lp["s" + n] if quant and cfg.w_bits > 0 else None, quant) for n in WEIGHT_NAMES}
+    c["aq"], c["wq"] = aq, wq
+
+    # self-attention: three projections of one quantized input
+    xh = aq[AQ_X].fwd(x)
+    qkv = R(xh @ wq["w_qkv"].w_hat.T + lp["b_qkv"])
+    Q = split_heads(qkv[:, :H], batch, seq, nh)
+    K = split_heads(qkv[:, H:2 * H], batch, seq, nh)
+    V = split_heads(qkv[:, 2 * H:], batch, seq, nh)
+    Qh, Kh, Vh = aq[AQ_Q].fwd(Q), aq[AQ_K].fwd(K), aq[AQ_V].fwd(V)
+    A = Qh @ Kh.transpose(0, 1, 3, 2) / math.sqrt(d) + key_mask(seqlens, batch, seq)
+    P = softmax_rows(A)
+    Ph = aq[AQ_P].fwd(P)
+    C = R(merge_heads(Ph @ Vh))
+    Ch = aq[AQ_C].fwd(C)
+    o = R(Ch @ wq["w_o"].w_hat.T + lp["b_o"])
+    x1_pre, ln1 = layernorm_forward(x + o, lp["ln1_g"], lp["ln1_b"], cfg.ln_eps)
+    x1 = R(x1_pre)
+
+    # feed-forward network
+    x1h = aq[AQ_X1].fwd(x1)
+    u = R(x1h @ wq["w_1"].w_hat.T + lp["b_1"])
+    g = gelu(u)
+    gh = aq[AQ_G].fwd(g)
+    y = R(gh @ wq["w_2"].w_hat.T + lp["b_2"])
+    f_pre, ln2 = layernorm_forward(x1 + y, lp["ln2_g"], lp["ln2_b"], cfg.ln_eps)
+    f = R(f_pre)
+
+    c.update(xh=xh, Qh=Qh, Kh=Kh, Vh=Vh, P=P, Ph=Ph, Ch=Ch, ln1=ln1, x1h=x1h, u=u, gh=gh, ln2=ln2,
+             qkv=qkv, C=C, o=o, x1=x1, y=y, f=f)
+    return f, c
+
+
+def layer_backward(df, c, cfg: Config):
+    """Chain rule through layer_forward with every quantizer replaced by its
+    straight-through surrogate.  Returns (dx, grads) with grads keyed like the
+    layer's parameter dict (z_a gets no gradient: fixed offsets)."""
+    lp, aq, wq = c["lp"], c["aq"], c["wq"]
+    batch, seq = c["batch"], c["seq"]
+    H, nh, d = cfg.hidden, cfg.n_heads, cfg.head_dim
+    g = {}
+    ds_a = np.zeros(8)
+
+    # f = LN2(x1 + y)
+    dr2, g["ln2_g"], g["ln2_b"] = layernorm_backward(df, lp["ln2_g"], c["ln2"])
+    dx1 = dr2.copy()
+    dy = dr2
+    # y = gh W2^T + b2
+    g["b_2"] = dy.sum(axis=0)
+    g["w_2"], g["sw_2"] = wq["w_2"].bwd(dy.T @ c["gh"])
+    dgh = dy @ wq["w_2"].w_hat
+    dg, ds_a[AQ_G] = aq[AQ_G].bwd(dgh)
+    du = dg * gelu_grad(c["u"])
+    # u = x1h W1^T + b1
+    g["b_1"] = du.sum(axis=0)
+    g["w_1"], g["sw_1"] = wq["w_1"].bwd(du.T @ c["x1h"])
+    dx1h = du @ wq["w_1"].w_hat
+    t, ds_a[AQ_X1] = aq[AQ_X1].bwd(dx1h)
+    dx1 = dx1 + t
+    # x1 = LN1(x + o)
+    dr1, g["ln1_g"], g["ln1_b"] = layernorm_backward(dx1, lp["ln1_g"], c["ln1"])
+    dx = dr1.copy()
+    do = dr1
+    # o = Ch Wo^T + bo
+    g["b_o"] = do.sum(axis=0)
+    g["w_o"], g["sw_o"] = wq["w_o"].bwd(do.T @ c["Ch"])
+    dCh = do @ wq["w_o"].w_hat
+    dC, ds_a[AQ_C] = aq[AQ_C].bwd(dCh)
+    dC = split_heads(dC, batch, seq, nh)
+    # C = Ph Vh
+    dPh = dC @ c["Vh"].transpose(0, 1, 3, 2)
+    dVh = c["Ph"].transpose(0, 1, 3, 2) @ dC
+    dV, ds_a[AQ_V] = aq[AQ_V].bwd(dVh)
+    dP, ds_a[AQ_P] = aq[AQ_P].bwd(dPh)
+    # P = softmax(A)
+    P = c["P"]
+    dA = P * (dP - (dP * P).sum(axis=-1, keepdims=True))
+    # A = Qh Kh^T / sqrt(d)
+    dQh = dA @ c["Kh"] / math.sqrt(d)
+    dKh = dA.transpose(0, 1, 3, 2) @ c["Qh"] / math.sqrt(d)
+    dQ, ds_a[AQ_Q] = aq[AQ_Q].bwd(dQh)
+    dK, ds_a[AQ_K] = aq[AQ_K].bwd(dKh)
+    dqkv = np.concatenate([merge_heads(dQ), merge_heads(dK), merge_heads(dV)], axis=1)
+    # qkv = xh Wqkv^T + b
+    g["b_qkv"] = dqkv.sum(axis=0)
+    g["w_qkv"], g["sw_qkv"] = wq["w_qkv"].bwd(dqkv.T @ c["xh"])
+    dxh = dqkv @ wq["w_qkv"].w_hat
+    t, ds_a[AQ_X] = aq[AQ_X].bwd(dxh)
+    dx = dx + t
+    g["s_a"] = ds_a
+    return dx, g
+
+
+# ----------------------------------------------------------------------------
+# module: forward, loss (Eq. 3), backward, update (Algorithm 2)
+# ----------------------------------------------------------------------------
+
+def mix_inputs(x_fp, x_q, lam: float):
+    """Eq. 4: convex combination of the full-precision and quantized inputs."""
+    return lam * np.asarray(x_fp, dtype=np.float64) + (1.0 - lam) * np.asarray(x_q, dtype=np.float64)
+
+
+def module_forward(x, layers, cfg: Config, batch: int, seq: int, seqlens=None, quant: bool = True):
+    """Runs the module's layers in order on x[batch*seq, hidden].  Returns the
+    list of per-layer outputs f_l and the per-layer caches."""
+    outs, caches = [], []
+    h = np.asarray(x, dtype=np.float64).reshape(batch * seq, cfg.hidden)
+    for lp in layers:
+        h, c = layer_forward(h, lp, cfg, batch, seq, seqlens, quant)
+        outs.append(h)
+        caches.append(c)
+    return outs, caches
+
+
+def module_loss(f_q: List[np.ndarray], f_fp: List[np.ndarray], cfg: Config):
+    """Eq. 3.  Returns (total, per-layer list, per-layer gradient w.r.t. f^_l)."""
+    per, grads = [], []
+    for l, (a, b) in enumerate(zip(f_q, f_fp)):
+        if not (cfg.loss_layer_mask >> l) & 1:
+            per.append(0.0)
+            grads.append(np.zeros_like(a))
+            continue
+        diff = a - b
+        scale = 1.0 / diff.size if cfg.loss_mean else 1.0
+        per.append(float((diff * diff).sum() * scale))
+        grads.append(2.0 * diff * scale)
+    return float(sum(per)), per, grads
+
+
+def module_backward(loss_grads, caches, cfg: Config):
+    """Backward through the quantized module.  The gradient with respect to the
+    module input is dropped (Section 4.2: gradients stay local)."""
+    grads = [None] * len(caches)
+    dnext = np.zeros_like(loss_grads[-1])
+    for l in reversed(range(len(caches))):
+        df = dnext + loss_grads[l]
+        dnext, grads[l] = layer_backward(df, caches[l], cfg)
+    return grads
+
+
+def adamw_update(p, g, m, v, t: int, lr: float, cfg: Config, decay: bool):
+    """Decoupled-weight-decay Adam with bias correction; t is 1-based."""
+    m = cfg.beta1 * m + (1.0 - cfg.beta1) * g
+    v = cfg.beta2 * v + (1.0 - cfg.beta2) * g * g
+    mhat = m / (1.0 - cfg.beta1 ** t)
+    vhat = v / (1.0 - cfg.beta2 ** t)
+    wd = cfg.weight_decay if decay else 0.0
+    p = p - lr * (mhat / (np.sqrt(vhat) + cfg.adam_eps) + wd * p)
+    return p, m, v
+
+
+def linear_decay_lr(lr0: float, t: int, total: int) -> float:
+    """Linearly decayed rate, t = 0 .. total-1."""
+    return lr0 * (1.0 - t / float(total))
+
+
+def teacher_forcing_lambda(t: int, t0: int) -> float:
+    """Section 4.2.1: lambda_t = max(1 - t/T0, 0)."""
+    return max(1.0 - t / float(t0), 0.0)
+
+
+@dataclass
+class StepResult:
+    loss: float
+    per_layer_loss: List[float]
+    f_fp: List[np.ndarray]
+    f_q: List[np.ndarray]
+    grads: List[Dict[str, np.ndarray]]
+    caches: list = field(default_factory=list)
+
+
+def module_grads(x_fp, x_q, teacher, student, cfg: Config, batch, seq, seqlens=None) -> StepResult:
+    """Algorithm 2 up to the gradients: teacher forward on x_fp, student forward
+    on x_q, Eq. 3, straight-through backward."""
+    f_fp, _ = module_forward(x_fp, teacher, cfg, batch, seq, seqlens, quant=False)
+    f_q, caches = module_forward(x_q, student, cfg, batch, seq, seqlens, quant=True)
+    loss, per, lg = module_loss(f_q, f_fp, cfg)
+    grads = module_backward(lg, caches, cfg)
+    return StepResult(loss, per, f_fp, f_q, grads, caches)
+
+
+def module_step(x_fp, x_q, teacher, student, adam_m, adam_v, t: int, lr: float, cfg: Config,
+                batch, seq, seqlens=None) -> StepResult:
+    """One full step of Algorithm 2 (t is the 1-based update count).  student,
+    adam_m, adam_v are lists of per-layer dicts and are updated in place."""
+    res = module_grads(x_fp, x_q, teacher, student, cfg, batch, seq, seqlens)
+    for lp, g, m, v in zip(student, res.grads, adam_m, adam_v):
+        for name in TRAINABLE_FIELDS:
+            if name not in g:
+                continue
+            if name in STEP_NAMES and cfg.w_bits == 0:
+                continue
+            if name == "s_a" and cfg.a_bits == 0:
+                continue
+            lp[name], m[name], v[name] = adamw_update(lp[name], g[name], m[name], v[name], t, lr, cfg,
+                                                      decay=name in WEIGHT_NAMES)
+            if name in STEP_NAMES or name == "s_a":
+                lp[name] = np.maximum(lp[name], cfg.step_floor)
+    return res
+
+
+# ----------------------------------------------------------------------------
+# calibration of the activation quantizers (clip range from max |x|)
+# ----------------------------------------------------------------------------
+
+def calibrate(x_fp, teacher, cfg: Config, batch, seq, seqlens=None):
+    """Sets s_a (and z_a for the GELU output) of every layer from the
+    full-precision activations of one batch:
+      symmetric:  s = max|a| / Qp ;  softmax: z = 0, s = max(P) / (2^b - 1) ;
+      GELU out :  z = min(g), s = (max(g) - z) / (2^b - 1).
+    Divisions and the subtraction are fp32 operations on fp32-rounded extrema.
+    Returns a list of (s_a[8], z_a[8])."""
+    f32 = lambda t: np.float64(np.float32(t))
+    _, qp = sym_range(cfg.a_bits)
+    _, qu = unsigned_range(cfg.a_bits)
+    out = []
+    _, caches = module_forward(x_fp, teacher, cfg, batch, seq, seqlens, quant=False)
+    for c in caches:
+        H, nh = cfg.hidden, cfg.n_heads
+        qkv = c["qkv"]
+        tens = {AQ_X: c["x"], AQ_Q: qkv[:, :H], AQ_K: qkv[:, H:2 * H], AQ_V: qkv[:, 2 * H:],
+                AQ_C: c["C"], AQ_X1: c["x1"]}
+        s = np.zeros(8)
+        z = np.zeros(8)
+        for i, a in tens.items():
+            s[i] = f32(f32(np.abs(a).max()) / qp)
+        s[AQ_P] = f32(f32(c["P"].max()) / qu)
+        gact = gelu(c["u"])
+        z[AQ_G] = f32(gact.min())
+        s[AQ_G] = f32(f32(f32(gact.max()) - z[AQ_G]) / qu)
+        out.append((s, z))
+    return out
