@@ -1,0 +1,206 @@
+/*
+ * mrem.h -- C ABI of the MI355X (gfx950) implementation of one module-wise
+ * reconstruction (MREM) training step.
+ *
+ * Paper: "Towards Efficient Post-training Quantization of Pre-trained Language
+ * Models".  A module is a contiguous block of BERT encoder layers (Section 4.1).
+ * One step (Algorithm 2) runs the full-precision module and its fake-quantized
+ * copy forward, forms the module objective (Eq. 3), back-propagates through the
+ * quantized copy with straight-through gradients (Section 3.1.1) and updates the
+ * module's parameters and quantizer step sizes.
+ *
+ * General rules of this ABI
+ *  - Every pointer marked "device" is HIP device memory owned by the caller.  The
+ *    library never allocates, frees or retains device memory.  "host" pointers are
+ *    ordinary host memory.
+ *  - All work is enqueued on the caller's hipStream_t (passed as void*, NULL = the
+ *    default stream).  Calls return without synchronising.
+ *  - Arguments are validated on the host before anything is enqueued; a call that
+ *    returns an error has had no effect on device memory.
+ *  - Return value: MREM_OK or a negative mrem_status.  mrem_last_error() gives a
+ *    human-readable message for the last failing call on that context (or for
+ *    context-free calls, of the calling thread).
+ *  - Matrices are row-major and contiguous.  Activations are [batch*seq, hidden]
+ *    with the token index slowest.  Linear weights are [out_features, in_features].
+ *  - Device pointers must be 16-byte aligned.
+ *  - Calls on one context that overlap in time (different streams) race on the
+ *    workspace; give each concurrent caller its own workspace.
+ */
+#ifndef MREM_H_
+#define MREM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mrem_ctx mrem_ctx; /* opaque, host memory only */
+
+typedef enum {
+  MREM_OK = 0,
+  MREM_EINVAL = -1,     /* null pointer, bad enum, misaligned pointer */
+  MREM_ESHAPE = -2,     /* sizes the kernels do not support */
+  MREM_EWORKSPACE = -3, /* workspace smaller than mrem_workspace_bytes() */
+  MREM_EHIP = -5        /* a HIP runtime call failed */
+} mrem_status;
+
+typedef enum {
+  MREM_BF16 = 0, /* activations and matmul operands stored as bfloat16, fp32 accumulation */
+  MREM_FP32 = 1  /* check mode: everything fp32 */
+} mrem_dtype;
+
+/* Shape and hyper-parameters of one module.  (Section 4.1 for the partition into
+ * modules; Section 3.1 for the bit-widths; Section 5.1.2 for the optimiser.) */
+typedef struct {
+  int32_t n_layers;  /* encoder layers in the module, 1..32 */
+  int32_t hidden;    /* model width H, multiple of 8 */
+  int32_t n_heads;   /* attention heads, H / n_heads in {32, 64, 128} */
+  int32_t ffn;       /* feed-forward width F, multiple of 8 */
+  int32_t max_seq;   /* largest seq passed to any call, <= 512 */
+  int32_t max_batch; /* largest batch passed to any call */
+  int32_t w_bits;    /* 2..8; 0 = weight quantizers off */
+  int32_t a_bits;    /* 2..8; 0 = activation quantizers off */
+  int32_t act_dtype; /* mrem_dtype */
+  uint32_t loss_layer_mask; /* bit l set: layer l enters the sum of Eq. 3 */
+  int32_t loss_mean; /* 1: each layer's term is the mean of squared differences; 0: the raw sum */
+  float ln_eps;      /* LayerNorm epsilon (BERT: 1e-12) */
+  float beta1, beta2, adam_eps, weight_decay; /* AdamW; decay applies to the four linear weights only */
+  float step_floor;  /* step sizes are kept >= this after every update */
+} mrem_config;
+
+/* Fields of one layer inside the flat fp32 parameter vector, in storage order;
+ * layer l starts at l * (sum of all field sizes).  The teacher vector, the Adam
+ * moment vectors and the gradient vector all use this same layout (the teacher's
+ * step-size fields are ignored, so a copy of the initial student vector is a
+ * valid teacher vector). */
+typedef enum {
+  MREM_F_W_QKV = 0, /* [3H,H] rows: query, key, value projections stacked */
+  MREM_F_W_O,       /* [H,H]  attention output projection */
+  MREM_F_W_1,       /* [F,H]  first feed-forward projection */
+  MREM_F_W_2,       /* [H,F]  second feed-forward projection */
+  MREM_F_B_QKV,     /* [3H] */
+  MREM_F_B_O,       /* [H] */
+  MREM_F_LN1_G,     /* [H] LayerNorm after attention: gain */
+  MREM_F_LN1_B,     /* [H] shift */
+  MREM_F_B_1,       /* [F] */
+  MREM_F_B_2,       /* [H] */
+  MREM_F_LN2_G,     /* [H] LayerNorm after the feed-forward network */
+  MREM_F_LN2_B,     /* [H] */
+  MREM_F_SW_QKV,    /* [3H] weight step sizes, one per output channel */
+  MREM_F_SW_O,      /* [H] */
+  MREM_F_SW_1,      /* [F] */
+  MREM_F_SW_2,      /* [H] */
+  MREM_F_S_A,       /* [8] activation step sizes: layer input, Q, K, softmax P, V, context, FFN input, GELU output */
+  MREM_F_Z_A,       /* [8] fixed offsets of the two unsigned quantizers (P: 0, GELU output: its minimum); others 0 */
+  MREM_F_COUNT
+} mrem_field;
+
+mrem_status mrem_create(const mrem_config* cfg /*host*/, mrem_ctx** out /*host*/);
+void mrem_destroy(mrem_ctx* ctx);
+const char* mrem_last_error(const mrem_ctx* ctx /* may be NULL */);
+
+/* Layout queries (host only, no GPU work). Offsets and counts are in floats. */
+int64_t mrem_param_count(const mrem_ctx* ctx);   /* student vector length */
+int64_t mrem_teacher_count(const mrem_ctx* ctx); /* teacher vector length */
+int64_t mrem_param_offset(const mrem_ctx* ctx, int32_t layer, int32_t field);
+int64_t mrem_param_size(const mrem_ctx* ctx, int32_t field);
+size_t mrem_workspace_bytes(const mrem_ctx* ctx, int32_t batch, int32_t seq);
+/* bytes of the teacher cache written by mrem_teacher_prepare */
+size_t mrem_teacher_cache_bytes(const mrem_ctx* ctx);
+
+/*
+ * mrem_quantize -- the uniform quantizer of Section 3.1, Eq. 1, per output channel:
+ *   codes[n,k] = nearest_even( clamp( w[n,k] / scale[n], -Qp, Qp ) ),  Qp = 2^(bits-1) - 1,
+ * with the quotient formed as one IEEE fp32 division.
+ *   w      device fp32 [N,K]      (in)
+ *   scale  device fp32 [N]        (in; out if init_scale != 0)
+ *   codes  device int8 [N,K]      (out)
+ * init_scale != 0 first sets scale[n] = max_k |w[n,k]| / Qp (one fp32 division; a
+ * row of zeros gets the smallest positive normal float).  bits in 2..8.
+ * Errors: MREM_EINVAL (null/misaligned pointer, bits), MREM_ESHAPE (N or K < 1).
+ */
+mrem_status mrem_quantize(const float* w, int64_t N, int64_t K, int32_t bits, int32_t init_scale,
+                          float* scale, int8_t* codes, void* hip_stream);
+
+/*
+ * mrem_module_init_steps -- initial weight step sizes of every layer of a student
+ * vector: for each of the four linear weights, step[n] = max_k |w[n,k]| / Qp with
+ * Qp = 2^(w_bits-1) - 1 (so that the largest weight of a channel maps to the last
+ * level of the integer set of Eq. 1).  Writes only the four SW fields of params.
+ * Error if w_bits = 0.
+ */
+mrem_status mrem_module_init_steps(mrem_ctx* ctx, float* params, void* hip_stream);
+
+/*
+ * mrem_teacher_prepare -- converts the teacher's fp32 parameter vector into the
+ * operand format of the forward kernels (the full-precision module of Algorithm 2
+ * is frozen, so this runs once).  teacher: device fp32 [mrem_teacher_count].
+ * cache: device, mrem_teacher_cache_bytes() bytes, written.
+ */
+mrem_status mrem_teacher_prepare(mrem_ctx* ctx, const float* teacher, void* cache, void* hip_stream);
+
+/*
+ * mrem_module_calibrate -- initial clipping ranges of the activation quantizers
+ * from the full-precision module's activations on one batch (Section 5.1.2 uses a
+ * learned-step quantizer whose step is initialised from the data): for the six
+ * symmetric quantizers s = max|a| / Qp, for the softmax probabilities z = 0 and
+ * s = max(P) / (2^b - 1), for the GELU output z = min(g), s = (max(g) - z) / (2^b - 1).
+ * Writes the S_A and Z_A fields of every layer of params; nothing else is touched.
+ *   x_fp     device act_dtype [batch, seq, hidden]
+ *   seqlens  device int32 [batch] valid keys per sequence, or NULL (no padding)
+ */
+mrem_status mrem_module_calibrate(mrem_ctx* ctx, float* params, const float* teacher, const void* teacher_cache,
+                                  const void* x_fp, const int32_t* seqlens, int32_t batch, int32_t seq,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * mrem_module_forward -- the two forward passes of Algorithm 2: the full-precision
+ * module on x_fp and the quantized module on x_q (Section 3.1: both operands of
+ * every matrix multiplication are quantized; LayerNorm, residuals and biases are not).
+ *   params         device fp32 [mrem_param_count]  (in)
+ *   teacher        device fp32 [mrem_teacher_count] (in: biases and LayerNorm parameters)
+ *   teacher_cache  device, from mrem_teacher_prepare (in: matrices)
+ *   x_fp, x_q      device act_dtype [batch, seq, hidden]; may alias
+ *   seqlens        device int32 [batch] or NULL
+ *   per_layer_fp, per_layer_q  device act_dtype [n_layers, batch, seq, hidden] (out):
+ *                  the layer outputs f_l and f^_l of Eq. 3; the last slice is the
+ *                  module output handed to the next module.  Either may be NULL to
+ *                  skip that pass.
+ */
+mrem_status mrem_module_forward(mrem_ctx* ctx, const float* params, const float* teacher, const void* teacher_cache,
+                                const void* x_fp, const void* x_q, const int32_t* seqlens, int32_t batch,
+                                int32_t seq, void* per_layer_fp, void* per_layer_q, void* workspace,
+                                size_t workspace_bytes, void* hip_stream);
+
+/*
+ * mrem_module_step -- one full iteration of Algorithm 2 (without its input mixing):
+ * both forward passes, the loss of Eq. 3, the straight-through backward pass
+ * confined to the module (Section 4.2), and one AdamW update with rate lr of every
+ * trainable parameter and every step size.
+ *   params, adam_m, adam_v   device fp32 [mrem_param_count]  (in/out)
+ *   step_index               1-based count of this update (bias correction)
+ *   lr                       learning rate of this step (caller applies the linear decay)
+ *   loss_out                 device fp32 [1 + n_layers] (out): total, then per layer
+ *   per_layer_fp, per_layer_q  device act_dtype [n_layers, batch, seq, hidden] (out, required)
+ *   grads_out                device fp32 [mrem_param_count] or NULL (out): the gradients
+ *                            that were applied (Z_A slots are written as 0)
+ */
+mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* adam_m, float* adam_v, int64_t step_index,
+                             float lr, const float* teacher, const void* teacher_cache, const void* x_fp,
+                             const void* x_q, const int32_t* seqlens, int32_t batch, int32_t seq,
+                             float* loss_out, void* per_layer_fp, void* per_layer_q, float* grads_out,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * mrem_mix_inputs -- annealed teacher forcing, Eq. 4: out = lambda * x_fp + (1 - lambda) * x_q,
+ * elementwise over n values of act_dtype (device). out may alias x_q.
+ */
+mrem_status mrem_mix_inputs(mrem_ctx* ctx, const void* x_fp, const void* x_q, float lambda, void* out, int64_t n,
+                            void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MREM_H_ */

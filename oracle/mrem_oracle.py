@@ -45,6 +45,9 @@ are the ones the HIP path implements):
   This is what "bf16 activations" means in the workloads: the stored tensors
   (qkv, context, projections, LayerNorm outputs, FFN pre-activation) hold
   bf16 values, and the quantizer decisions are taken on those stored values.
+  Softmax probabilities and the GELU output are not stored when their
+  quantizer is on (the codes are); when it is off (the full-precision module)
+  they are matrix-product operands and therefore stored tensors too.
 
 parity unpinned: none of the functions below -- every one is pinned in
 tests/test_oracle_pins.py (hand-computed fixtures under tests/golden/, closed
@@ -299,8 +302,12 @@ class _AQ:
         return xh
 
     def bwd(self, d_xhat):
+        """Also records ds_abs = sum |terms of ds|, the natural scale for judging a
+        computed ds (the sum itself cancels heavily)."""
+        self.ds_abs = 0.0
         if not self.enabled:
             return d_xhat, 0.0
+        self.ds_abs = float(np.abs(np.asarray(d_xhat) * (self.q - self.v * self.inside)).sum())
         return fake_quant_backward(d_xhat, self.q, self.v, self.inside)
 
 
@@ -339,7 +346,8 @@ def layer_forward(x, lp, cfg: Config, batch: int, seq: int, seqlens=None, quant:
     Qh, Kh, Vh = aq[AQ_Q].fwd(Q), aq[AQ_K].fwd(K), aq[AQ_V].fwd(V)
     A = Qh @ Kh.transpose(0, 1, 3, 2) / math.sqrt(d) + key_mask(seqlens, batch, seq)
     P = softmax_rows(A)
-    Ph = aq[AQ_P].fwd(P)
+    # an operand of a matrix product is either quantizer codes or a stored tensor
+    Ph = aq[AQ_P].fwd(P) if aq[AQ_P].enabled else R(P)
     C = R(merge_heads(Ph @ Vh))
     Ch = aq[AQ_C].fwd(C)
     o = R(Ch @ wq["w_o"].w_hat.T + lp["b_o"])
@@ -350,7 +358,7 @@ def layer_forward(x, lp, cfg: Config, batch: int, seq: int, seqlens=None, quant:
     x1h = aq[AQ_X1].fwd(x1)
     u = R(x1h @ wq["w_1"].w_hat.T + lp["b_1"])
     g = gelu(u)
-    gh = aq[AQ_G].fwd(g)
+    gh = aq[AQ_G].fwd(g) if aq[AQ_G].enabled else R(g)
     y = R(gh @ wq["w_2"].w_hat.T + lp["b_2"])
     f_pre, ln2 = layernorm_forward(x1 + y, lp["ln2_g"], lp["ln2_b"], cfg.ln_eps)
     f = R(f_pre)
@@ -417,6 +425,7 @@ def layer_backward(df, c, cfg: Config):
     t, ds_a[AQ_X] = aq[AQ_X].bwd(dxh)
     dx = dx + t
     g["s_a"] = ds_a
+    g["s_a_abs"] = np.array([a.ds_abs for a in aq])     # diagnostic, not a gradient
     return dx, g
 
 

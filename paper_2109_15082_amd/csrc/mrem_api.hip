@@ -1,0 +1,605 @@
+// C ABI of the MREM module step (Algorithm 2) and the host-side orchestration of
+// its kernels.  Host code only enqueues kernels on the caller's stream; all
+// arithmetic of the method runs on the device.
+#include "../../include/mrem.h"
+#include "mrem_kernels.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+
+using namespace mrem;
+
+static thread_local std::string g_err;
+
+struct mrem_ctx {
+  mrem_config cfg;
+  int dt, L, H, F, nh, d;
+  int64_t foff[MREM_F_COUNT], fsize[MREM_F_COUNT];
+  int64_t layer_stride;
+  int64_t tc_off[4], tc_layer_stride;  // teacher cache, in elements
+  int wN[4], wK[4];                    // the four linear layers [N,K]
+  std::string err;
+};
+
+static mrem_status fail(const mrem_ctx* ctx, mrem_status st, const std::string& msg) {
+  g_err = msg;
+  if (ctx) const_cast<mrem_ctx*>(ctx)->err = msg;
+  return st;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+extern "C" const char* mrem_last_error(const mrem_ctx* ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+extern "C" mrem_status mrem_create(const mrem_config* cfg, mrem_ctx** out) {
+  if (!cfg || !out) return fail(nullptr, MREM_EINVAL, "mrem_create: null argument");
+  const mrem_config& c = *cfg;
+  if (c.n_layers < 1 || c.n_layers > 32) return fail(nullptr, MREM_ESHAPE, "n_layers must be in 1..32");
+  if (c.hidden < 8 || c.hidden % 8 || c.hidden > 2048) return fail(nullptr, MREM_ESHAPE, "hidden must be a multiple of 8, <= 2048");
+  if (c.ffn < 8 || c.ffn % 8) return fail(nullptr, MREM_ESHAPE, "ffn must be a multiple of 8");
+  if (c.n_heads < 1 || c.hidden % c.n_heads) return fail(nullptr, MREM_ESHAPE, "hidden must be divisible by n_heads");
+  const int d = c.hidden / c.n_heads;
+  if (d % 8 || d > 128) return fail(nullptr, MREM_ESHAPE, "head dimension must be a multiple of 8, <= 128");
+  if (c.max_seq < 1 || c.max_seq > 512) return fail(nullptr, MREM_ESHAPE, "max_seq must be in 1..512");
+  if (c.max_batch < 1) return fail(nullptr, MREM_ESHAPE, "max_batch must be >= 1");
+  if (!(c.w_bits == 0 || (c.w_bits >= 2 && c.w_bits <= 8))) return fail(nullptr, MREM_EINVAL, "w_bits must be 0 or 2..8");
+  if (!(c.a_bits == 0 || (c.a_bits >= 2 && c.a_bits <= 8))) return fail(nullptr, MREM_EINVAL, "a_bits must be 0 or 2..8");
+  if (c.act_dtype != MREM_BF16 && c.act_dtype != MREM_FP32) return fail(nullptr, MREM_EINVAL, "act_dtype must be MREM_BF16 or MREM_FP32");
+  mrem_ctx* x = new mrem_ctx();
+  x->cfg = c;
+  x->dt = c.act_dtype == MREM_BF16 ? DT_BF16 : DT_F32;
+  x->L = c.n_layers; x->H = c.hidden; x->F = c.ffn; x->nh = c.n_heads; x->d = d;
+  const int64_t H = x->H, F = x->F;
+  const int64_t sizes[MREM_F_COUNT] = {3 * H * H, H * H, F * H, H * F, 3 * H, H, H, H, F, H, H, H, 3 * H, H, F, H, 8, 8};
+  int64_t off = 0;
+  for (int f = 0; f < MREM_F_COUNT; ++f) { x->foff[f] = off; x->fsize[f] = sizes[f]; off += sizes[f]; }
+  x->layer_stride = off;
+  x->wN[0] = 3 * H; x->wK[0] = H; x->wN[1] = H; x->wK[1] = H; x->wN[2] = F; x->wK[2] = H; x->wN[3] = H; x->wK[3] = F;
+  int64_t t = 0;
+  for (int i = 0; i < 4; ++i) { x->tc_off[i] = t; t += (int64_t)x->wN[i] * x->wK[i]; }
+  x->tc_layer_stride = t;
+  *out = x;
+  return MREM_OK;
+}
+
+extern "C" void mrem_destroy(mrem_ctx* ctx) { delete ctx; }
+extern "C" int64_t mrem_param_count(const mrem_ctx* ctx) { return ctx ? ctx->layer_stride * ctx->L : -1; }
+extern "C" int64_t mrem_teacher_count(const mrem_ctx* ctx) { return mrem_param_count(ctx); }
+extern "C" int64_t mrem_param_offset(const mrem_ctx* ctx, int32_t layer, int32_t field) {
+  if (!ctx || layer < 0 || layer >= ctx->L || field < 0 || field >= MREM_F_COUNT) return -1;
+  return ctx->layer_stride * layer + ctx->foff[field];
+}
+extern "C" int64_t mrem_param_size(const mrem_ctx* ctx, int32_t field) {
+  if (!ctx || field < 0 || field >= MREM_F_COUNT) return -1;
+  return ctx->fsize[field];
+}
+extern "C" size_t mrem_teacher_cache_bytes(const mrem_ctx* ctx) {
+  return ctx ? (size_t)(ctx->tc_layer_stride * ctx->L) * dt_size(ctx->dt) : 0;
+}
+
+// ------------------------------------------------------------------------------
+// workspace plan
+// ------------------------------------------------------------------------------
+namespace {
+
+struct Bump {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    const size_t o = off;
+    off += (bytes + 255) & ~size_t(255);
+    return o;
+  }
+};
+
+struct LayerWs {
+  size_t wcodes[4], what_t[4], zcorr[4];
+  size_t xcodes, qkv, qkvcodes, ctx, ctxcodes, o, x1, x1codes, u, gcodes, y, mu1, rstd1, mu2, rstd2;
+};
+
+struct Plan {
+  LayerWs lw[32];
+  // teacher scratch
+  size_t t_qkv, t_ctx, t_o, t_x1, t_g, t_y, t_mu, t_rstd;
+  // backward scratch
+  size_t lg, dr2, dr1, dxh, dx1h, dch, dc, dgh, du, dqkvh, dqkv, tA, tB, s_da, s_ph, ds_rows, partials, grads, pmax;
+  size_t total;
+};
+
+Plan make_plan(const mrem_ctx* c, int B, int S) {
+  Plan p;
+  Bump b;
+  const size_t T = (size_t)B * S, H = c->H, F = c->F, es = dt_size(c->dt);
+  for (int l = 0; l < c->L; ++l) {
+    LayerWs& w = p.lw[l];
+    for (int i = 0; i < 4; ++i) {
+      const size_t n = (size_t)c->wN[i] * c->wK[i];
+      w.wcodes[i] = b.take(n * es);
+      w.what_t[i] = b.take(n * es);
+      w.zcorr[i] = b.take((size_t)c->wN[i] * 4);
+    }
+    w.xcodes = b.take(T * H * es); w.qkv = b.take(T * 3 * H * es); w.qkvcodes = b.take(T * 3 * H * es);
+    w.ctx = b.take(T * H * es); w.ctxcodes = b.take(T * H * es); w.o = b.take(T * H * es);
+    w.x1 = b.take(T * H * es); w.x1codes = b.take(T * H * es); w.u = b.take(T * F * es); w.gcodes = b.take(T * F * es);
+    w.y = b.take(T * H * es);
+    w.mu1 = b.take(T * 4); w.rstd1 = b.take(T * 4); w.mu2 = b.take(T * 4); w.rstd2 = b.take(T * 4);
+  }
+  p.t_qkv = b.take(T * 3 * H * es); p.t_ctx = b.take(T * H * es); p.t_o = b.take(T * H * es); p.t_x1 = b.take(T * H * es);
+  p.t_g = b.take(T * F * es); p.t_y = b.take(T * H * es); p.t_mu = b.take(T * 4); p.t_rstd = b.take(T * 4);
+  p.lg = b.take(T * H * es); p.dr2 = b.take(T * H * es); p.dr1 = b.take(T * H * es); p.dxh = b.take(T * H * es);
+  p.dx1h = b.take(T * H * es); p.dch = b.take(T * H * es); p.dc = b.take(T * H * es);
+  p.dgh = b.take(T * F * es); p.du = b.take(T * F * es); p.dqkvh = b.take(T * 3 * H * es); p.dqkv = b.take(T * 3 * H * es);
+  const size_t widest = (3 * H > F ? 3 * H : F);
+  p.tA = b.take(widest * T * es); p.tB = b.take(widest * T * es);
+  const size_t pp = (size_t)B * c->nh * S * S;
+  p.s_da = b.take(pp * 4); p.s_ph = b.take(pp * 4); p.ds_rows = b.take((size_t)B * c->nh * S * 4);
+  p.pmax = b.take((size_t)B * c->nh * S * 4);
+  size_t np = (size_t)ln_bwd_parts((int)T) * (3 * H + 1);
+  const size_t np2 = ((T + 63) / 64) * widest;
+  if (np2 > np) np = np2;
+  if (np < 2048 * 3) np = 2048 * 3;
+  p.partials = b.take(np * 4);
+  p.grads = b.take((size_t)mrem_param_count(c) * 4);
+  p.total = b.off;
+  return p;
+}
+
+struct Run {
+  const mrem_ctx* c;
+  Plan p;
+  char* ws;
+  hipStream_t st;
+  int B, S, T;
+  const int32_t* seqlens;
+  template <class X = void> X* at(size_t off) const { return reinterpret_cast<X*>(ws + off); }
+};
+
+QArg make_q(const mrem_ctx* c, const float* params, int layer, int idx) {
+  QArg q;
+  q.on = c->cfg.a_bits > 0;
+  if (!q.on) return q;
+  const float* base = params + c->layer_stride * layer;
+  q.s = base + c->foff[MREM_F_S_A] + idx;
+  const bool uns = (idx == 3 || idx == 7);
+  q.z = (idx == 7) ? base + c->foff[MREM_F_Z_A] + idx : nullptr;
+  if (uns) { q.qn = 0.f; q.qp = (float)((1 << c->cfg.a_bits) - 1); }
+  else { q.qp = (float)((1 << (c->cfg.a_bits - 1)) - 1); q.qn = -q.qp; }
+  return q;
+}
+
+AttnQ make_attn_q(const mrem_ctx* c, const float* params, int layer, bool quant) {
+  AttnQ a;
+  if (!quant) return a;
+  a.q = make_q(c, params, layer, 1); a.k = make_q(c, params, layer, 2); a.p = make_q(c, params, layer, 3);
+  a.v = make_q(c, params, layer, 4); a.c = make_q(c, params, layer, 5);
+  return a;
+}
+
+const int kWField[4] = {MREM_F_W_QKV, MREM_F_W_O, MREM_F_W_1, MREM_F_W_2};
+const int kBField[4] = {MREM_F_B_QKV, MREM_F_B_O, MREM_F_B_1, MREM_F_B_2};
+const int kSField[4] = {MREM_F_SW_QKV, MREM_F_SW_O, MREM_F_SW_1, MREM_F_SW_2};
+const int kInQuant[4] = {0, 5, 6, 7};  // activation quantizer feeding each linear layer
+
+// quantized linear layer i of layer l: out = codes_in * wcodes^T with the steps in the epilogue
+void student_linear(const Run& r, const float* params, int l, int i, const void* in_codes, void* out) {
+  const mrem_ctx* c = r.c;
+  const float* base = params + c->layer_stride * l;
+  Epilogue e;
+  const QArg q = make_q(c, params, l, kInQuant[i]);
+  if (q.on) e.alpha = q.s;
+  if (c->cfg.w_bits > 0) e.col_scale = base + c->foff[kSField[i]];
+  if (q.on && q.z) { e.beta = q.z; e.col_vec = r.at<float>(r.p.lw[l].zcorr[i]); }
+  e.bias = base + c->foff[kBField[i]];
+  gemm_nt(c->dt, in_codes, c->wK[i], r.at(r.p.lw[l].wcodes[i]), c->wK[i], out, c->wN[i], r.T, c->wN[i], c->wK[i], e, r.st);
+}
+
+void prepare_weights(const Run& r, const float* params) {
+  const mrem_ctx* c = r.c;
+  for (int l = 0; l < c->L; ++l) {
+    const float* base = params + c->layer_stride * l;
+    for (int i = 0; i < 4; ++i)
+      weight_prepare(c->dt, base + c->foff[kWField[i]], base + c->foff[kSField[i]], c->wN[i], c->wK[i], c->cfg.w_bits,
+                     r.at(r.p.lw[l].wcodes[i]), r.at(r.p.lw[l].what_t[i]), r.at<float>(r.p.lw[l].zcorr[i]), r.st);
+  }
+}
+
+void student_forward(const Run& r, const float* params, const void* x_q, void* per_layer_q) {
+  const mrem_ctx* c = r.c;
+  const size_t es = dt_size(c->dt);
+  const int H = c->H, F = c->F, T = r.T;
+  const size_t slice = (size_t)T * H * es;
+  for (int l = 0; l < c->L; ++l) {
+    const LayerWs& w = r.p.lw[l];
+    const float* base = params + c->layer_stride * l;
+    const void* x = l == 0 ? x_q : (const char*)per_layer_q + slice * (l - 1);
+    void* f = (char*)per_layer_q + slice * l;
+    act_quantize(c->dt, x, r.at(w.xcodes), (int64_t)T * H, make_q(c, params, l, 0), r.st);
+    student_linear(r, params, l, 0, r.at(w.xcodes), r.at(w.qkv));
+    const AttnQ aq = make_attn_q(c, params, l, true);
+    qkv_quantize(c->dt, r.at(w.qkv), r.at(w.qkvcodes), T, H, aq.q, aq.k, aq.v, r.st);
+    attn_fwd(c->dt, r.at(w.qkvcodes), r.at(w.ctx), r.at(w.ctxcodes), aq, r.seqlens, r.B, r.S, c->nh, c->d, nullptr, r.st);
+    student_linear(r, params, l, 1, r.at(w.ctxcodes), r.at(w.o));
+    ln_fwd(c->dt, x, r.at(w.o), base + c->foff[MREM_F_LN1_G], base + c->foff[MREM_F_LN1_B], r.at(w.x1), r.at(w.x1codes),
+           make_q(c, params, l, 6), r.at<float>(w.mu1), r.at<float>(w.rstd1), T, H, c->cfg.ln_eps, r.st);
+    student_linear(r, params, l, 2, r.at(w.x1codes), r.at(w.u));
+    gelu_quantize(c->dt, r.at(w.u), r.at(w.gcodes), (int64_t)T * F, make_q(c, params, l, 7), r.st);
+    student_linear(r, params, l, 3, r.at(w.gcodes), r.at(w.y));
+    ln_fwd(c->dt, r.at(w.x1), r.at(w.y), base + c->foff[MREM_F_LN2_G], base + c->foff[MREM_F_LN2_B], f, nullptr, QArg(),
+           r.at<float>(w.mu2), r.at<float>(w.rstd2), T, H, c->cfg.ln_eps, r.st);
+  }
+}
+
+// Full-precision module.  With calib_params != null the clipping ranges of the
+// eight activation quantizers of every layer are derived on the way.
+void teacher_forward(const Run& r, const float* teacher, const void* cache, const void* x_fp, void* per_layer_fp, float* calib_params) {
+  const mrem_ctx* c = r.c;
+  const size_t es = dt_size(c->dt);
+  const int H = c->H, F = c->F, T = r.T;
+  const size_t slice = (size_t)T * H * es;
+  const float qp_s = (float)((1 << (c->cfg.a_bits > 0 ? c->cfg.a_bits - 1 : 1)) - 1);
+  const float qp_u = (float)((1 << (c->cfg.a_bits > 0 ? c->cfg.a_bits : 1)) - 1);
+  float* parts = r.at<float>(r.p.partials);
+  auto calib = [&](int l, int idx, const void* a, int dt, int rows, int cols, int ld, int gelu, int mode) {
+    float* base = calib_params + c->layer_stride * l;
+    const int n = absminmax(dt, a, rows, cols, ld, gelu, parts, r.st);
+    calib_finalize(parts, n, mode, mode == 0 ? qp_s : qp_u, base + c->foff[MREM_F_S_A] + idx, base + c->foff[MREM_F_Z_A] + idx, r.st);
+  };
+  for (int l = 0; l < c->L; ++l) {
+    const float* base = teacher + c->layer_stride * l;
+    const char* wc = (const char*)cache + (size_t)c->tc_layer_stride * l * es;
+    auto W = [&](int i) { return (const void*)(wc + (size_t)c->tc_off[i] * es); };
+    const void* x = l == 0 ? x_fp : (const char*)per_layer_fp + slice * (l - 1);
+    void* f = (char*)per_layer_fp + slice * l;
+    Epilogue e;
+    if (calib_params) calib(l, 0, x, c->dt, T, H, H, 0, 0);
+    e.bias = base + c->foff[MREM_F_B_QKV];
+    gemm_nt(c->dt, x, H, W(0), H, r.at(r.p.t_qkv), 3 * H, T, 3 * H, H, e, r.st);
+    if (calib_params) {
+      const char* q = r.at<char>(r.p.t_qkv);
+      calib(l, 1, q, c->dt, T, H, 3 * H, 0, 0);
+      calib(l, 2, q + (size_t)H * es, c->dt, T, H, 3 * H, 0, 0);
+      calib(l, 4, q + (size_t)2 * H * es, c->dt, T, H, 3 * H, 0, 0);
+    }
+    attn_fwd(c->dt, r.at(r.p.t_qkv), r.at(r.p.t_ctx), nullptr, AttnQ(), r.seqlens, r.B, r.S, c->nh, c->d,
+             calib_params ? r.at<float>(r.p.pmax) : nullptr, r.st);
+    if (calib_params) {
+      calib(l, 3, r.at(r.p.pmax), DT_F32, 1, r.B * c->nh * r.S, r.B * c->nh * r.S, 0, 1);
+      calib(l, 5, r.at(r.p.t_ctx), c->dt, T, H, H, 0, 0);
+    }
+    e.bias = base + c->foff[MREM_F_B_O];
+    gemm_nt(c->dt, r.at(r.p.t_ctx), H, W(1), H, r.at(r.p.t_o), H, T, H, H, e, r.st);
+    ln_fwd(c->dt, x, r.at(r.p.t_o), base + c->foff[MREM_F_LN1_G], base + c->foff[MREM_F_LN1_B], r.at(r.p.t_x1), nullptr, QArg(),
+           r.at<float>(r.p.t_mu), r.at<float>(r.p.t_rstd), T, H, c->cfg.ln_eps, r.st);
+    if (calib_params) calib(l, 6, r.at(r.p.t_x1), c->dt, T, H, H, 0, 0);
+    e.bias = base + c->foff[MREM_F_B_1];
+    if (calib_params) {
+      // pre-activation first, so that the range of gelu(u) can be measured on unrounded values
+      gemm_nt(c->dt, r.at(r.p.t_x1), H, W(2), H, r.at(r.p.t_g), F, T, F, H, e, r.st);
+      calib(l, 7, r.at(r.p.t_g), c->dt, T, F, F, 1, 2);
+      gelu_quantize(c->dt, r.at(r.p.t_g), r.at(r.p.t_g), (int64_t)T * F, QArg(), r.st);
+    } else {
+      e.gelu = 1;
+      gemm_nt(c->dt, r.at(r.p.t_x1), H, W(2), H, r.at(r.p.t_g), F, T, F, H, e, r.st);
+      e.gelu = 0;
+    }
+    e.bias = base + c->foff[MREM_F_B_2];
+    gemm_nt(c->dt, r.at(r.p.t_g), F, W(3), F, r.at(r.p.t_y), H, T, H, F, e, r.st);
+    ln_fwd(c->dt, r.at(r.p.t_x1), r.at(r.p.t_y), base + c->foff[MREM_F_LN2_G], base + c->foff[MREM_F_LN2_B], f, nullptr, QArg(),
+           r.at<float>(r.p.t_mu), r.at<float>(r.p.t_rstd), T, H, c->cfg.ln_eps, r.st);
+  }
+}
+
+// weight-gradient product of linear layer i: grads[w] = (dY^T * codes_in) * s_a (+ z * db)
+void wgrad(const Run& r, const float* params, float* grads, int l, int i, const void* dyT, const void* codesT) {
+  const mrem_ctx* c = r.c;
+  float* g = grads + c->layer_stride * l;
+  Epilogue e;
+  const QArg q = make_q(c, params, l, kInQuant[i]);
+  if (q.on) e.alpha = q.s;
+  if (q.on && q.z) { e.beta = q.z; e.row_vec = g + c->foff[kBField[i]]; }
+  e.out_f32 = 1;
+  gemm_nt(c->dt, dyT, r.T, codesT, r.T, g + c->foff[kWField[i]], c->wK[i], c->wN[i], c->wK[i], r.T, e, r.st);
+}
+// input-gradient product: d(in^) = dY * W^  via the transposed dequantized copy
+void dgrad(const Run& r, int l, int i, const void* dy, void* out) {
+  const mrem_ctx* c = r.c;
+  Epilogue e;
+  gemm_nt(c->dt, dy, c->wN[i], r.at(r.p.lw[l].what_t[i]), c->wN[i], out, c->wK[i], r.T, c->wK[i], c->wN[i], e, r.st);
+}
+
+void student_backward(const Run& r, const float* params, const void* x_q, const void* per_layer_fp, const void* per_layer_q,
+                      float* grads, float* loss_out) {
+  const mrem_ctx* c = r.c;
+  const size_t es = dt_size(c->dt);
+  const int H = c->H, F = c->F, T = r.T, L = c->L;
+  const size_t slice = (size_t)T * H * es;
+  float* parts = r.at<float>(r.p.partials);
+  const int64_t numel = (int64_t)T * H;
+  for (int l = L - 1; l >= 0; --l) {
+    const LayerWs& w = r.p.lw[l];
+    const float* base = params + c->layer_stride * l;
+    float* g = grads + c->layer_stride * l;
+    const void* x = l == 0 ? x_q : (const char*)per_layer_q + slice * (l - 1);
+    const void* fq = (const char*)per_layer_q + slice * l;
+    const void* ffp = (const char*)per_layer_fp + slice * l;
+    const bool in_loss = (c->cfg.loss_layer_mask >> l) & 1u;
+    // Eq. 3 term of this layer and its gradient
+    if (in_loss) {
+      const float scale = c->cfg.loss_mean ? 1.0f / (float)numel : 1.0f;
+      const int n = mse_loss_grad(c->dt, fq, ffp, r.at(r.p.lg), numel, scale, parts, r.st);
+      ReduceSeg sg{0, 1, loss_out + 1 + l};
+      reduce_partials(parts, n, 1, &sg, 1, scale, r.st);
+    } else {
+      fill_f32(loss_out + 1 + l, 0.f, 1, r.st);
+    }
+    // second LayerNorm: dy = [dr1 + dxh*mask of the layer above] + loss gradient
+    {
+      const bool top = (l == L - 1);
+      const QArg q_above = top ? QArg() : make_q(c, params, l + 1, 0);
+      const int n = ln_bwd(c->dt, top ? nullptr : r.at(r.p.dr1), in_loss ? r.at(r.p.lg) : nullptr, top ? nullptr : r.at(r.p.dxh), fq,
+                           q_above, r.at(w.x1), r.at(w.y), r.at<float>(w.mu2), r.at<float>(w.rstd2), base + c->foff[MREM_F_LN2_G],
+                           r.at(r.p.dr2), parts, T, H, r.st);
+      ReduceSeg sg[4] = {{0, H, g + c->foff[MREM_F_LN2_G]}, {H, H, g + c->foff[MREM_F_LN2_B]}, {2 * H, H, g + c->foff[MREM_F_B_2]},
+                         {3 * H, 1, top ? nullptr : grads + c->layer_stride * (l + 1) + c->foff[MREM_F_S_A] + 0}};
+      reduce_partials(parts, n, 3 * H + 1, sg, top ? 3 : 4, 1.f, r.st);
+    }
+    // second feed-forward projection
+    transpose_colsum(c->dt, r.at(r.p.dr2), T, H, H, r.at(r.p.tA), nullptr, r.st);
+    transpose_colsum(c->dt, r.at(w.gcodes), T, F, F, r.at(r.p.tB), nullptr, r.st);
+    wgrad(r, params, grads, l, 3, r.at(r.p.tA), r.at(r.p.tB));
+    dgrad(r, l, 3, r.at(r.p.dr2), r.at(r.p.dgh));
+    // GELU and its output quantizer
+    {
+      const int n = gelu_quant_bwd(c->dt, r.at(r.p.dgh), r.at(w.u), r.at(r.p.du), (int64_t)T * F, make_q(c, params, l, 7), parts, r.st);
+      ReduceSeg sg{0, 1, g + c->foff[MREM_F_S_A] + 7};
+      reduce_partials(parts, n, 1, &sg, 1, 1.f, r.st);
+    }
+    // first feed-forward projection
+    {
+      const int n = transpose_colsum(c->dt, r.at(r.p.du), T, F, F, r.at(r.p.tA), parts, r.st);
+      ReduceSeg sg{0, F, g + c->foff[MREM_F_B_1]};
+      reduce_partials(parts, n, F, &sg, 1, 1.f, r.st);
+    }
+    transpose_colsum(c->dt, r.at(w.x1codes), T, H, H, r.at(r.p.tB), nullptr, r.st);
+    wgrad(r, params, grads, l, 2, r.at(r.p.tA), r.at(r.p.tB));
+    dgrad(r, l, 2, r.at(r.p.du), r.at(r.p.dx1h));
+    // first LayerNorm: dy = dr2 (residual) + dx1h through the FFN-input quantizer
+    {
+      const int n = ln_bwd(c->dt, r.at(r.p.dr2), nullptr, r.at(r.p.dx1h), r.at(w.x1), make_q(c, params, l, 6), x, r.at(w.o),
+                           r.at<float>(w.mu1), r.at<float>(w.rstd1), base + c->foff[MREM_F_LN1_G], r.at(r.p.dr1), parts, T, H, r.st);
+      ReduceSeg sg[4] = {{0, H, g + c->foff[MREM_F_LN1_G]}, {H, H, g + c->foff[MREM_F_LN1_B]}, {2 * H, H, g + c->foff[MREM_F_B_O]},
+                         {3 * H, 1, g + c->foff[MREM_F_S_A] + 6}};
+      reduce_partials(parts, n, 3 * H + 1, sg, 4, 1.f, r.st);
+    }
+    // attention output projection
+    transpose_colsum(c->dt, r.at(r.p.dr1), T, H, H, r.at(r.p.tA), nullptr, r.st);
+    transpose_colsum(c->dt, r.at(w.ctxcodes), T, H, H, r.at(r.p.tB), nullptr, r.st);
+    wgrad(r, params, grads, l, 1, r.at(r.p.tA), r.at(r.p.tB));
+    dgrad(r, l, 1, r.at(r.p.dr1), r.at(r.p.dch));
+    {
+      const int n = quant_bwd(c->dt, r.at(r.p.dch), r.at(w.ctx), r.at(r.p.dc), numel, make_q(c, params, l, 5), parts, r.st);
+      ReduceSeg sg{0, 1, g + c->foff[MREM_F_S_A] + 5};
+      reduce_partials(parts, n, 1, &sg, 1, 1.f, r.st);
+    }
+    // attention
+    const AttnQ aq = make_attn_q(c, params, l, true);
+    attn_bwd(c->dt, r.at(w.qkvcodes), r.at(r.p.dc), r.at(r.p.dqkvh), aq, r.seqlens, r.B, r.S, c->nh, c->d, r.at<float>(r.p.s_da),
+             r.at<float>(r.p.s_ph), r.at<float>(r.p.ds_rows), r.st);
+    {
+      ReduceSeg sg{0, 1, g + c->foff[MREM_F_S_A] + 3};
+      reduce_partials(r.at<float>(r.p.ds_rows), r.B * c->nh * r.S, 1, &sg, 1, 1.f, r.st);
+    }
+    {
+      const int n = qkv_quant_bwd(c->dt, r.at(r.p.dqkvh), r.at(w.qkv), r.at(r.p.dqkv), T, H, aq.q, aq.k, aq.v, parts, r.st);
+      ReduceSeg sg[3] = {{0, 1, g + c->foff[MREM_F_S_A] + 1}, {1, 1, g + c->foff[MREM_F_S_A] + 2}, {2, 1, g + c->foff[MREM_F_S_A] + 4}};
+      reduce_partials(parts, n, 3, sg, 3, 1.f, r.st);
+    }
+    // query/key/value projection
+    {
+      const int n = transpose_colsum(c->dt, r.at(r.p.dqkv), T, 3 * H, 3 * H, r.at(r.p.tA), parts, r.st);
+      ReduceSeg sg{0, 3 * H, g + c->foff[MREM_F_B_QKV]};
+      reduce_partials(parts, n, 3 * H, &sg, 1, 1.f, r.st);
+    }
+    transpose_colsum(c->dt, r.at(w.xcodes), T, H, H, r.at(r.p.tB), nullptr, r.st);
+    wgrad(r, params, grads, l, 0, r.at(r.p.tA), r.at(r.p.tB));
+    dgrad(r, l, 0, r.at(r.p.dqkv), r.at(r.p.dxh));
+    if (l == 0) {
+      // nothing flows out of the module (Section 4.2); only the input quantizer's step needs dxh
+      const int n = quant_bwd_reduce(c->dt, r.at(r.p.dxh), x, numel, make_q(c, params, 0, 0), parts, r.st);
+      ReduceSeg sg{0, 1, g + c->foff[MREM_F_S_A] + 0};
+      reduce_partials(parts, n, 1, &sg, 1, 1.f, r.st);
+    }
+    fill_f32(g + c->foff[MREM_F_Z_A], 0.f, 8, r.st);
+  }
+  loss_total(loss_out, L, r.st);
+}
+
+void apply_update(const Run& r, float* params, float* grads, float* m, float* v, int64_t step, float lr, int write_grads) {
+  const mrem_ctx* c = r.c;
+  AdamArg a;
+  a.lr = lr; a.beta1 = c->cfg.beta1; a.beta2 = c->cfg.beta2; a.eps = c->cfg.adam_eps; a.wd = c->cfg.weight_decay;
+  a.bc1 = (float)(1.0 - std::pow((double)c->cfg.beta1, (double)step));
+  a.bc2 = (float)(1.0 - std::pow((double)c->cfg.beta2, (double)step));
+  a.floor = c->cfg.step_floor;
+  AdamArg nodecay = a;
+  nodecay.wd = 0.f;
+  for (int l = 0; l < c->L; ++l) {
+    const int64_t o = c->layer_stride * l;
+    for (int i = 0; i < 4; ++i) {
+      const int64_t ow = o + c->foff[kWField[i]], os = o + c->foff[kSField[i]];
+      adam_matrix(params + ow, params + os, grads + ow, grads + os, m + ow, v + ow, m + os, v + os, c->wN[i], c->wK[i], c->cfg.w_bits, a,
+                  write_grads, r.st);
+    }
+    const int64_t ob = o + c->foff[MREM_F_B_QKV];
+    const int64_t nb = c->foff[MREM_F_SW_QKV] - c->foff[MREM_F_B_QKV];
+    adam_vector(params + ob, grads + ob, m + ob, v + ob, nb, nodecay, 0, r.st);
+    if (c->cfg.a_bits > 0) {
+      const int64_t oa = o + c->foff[MREM_F_S_A];
+      adam_vector(params + oa, grads + oa, m + oa, v + oa, 8, nodecay, 1, r.st);
+    }
+  }
+}
+
+mrem_status check_common(const mrem_ctx* ctx, int32_t batch, int32_t seq, const void* workspace, size_t workspace_bytes, const char* who,
+                         Plan* plan) {
+  if (!ctx) return fail(nullptr, MREM_EINVAL, std::string(who) + ": null context");
+  if (batch < 1 || batch > ctx->cfg.max_batch) return fail(ctx, MREM_ESHAPE, std::string(who) + ": batch outside 1..max_batch");
+  if (seq < 1 || seq > ctx->cfg.max_seq) return fail(ctx, MREM_ESHAPE, std::string(who) + ": seq outside 1..max_seq");
+  if (!workspace || !aligned16(workspace)) return fail(ctx, MREM_EINVAL, std::string(who) + ": workspace null or misaligned");
+  *plan = make_plan(ctx, batch, seq);
+  if (workspace_bytes < plan->total) return fail(ctx, MREM_EWORKSPACE, std::string(who) + ": workspace too small");
+  return MREM_OK;
+}
+
+mrem_status finish(const mrem_ctx* ctx, const char* who) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(ctx, MREM_EHIP, std::string(who) + ": " + hipGetErrorString(e));
+  return MREM_OK;
+}
+
+#define REQUIRE_PTR(p, who)                                                                  \
+  do {                                                                                       \
+    if (!(p) || !aligned16(p)) return fail(ctx, MREM_EINVAL, std::string(who) + ": " #p " is null or not 16-byte aligned"); \
+  } while (0)
+
+}  // namespace
+
+extern "C" size_t mrem_workspace_bytes(const mrem_ctx* ctx, int32_t batch, int32_t seq) {
+  if (!ctx || batch < 1 || seq < 1) return 0;
+  return make_plan(ctx, batch, seq).total;
+}
+
+extern "C" mrem_status mrem_quantize(const float* w, int64_t N, int64_t K, int32_t bits, int32_t init_scale, float* scale, int8_t* codes,
+                                     void* hip_stream) {
+  const mrem_ctx* ctx = nullptr;
+  REQUIRE_PTR(w, "mrem_quantize");
+  REQUIRE_PTR(scale, "mrem_quantize");
+  REQUIRE_PTR(codes, "mrem_quantize");
+  if (bits < 2 || bits > 8) return fail(nullptr, MREM_EINVAL, "mrem_quantize: bits must be in 2..8");
+  if (N < 1 || K < 1 || N > 0x7fffffff) return fail(nullptr, MREM_ESHAPE, "mrem_quantize: N and K must be >= 1 (N < 2^31)");
+  weight_quantize_i8(w, scale, codes, N, K, bits, init_scale, (hipStream_t)hip_stream);
+  return finish(nullptr, "mrem_quantize");
+}
+
+extern "C" mrem_status mrem_module_init_steps(mrem_ctx* ctx, float* params, void* hip_stream) {
+  if (!ctx) return fail(nullptr, MREM_EINVAL, "mrem_module_init_steps: null context");
+  REQUIRE_PTR(params, "mrem_module_init_steps");
+  if (ctx->cfg.w_bits == 0) return fail(ctx, MREM_EINVAL, "mrem_module_init_steps: weight quantizers are off (w_bits = 0)");
+  for (int l = 0; l < ctx->L; ++l)
+    for (int i = 0; i < 4; ++i)
+      weight_step_init(params + ctx->layer_stride * l + ctx->foff[kWField[i]], params + ctx->layer_stride * l + ctx->foff[kSField[i]],
+                       ctx->wN[i], ctx->wK[i], ctx->cfg.w_bits, (hipStream_t)hip_stream);
+  return finish(ctx, "mrem_module_init_steps");
+}
+
+extern "C" mrem_status mrem_teacher_prepare(mrem_ctx* ctx, const float* teacher, void* cache, void* hip_stream) {
+  if (!ctx) return fail(nullptr, MREM_EINVAL, "mrem_teacher_prepare: null context");
+  REQUIRE_PTR(teacher, "mrem_teacher_prepare");
+  REQUIRE_PTR(cache, "mrem_teacher_prepare");
+  const size_t es = dt_size(ctx->dt);
+  for (int l = 0; l < ctx->L; ++l)
+    for (int i = 0; i < 4; ++i)
+      convert_f32(ctx->dt, teacher + ctx->layer_stride * l + ctx->foff[kWField[i]],
+                  (char*)cache + ((size_t)ctx->tc_layer_stride * l + ctx->tc_off[i]) * es, (int64_t)ctx->wN[i] * ctx->wK[i],
+                  (hipStream_t)hip_stream);
+  return finish(ctx, "mrem_teacher_prepare");
+}
+
+extern "C" mrem_status mrem_module_calibrate(mrem_ctx* ctx, float* params, const float* teacher, const void* teacher_cache, const void* x_fp,
+                                             const int32_t* seqlens, int32_t batch, int32_t seq, void* workspace, size_t workspace_bytes,
+                                             void* hip_stream) {
+  Plan plan;
+  mrem_status s = check_common(ctx, batch, seq, workspace, workspace_bytes, "mrem_module_calibrate", &plan);
+  if (s != MREM_OK) return s;
+  REQUIRE_PTR(params, "mrem_module_calibrate");
+  REQUIRE_PTR(teacher, "mrem_module_calibrate");
+  REQUIRE_PTR(teacher_cache, "mrem_module_calibrate");
+  REQUIRE_PTR(x_fp, "mrem_module_calibrate");
+  if (ctx->cfg.a_bits == 0) return fail(ctx, MREM_EINVAL, "mrem_module_calibrate: activation quantizers are off (a_bits = 0)");
+  Run r{ctx, plan, (char*)workspace, (hipStream_t)hip_stream, batch, seq, batch * seq, seqlens};
+  // Layer by layer with two alternating output buffers: only the ranges are wanted, not the per-layer outputs.
+  {
+    mrem_ctx one = *ctx;
+    one.L = 1;
+    const size_t es = dt_size(ctx->dt);
+    void* bufs[2] = {r.at(r.p.dr1), r.at(r.p.dr2)};
+    const void* x = x_fp;
+    for (int l = 0; l < ctx->L; ++l) {
+      Run rl = r;
+      rl.c = &one;
+      teacher_forward(rl, teacher + ctx->layer_stride * l, (const char*)teacher_cache + (size_t)ctx->tc_layer_stride * l * es, x,
+                      bufs[l & 1], params + ctx->layer_stride * l);
+      x = bufs[l & 1];
+    }
+  }
+  return finish(ctx, "mrem_module_calibrate");
+}
+
+extern "C" mrem_status mrem_module_forward(mrem_ctx* ctx, const float* params, const float* teacher, const void* teacher_cache,
+                                           const void* x_fp, const void* x_q, const int32_t* seqlens, int32_t batch, int32_t seq,
+                                           void* per_layer_fp, void* per_layer_q, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Plan plan;
+  mrem_status s = check_common(ctx, batch, seq, workspace, workspace_bytes, "mrem_module_forward", &plan);
+  if (s != MREM_OK) return s;
+  if (!per_layer_fp && !per_layer_q) return fail(ctx, MREM_EINVAL, "mrem_module_forward: both outputs are null");
+  Run r{ctx, plan, (char*)workspace, (hipStream_t)hip_stream, batch, seq, batch * seq, seqlens};
+  if (per_layer_fp) {
+    REQUIRE_PTR(teacher, "mrem_module_forward");
+    REQUIRE_PTR(teacher_cache, "mrem_module_forward");
+    REQUIRE_PTR(x_fp, "mrem_module_forward");
+    if (!aligned16(per_layer_fp)) return fail(ctx, MREM_EINVAL, "mrem_module_forward: per_layer_fp misaligned");
+  }
+  if (per_layer_q) {
+    REQUIRE_PTR(params, "mrem_module_forward");
+    REQUIRE_PTR(x_q, "mrem_module_forward");
+    if (!aligned16(per_layer_q)) return fail(ctx, MREM_EINVAL, "mrem_module_forward: per_layer_q misaligned");
+  }
+  if (per_layer_fp) teacher_forward(r, teacher, teacher_cache, x_fp, per_layer_fp, nullptr);
+  if (per_layer_q) {
+    prepare_weights(r, params);
+    student_forward(r, params, x_q, per_layer_q);
+  }
+  return finish(ctx, "mrem_module_forward");
+}
+
+extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* adam_m, float* adam_v, int64_t step_index, float lr,
+                                        const float* teacher, const void* teacher_cache, const void* x_fp, const void* x_q,
+                                        const int32_t* seqlens, int32_t batch, int32_t seq, float* loss_out, void* per_layer_fp,
+                                        void* per_layer_q, float* grads_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Plan plan;
+  mrem_status s = check_common(ctx, batch, seq, workspace, workspace_bytes, "mrem_module_step", &plan);
+  if (s != MREM_OK) return s;
+  REQUIRE_PTR(params, "mrem_module_step");
+  REQUIRE_PTR(adam_m, "mrem_module_step");
+  REQUIRE_PTR(adam_v, "mrem_module_step");
+  REQUIRE_PTR(teacher, "mrem_module_step");
+  REQUIRE_PTR(teacher_cache, "mrem_module_step");
+  REQUIRE_PTR(x_fp, "mrem_module_step");
+  REQUIRE_PTR(x_q, "mrem_module_step");
+  REQUIRE_PTR(loss_out, "mrem_module_step");
+  REQUIRE_PTR(per_layer_fp, "mrem_module_step");
+  REQUIRE_PTR(per_layer_q, "mrem_module_step");
+  if (grads_out && !aligned16(grads_out)) return fail(ctx, MREM_EINVAL, "mrem_module_step: grads_out misaligned");
+  if (step_index < 1) return fail(ctx, MREM_EINVAL, "mrem_module_step: step_index is 1-based");
+  Run r{ctx, plan, (char*)workspace, (hipStream_t)hip_stream, batch, seq, batch * seq, seqlens};
+  float* grads = grads_out ? grads_out : r.at<float>(r.p.grads);
+  teacher_forward(r, teacher, teacher_cache, x_fp, per_layer_fp, nullptr);
+  prepare_weights(r, params);
+  student_forward(r, params, x_q, per_layer_q);
+  student_backward(r, params, x_q, per_layer_fp, per_layer_q, grads, loss_out);
+  apply_update(r, params, grads, adam_m, adam_v, step_index, lr, grads_out != nullptr);
+  return finish(ctx, "mrem_module_step");
+}
+
+extern "C" mrem_status mrem_mix_inputs(mrem_ctx* ctx, const void* x_fp, const void* x_q, float lambda, void* out, int64_t n,
+                                       void* hip_stream) {
+  if (!ctx) return fail(nullptr, MREM_EINVAL, "mrem_mix_inputs: null context");
+  REQUIRE_PTR(x_fp, "mrem_mix_inputs");
+  REQUIRE_PTR(x_q, "mrem_mix_inputs");
+  REQUIRE_PTR(out, "mrem_mix_inputs");
+  if (n < 1) return fail(ctx, MREM_ESHAPE, "mrem_mix_inputs: n must be >= 1");
+  if (!(lambda >= 0.f && lambda <= 1.f)) return fail(ctx, MREM_EINVAL, "mrem_mix_inputs: lambda must be in [0,1]");
+  axpby(ctx->dt, x_fp, x_q, lambda, 1.f - lambda, out, n, (hipStream_t)hip_stream);
+  return finish(ctx, "mrem_mix_inputs");
+}

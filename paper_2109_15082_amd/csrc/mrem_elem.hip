@@ -1,0 +1,800 @@
+// Bandwidth-bound kernels of the MREM module step: quantizers (Section 3.1, Eq. 1,
+// with the straight-through backward of Section 3.1.1), residual + LayerNorm,
+// GELU, the per-layer squared-error term of Eq. 3, transposes for the weight
+// gradient products, calibration reductions and the AdamW update.
+#include "mrem_common.h"
+#include "mrem_kernels.h"
+
+#include <float.h>
+
+namespace mrem {
+
+// ------------------------------------------------------------------------------
+// 8-element (16 or 32 byte) vector access
+// ------------------------------------------------------------------------------
+__device__ __forceinline__ void load8(const float* p, float* o) {
+  const float4 a = *reinterpret_cast<const float4*>(p);
+  const float4 b = *reinterpret_cast<const float4*>(p + 4);
+  o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_t* p, float* o) {
+  const uint4 r = *reinterpret_cast<const uint4*>(p);
+  o[0] = __uint_as_float(r.x << 16); o[1] = __uint_as_float(r.x & 0xffff0000u);
+  o[2] = __uint_as_float(r.y << 16); o[3] = __uint_as_float(r.y & 0xffff0000u);
+  o[4] = __uint_as_float(r.z << 16); o[5] = __uint_as_float(r.z & 0xffff0000u);
+  o[6] = __uint_as_float(r.w << 16); o[7] = __uint_as_float(r.w & 0xffff0000u);
+}
+__device__ __forceinline__ void store8(float* p, const float* v) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  union { bf16_t h[2]; uint32_t u; } c;
+  c.h[0] = static_cast<bf16_t>(lo);
+  c.h[1] = static_cast<bf16_t>(hi);
+  return c.u;
+}
+__device__ __forceinline__ void store8(bf16_t* p, const float* v) {
+  uint4 r;
+  r.x = pack2(v[0], v[1]); r.y = pack2(v[2], v[3]); r.z = pack2(v[4], v[5]); r.w = pack2(v[6], v[7]);
+  *reinterpret_cast<uint4*>(p) = r;
+}
+
+__device__ __forceinline__ QuantParam load_q(const QArg& a) {
+  QuantParam q;
+  q.on = a.on;
+  q.s = a.on ? *a.s : 1.f;
+  q.z = (a.on && a.z) ? *a.z : 0.f;
+  q.qn = a.qn;
+  q.qp = a.qp;
+  return q;
+}
+
+static inline int ew_grid(int64_t n) {
+  int64_t g = (n / 8 + 255) / 256;
+  if (g < 1) g = 1;
+  if (g > 2048) g = 2048;
+  return (int)g;
+}
+
+#define MREM_DISPATCH(dt, ...)                      \
+  do {                                              \
+    if ((dt) == DT_BF16) { typedef bf16_t T; __VA_ARGS__; } \
+    else { typedef float T; __VA_ARGS__; }          \
+  } while (0)
+
+// ------------------------------------------------------------------------------
+// activation quantizer forward: integer-valued codes in the storage type
+// ------------------------------------------------------------------------------
+template <class T>
+__global__ void act_quantize_k(const T* __restrict__ a, T* __restrict__ codes, int64_t nchunks, QArg qa) {
+  const QuantParam q = load_q(qa);
+  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
+    float v[8];
+    load8(a + c * 8, v);
+    if (q.on) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = q_code(q_ratio(v[j], q), q);
+    }
+    store8(codes + c * 8, v);
+  }
+}
+void act_quantize(int dt, const void* a, void* codes, int64_t n, QArg q, hipStream_t st) {
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(act_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)a, (T*)codes, n / 8, q));
+}
+
+// three column sections of qkv[T,3H] with their own quantizers
+template <class T>
+__global__ void qkv_quantize_k(const T* __restrict__ a, T* __restrict__ codes, int64_t nchunks, int H8, QArg q0, QArg q1,
+                               QArg q2) {
+  const QuantParam qs[3] = {load_q(q0), load_q(q1), load_q(q2)};
+  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
+    const int sec = (int)((c % (3 * (int64_t)H8)) / H8);
+    const QuantParam q = qs[sec];
+    float v[8];
+    load8(a + c * 8, v);
+    if (q.on) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = q_code(q_ratio(v[j], q), q);
+    }
+    store8(codes + c * 8, v);
+  }
+}
+void qkv_quantize(int dt, const void* qkv, void* codes, int T_, int H, QArg q, QArg k, QArg v, hipStream_t st) {
+  const int64_t n = (int64_t)T_ * 3 * H;
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(qkv_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)qkv, (T*)codes, n / 8,
+                                       H / 8, q, k, v));
+}
+
+// d_out = d_q * inside ; partial[block][sec] += d_q * (code - v * inside)
+template <class T>
+__global__ void qkv_quant_bwd_k(const T* __restrict__ dq, const T* __restrict__ a, T* __restrict__ dout, int64_t nchunks,
+                                int H8, QArg q0, QArg q1, QArg q2, float* __restrict__ partials) {
+  __shared__ float red[17];
+  const QuantParam qs[3] = {load_q(q0), load_q(q1), load_q(q2)};
+  float acc[3] = {0.f, 0.f, 0.f};
+  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
+    const int sec = (int)((c % (3 * (int64_t)H8)) / H8);
+    const QuantParam q = qs[sec];
+    float g[8], x[8];
+    load8(dq + c * 8, g);
+    if (q.on) {
+      load8(a + c * 8, x);
+      float t = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float v = q_ratio(x[j], q);
+        const bool in = q_inside(v, q);
+        t += g[j] * (q_code(v, q) - (in ? v : 0.f));
+        g[j] = in ? g[j] : 0.f;
+      }
+      acc[0] += sec == 0 ? t : 0.f;
+      acc[1] += sec == 1 ? t : 0.f;
+      acc[2] += sec == 2 ? t : 0.f;
+    }
+    if (dout) store8(dout + c * 8, g);
+  }
+  for (int s = 0; s < 3; ++s) {
+    const float t = block_sum(acc[s], red);
+    if (threadIdx.x == 0) partials[blockIdx.x * 3 + s] = t;
+  }
+}
+int qkv_quant_bwd(int dt, const void* d_qkvh, const void* qkv, void* d_qkv, int T_, int H, QArg q, QArg k, QArg v,
+                  float* partials, hipStream_t st) {
+  const int64_t n = (int64_t)T_ * 3 * H;
+  const int g = ew_grid(n);
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(qkv_quant_bwd_k<T>, dim3(g), dim3(256), 0, st, (const T*)d_qkvh, (const T*)qkv,
+                                       (T*)d_qkv, n / 8, H / 8, q, k, v, partials));
+  return g;
+}
+
+// generic single-quantizer backward (d_out may be null: reduction only)
+template <class T>
+__global__ void quant_bwd_k(const T* __restrict__ dq, const T* __restrict__ a, T* __restrict__ dout, int64_t nchunks, QArg qa,
+                            float* __restrict__ partials) {
+  __shared__ float red[17];
+  const QuantParam q = load_q(qa);
+  float acc = 0.f;
+  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
+    float g[8], x[8];
+    load8(dq + c * 8, g);
+    if (q.on) {
+      load8(a + c * 8, x);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float v = q_ratio(x[j], q);
+        const bool in = q_inside(v, q);
+        acc += g[j] * (q_code(v, q) - (in ? v : 0.f));
+        g[j] = in ? g[j] : 0.f;
+      }
+    }
+    if (dout) store8(dout + c * 8, g);
+  }
+  const float t = block_sum(acc, red);
+  if (threadIdx.x == 0) partials[blockIdx.x] = t;
+}
+int quant_bwd(int dt, const void* d_q, const void* a, void* d_out, int64_t n, QArg q, float* partials, hipStream_t st) {
+  const int g = ew_grid(n);
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(quant_bwd_k<T>, dim3(g), dim3(256), 0, st, (const T*)d_q, (const T*)a, (T*)d_out,
+                                       n / 8, q, partials));
+  return g;
+}
+int quant_bwd_reduce(int dt, const void* d_q, const void* a, int64_t n, QArg q, float* partials, hipStream_t st) {
+  return quant_bwd(dt, d_q, a, nullptr, n, q, partials, st);
+}
+
+// ------------------------------------------------------------------------------
+// GELU + quantizer of its output (unsigned grid with offset)
+// ------------------------------------------------------------------------------
+template <class T>
+__global__ void gelu_quantize_k(const T* __restrict__ u, T* __restrict__ codes, int64_t nchunks, QArg qa) {
+  const QuantParam q = load_q(qa);
+  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
+    float v[8];
+    load8(u + c * 8, v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float g = gelu_f(v[j]);
+      v[j] = q.on ? q_code(q_ratio(g, q), q) : g;
+    }
+    store8(codes + c * 8, v);
+  }
+}
+void gelu_quantize(int dt, const void* u, void* codes, int64_t n, QArg q, hipStream_t st) {
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(gelu_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)u, (T*)codes, n / 8, q));
+}
+
+template <class T>
+__global__ void gelu_quant_bwd_k(const T* __restrict__ dgh, const T* __restrict__ u, T* __restrict__ du, int64_t nchunks,
+                                 QArg qa, float* __restrict__ partials) {
+  __shared__ float red[17];
+  const QuantParam q = load_q(qa);
+  float acc = 0.f;
+  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
+    float g[8], x[8];
+    load8(dgh + c * 8, g);
+    load8(u + c * 8, x);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float dg = g[j];
+      if (q.on) {
+        const float v = q_ratio(gelu_f(x[j]), q);
+        const bool in = q_inside(v, q);
+        acc += dg * (q_code(v, q) - (in ? v : 0.f));
+        dg = in ? dg : 0.f;
+      }
+      g[j] = dg * gelu_grad_f(x[j]);
+    }
+    store8(du + c * 8, g);
+  }
+  const float t = block_sum(acc, red);
+  if (threadIdx.x == 0) partials[blockIdx.x] = t;
+}
+int gelu_quant_bwd(int dt, const void* dgh, const void* u, void* du, int64_t n, QArg q, float* partials, hipStream_t st) {
+  const int g = ew_grid(n);
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(gelu_quant_bwd_k<T>, dim3(g), dim3(256), 0, st, (const T*)dgh, (const T*)u, (T*)du,
+                                       n / 8, q, partials));
+  return g;
+}
+
+// ------------------------------------------------------------------------------
+// residual + LayerNorm: one wavefront per token row, 8-element chunks per lane
+// ------------------------------------------------------------------------------
+constexpr int kLnMaxChunks = 4;  // hidden <= 64 lanes * 8 * 4 = 2048
+
+template <class T>
+__global__ void ln_fwd_k(const T* __restrict__ x, const T* __restrict__ r, const float* __restrict__ gamma,
+                         const float* __restrict__ beta, T* __restrict__ y, T* __restrict__ ycodes, QArg qa,
+                         float* __restrict__ mu_out, float* __restrict__ rstd_out, int T_, int H, float eps) {
+  const QuantParam q = load_q(qa);
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
+  if (row >= T_) return;
+  const int nch = H / 8;
+  float v[kLnMaxChunks][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < kLnMaxChunks; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nch) {
+      float a[8], b[8];
+      load8(x + (size_t)row * H + c * 8, a);
+      load8(r + (size_t)row * H + c * 8, b);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { v[i][j] = a[j] + b[j]; sum += v[i][j]; }
+    }
+  }
+  const float mean = wave_sum(sum) / (float)H;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < kLnMaxChunks; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nch) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { const float t = v[i][j] - mean; sq += t * t; }
+    }
+  }
+  const float var = wave_sum(sq) / (float)H;
+  const float rstd = 1.0f / sqrtf(var + eps);
+  if (lane == 0) { mu_out[row] = mean; rstd_out[row] = rstd; }
+#pragma unroll
+  for (int i = 0; i < kLnMaxChunks; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nch) {
+      float g[8], b[8], o[8];
+      load8(gamma + c * 8, g);
+      load8(beta + c * 8, b);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o[j] = (v[i][j] - mean) * rstd * g[j] + b[j];
+      store8(y + (size_t)row * H + c * 8, o);
+      if (ycodes) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float s = round_to<T>(o[j]);
+          o[j] = q.on ? q_code(q_ratio(s, q), q) : s;
+        }
+        store8(ycodes + (size_t)row * H + c * 8, o);
+      }
+    }
+  }
+}
+void ln_fwd(int dt, const void* x, const void* r, const float* gamma, const float* beta, void* y, void* ycodes, QArg q,
+            float* mu, float* rstd, int T_, int H, float eps, hipStream_t st) {
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(ln_fwd_k<T>, dim3((T_ + 3) / 4), dim3(256), 0, st, (const T*)x, (const T*)r, gamma, beta,
+                                       (T*)y, (T*)ycodes, q, mu, rstd, T_, H, eps));
+}
+
+constexpr int kLnBwdRows = 16;  // token rows per block (4 per wavefront)
+int ln_bwd_parts(int T_) { return (T_ + kLnBwdRows - 1) / kLnBwdRows; }
+
+template <class T>
+__global__ void ln_bwd_k(const T* __restrict__ d_a, const T* __restrict__ d_b, const T* __restrict__ d_q,
+                         const T* __restrict__ a_q, QArg qa, const T* __restrict__ x, const T* __restrict__ r,
+                         const float* __restrict__ mu, const float* __restrict__ rstd_in, const float* __restrict__ gamma,
+                         T* __restrict__ dr, float* __restrict__ partials, int T_, int H) {
+  extern __shared__ float red[];  // [3*H] + 4
+  const QuantParam q = load_q(qa);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x / 64;
+  const int nch = H / 8;
+  float acc_g[kLnMaxChunks][8], acc_b[kLnMaxChunks][8], acc_d[kLnMaxChunks][8];
+#pragma unroll
+  for (int i = 0; i < kLnMaxChunks; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc_g[i][j] = acc_b[i][j] = acc_d[i][j] = 0.f;
+  float ds_acc = 0.f;
+
+  for (int rr = wave; rr < kLnBwdRows; rr += 4) {
+    const int row = blockIdx.x * kLnBwdRows + rr;
+    if (row >= T_) break;
+    const float mean = mu[row], rstd = rstd_in[row];
+    float dy[kLnMaxChunks][8], xh[kLnMaxChunks][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < kLnMaxChunks; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nch) {
+        const size_t off = (size_t)row * H + c * 8;
+        float t[8], g[8], xa[8], xb[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dy[i][j] = 0.f;
+        if (d_a) { load8(d_a + off, t);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) dy[i][j] += t[j]; }
+        if (d_b) { load8(d_b + off, t);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) dy[i][j] += t[j]; }
+        if (d_q) {
+          load8(d_q + off, t);
+          if (q.on) {
+            float av[8];
+            load8(a_q + off, av);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              const float v = q_ratio(av[j], q);
+              const bool in = q_inside(v, q);
+              ds_acc += t[j] * (q_code(v, q) - (in ? v : 0.f));
+              t[j] = in ? t[j] : 0.f;
+            }
+          }
+#pragma unroll
+          for (int j = 0; j < 8; ++j) dy[i][j] += t[j];
+        }
+        load8(gamma + c * 8, g);
+        load8(x + off, xa);
+        load8(r + off, xb);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          xh[i][j] = (xa[j] + xb[j] - mean) * rstd;
+          acc_g[i][j] += dy[i][j] * xh[i][j];
+          acc_b[i][j] += dy[i][j];
+          dy[i][j] *= g[j];  // now d(xhat)
+          s1 += dy[i][j];
+          s2 += dy[i][j] * xh[i][j];
+        }
+      }
+    }
+    const float m1 = wave_sum(s1) / (float)H, m2 = wave_sum(s2) / (float)H;
+#pragma unroll
+    for (int i = 0; i < kLnMaxChunks; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nch) {
+        float o[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          o[j] = rstd * (dy[i][j] - m1 - xh[i][j] * m2);
+          acc_d[i][j] += round_to<T>(o[j]);
+        }
+        store8(dr + (size_t)row * H + c * 8, o);
+      }
+    }
+  }
+  // combine the four wavefronts in a fixed order, then write this block's partial row
+  ds_acc = wave_sum(ds_acc);
+  for (int w = 0; w < 4; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int i = 0; i < kLnMaxChunks; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nch) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const int col = c * 8 + j;
+            if (w == 0) { red[col] = acc_g[i][j]; red[H + col] = acc_b[i][j]; red[2 * H + col] = acc_d[i][j]; }
+            else { red[col] += acc_g[i][j]; red[H + col] += acc_b[i][j]; red[2 * H + col] += acc_d[i][j]; }
+          }
+        }
+      }
+      if (lane == 0) red[3 * H + w] = ds_acc;
+    }
+    __syncthreads();
+  }
+  const int width = 3 * H + 1;
+  float* out = partials + (size_t)blockIdx.x * width;
+  for (int c = threadIdx.x; c < 3 * H; c += blockDim.x) out[c] = red[c];
+  if (threadIdx.x == 0) out[3 * H] = red[3 * H] + red[3 * H + 1] + red[3 * H + 2] + red[3 * H + 3];
+}
+int ln_bwd(int dt, const void* d_a, const void* d_b, const void* d_q, const void* a_q, QArg q, const void* x, const void* r,
+           const float* mu, const float* rstd, const float* gamma, void* dr, float* partials, int T_, int H, hipStream_t st) {
+  const int g = ln_bwd_parts(T_);
+  const size_t lds = (3 * (size_t)H + 4) * sizeof(float);
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(ln_bwd_k<T>, dim3(g), dim3(256), lds, st, (const T*)d_a, (const T*)d_b, (const T*)d_q,
+                                       (const T*)a_q, q, (const T*)x, (const T*)r, mu, rstd, gamma, (T*)dr, partials, T_, H));
+  return g;
+}
+
+// ------------------------------------------------------------------------------
+// squared-error term of Eq. 3 for one layer and its gradient
+// ------------------------------------------------------------------------------
+template <class T>
+__global__ void mse_k(const T* __restrict__ fq, const T* __restrict__ ffp, T* __restrict__ grad, int64_t nchunks, float scale,
+                      float* __restrict__ partials) {
+  __shared__ float red[17];
+  float acc = 0.f;
+  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
+    float a[8], b[8];
+    load8(fq + c * 8, a);
+    load8(ffp + c * 8, b);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float d = a[j] - b[j];
+      acc += d * d;
+      a[j] = 2.0f * d * scale;
+    }
+    store8(grad + c * 8, a);
+  }
+  const float t = block_sum(acc, red);
+  if (threadIdx.x == 0) partials[blockIdx.x] = t;
+}
+int mse_loss_grad(int dt, const void* fq, const void* ffp, void* grad, int64_t n, float scale, float* partials, hipStream_t st) {
+  const int g = ew_grid(n);
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(mse_k<T>, dim3(g), dim3(256), 0, st, (const T*)fq, (const T*)ffp, (T*)grad, n / 8, scale,
+                                       partials));
+  return g;
+}
+
+// ------------------------------------------------------------------------------
+// transpose (for the token-contracted weight-gradient products) + column sums
+// ------------------------------------------------------------------------------
+template <class T>
+__global__ void transpose_k(const T* __restrict__ in, int R, int C, int ld_in, T* __restrict__ out, float* __restrict__ partials) {
+  __shared__ float tile[64][65];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;  // 256 threads: 4 rows at a time
+  for (int rr = ty; rr < 64; rr += 4) {
+    const int r = r0 + rr, c = c0 + tx;
+    tile[rr][tx] = (r < R && c < C) ? ldf(in, (size_t)r * ld_in + c) : 0.f;
+  }
+  __syncthreads();
+  for (int cc = ty; cc < 64; cc += 4) {
+    const int c = c0 + cc, r = r0 + tx;
+    if (c < C && r < R) stf(out, (size_t)c * R + r, tile[tx][cc]);
+  }
+  if (partials && threadIdx.x < 64) {
+    const int c = c0 + threadIdx.x;
+    if (c < C) {
+      float s = 0.f;
+      for (int rr = 0; rr < 64; ++rr) s += tile[rr][threadIdx.x];
+      partials[(size_t)blockIdx.y * C + c] = s;
+    }
+  }
+}
+int transpose_colsum(int dt, const void* in, int R, int C, int ld_in, void* out, float* partials, hipStream_t st) {
+  dim3 g((C + 63) / 64, (R + 63) / 64);
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(transpose_k<T>, g, dim3(256), 0, st, (const T*)in, R, C, ld_in, (T*)out, partials));
+  return (int)g.y;
+}
+
+// ------------------------------------------------------------------------------
+// second stage of the two-stage reductions (fixed order => run-to-run identical)
+// ------------------------------------------------------------------------------
+struct ReduceSegs {
+  ReduceSeg s[4];
+  int n;
+};
+__global__ void reduce_partials_k(const float* __restrict__ partials, int nparts, int width, ReduceSegs segs, float scale) {
+  __shared__ float red[17];
+  // wide segments: one thread per column; scalar segments: the whole block cooperates
+  int base = 0;
+  for (int k = 0; k < segs.n; ++k) {
+    const ReduceSeg sg = segs.s[k];
+    if (sg.len == 1) {
+      if (blockIdx.x == 0) {
+        float t = 0.f;
+        for (int p = threadIdx.x; p < nparts; p += blockDim.x) t += partials[(size_t)p * width + sg.begin];
+        t = block_sum(t, red);
+        if (threadIdx.x == 0) sg.out[0] = t * scale;
+      }
+    } else {
+      for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < sg.len; c += gridDim.x * blockDim.x) {
+        float t = 0.f;
+        for (int p = 0; p < nparts; ++p) t += partials[(size_t)p * width + sg.begin + c];
+        sg.out[c] = t * scale;
+      }
+    }
+    base += sg.len;
+  }
+}
+void reduce_partials(const float* partials, int nparts, int width, const ReduceSeg* segs, int nsegs, float scale, hipStream_t st) {
+  ReduceSegs s;
+  s.n = nsegs;
+  int maxlen = 1;
+  for (int i = 0; i < nsegs; ++i) { s.s[i] = segs[i]; if (segs[i].len > maxlen) maxlen = segs[i].len; }
+  int g = (maxlen + 255) / 256;
+  hipLaunchKernelGGL(reduce_partials_k, dim3(g), dim3(256), 0, st, partials, nparts, width, s, scale);
+}
+
+__global__ void loss_total_k(float* loss_out, int n_layers) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    float t = 0.f;
+    for (int l = 0; l < n_layers; ++l) t += loss_out[1 + l];
+    loss_out[0] = t;
+  }
+}
+void loss_total(float* loss_out, int n_layers, hipStream_t st) { hipLaunchKernelGGL(loss_total_k, dim3(1), dim3(64), 0, st, loss_out, n_layers); }
+
+__global__ void fill_k(float* p, float v, int64_t n) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+void fill_f32(float* p, float v, int64_t n, hipStream_t st) {
+  int g = (int)((n + 255) / 256);
+  if (g > 4096) g = 4096;
+  if (g < 1) g = 1;
+  hipLaunchKernelGGL(fill_k, dim3(g), dim3(256), 0, st, p, v, n);
+}
+
+// Eq. 4: out = wa * a + wb * b
+template <class T>
+__global__ void axpby_k(const T* __restrict__ a, const T* __restrict__ b, float wa, float wb, T* __restrict__ out, int64_t n) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    stf(out, i, wa * ldf(a, i) + wb * ldf(b, i));
+}
+void axpby(int dt, const void* a, const void* b, float wa, float wb, void* out, int64_t n, hipStream_t st) {
+  int g = (int)((n + 255) / 256);
+  if (g > 4096) g = 4096;
+  if (g < 1) g = 1;
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(axpby_k<T>, dim3(g), dim3(256), 0, st, (const T*)a, (const T*)b, wa, wb, (T*)out, n));
+}
+
+template <class T>
+__global__ void convert_k(const float* __restrict__ src, T* __restrict__ dst, int64_t n) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) stf(dst, i, src[i]);
+}
+void convert_f32(int dt, const float* src, void* dst, int64_t n, hipStream_t st) {
+  int g = (int)((n + 255) / 256);
+  if (g > 8192) g = 8192;
+  if (g < 1) g = 1;
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(convert_k<T>, dim3(g), dim3(256), 0, st, src, (T*)dst, n));
+}
+
+// ------------------------------------------------------------------------------
+// weight quantizer (Eq. 1 per output channel)
+// ------------------------------------------------------------------------------
+__device__ __forceinline__ float row_step_init(const float* __restrict__ wr, int64_t K, float qp, float* red) {
+  float m = 0.f;
+  for (int64_t k = threadIdx.x; k < K; k += blockDim.x) m = fmaxf(m, fabsf(wr[k]));
+  m = block_max(m, red);
+  float s = __fdiv_rn(m, qp);
+  if (!(s > 0.f)) s = FLT_MIN;
+  return s;
+}
+
+__global__ void weight_quantize_i8_k(const float* __restrict__ w, float* __restrict__ scale, int8_t* __restrict__ codes, int64_t K,
+                                     float qp, int init_scale) {
+  __shared__ float red[17];
+  const int64_t n = blockIdx.x;
+  const float* wr = w + n * K;
+  float s;
+  if (init_scale) {
+    s = row_step_init(wr, K, qp, red);
+    if (threadIdx.x == 0) scale[n] = s;
+  } else {
+    s = scale[n];
+  }
+  for (int64_t k = threadIdx.x; k < K; k += blockDim.x) {
+    const float v = __fdiv_rn(wr[k], s);
+    codes[n * K + k] = (int8_t)(int)rintf(fminf(fmaxf(v, -qp), qp));
+  }
+}
+void weight_quantize_i8(const float* w, float* scale, int8_t* codes, int64_t N, int64_t K, int bits, int init_scale, hipStream_t st) {
+  const float qp = (float)((1 << (bits - 1)) - 1);
+  hipLaunchKernelGGL(weight_quantize_i8_k, dim3((unsigned)N), dim3(256), 0, st, w, scale, codes, K, qp, init_scale);
+}
+
+__global__ void weight_step_init_k(const float* __restrict__ w, float* __restrict__ scale, int64_t K, float qp) {
+  __shared__ float red[17];
+  const float s = row_step_init(w + (int64_t)blockIdx.x * K, K, qp, red);
+  if (threadIdx.x == 0) scale[blockIdx.x] = s;
+}
+void weight_step_init(const float* w, float* scale, int64_t N, int64_t K, int bits, hipStream_t st) {
+  const float qp = (float)((1 << (bits - 1)) - 1);
+  hipLaunchKernelGGL(weight_step_init_k, dim3((unsigned)N), dim3(256), 0, st, w, scale, K, qp);
+}
+
+// codes (integer-valued, storage type) + zcorr[n] = s[n] * sum_k code
+template <class T>
+__global__ void weight_codes_k(const float* __restrict__ w, const float* __restrict__ sw, int K, float qp, int on,
+                               T* __restrict__ codes, float* __restrict__ zcorr) {
+  __shared__ float red[17];
+  const int n = blockIdx.x;
+  const float s = on ? sw[n] : 1.f;
+  float acc = 0.f;
+  for (int k = threadIdx.x; k < K; k += blockDim.x) {
+    const float x = w[(size_t)n * K + k];
+    float c = x;
+    if (on) { c = rintf(fminf(fmaxf(__fdiv_rn(x, s), -qp), qp)); acc += c; }
+    stf(codes, (size_t)n * K + k, c);
+  }
+  acc = block_sum(acc, red);
+  if (threadIdx.x == 0) zcorr[n] = on ? s * acc : 0.f;
+}
+// what_t[k][n] = round(s[n] * code[n][k])
+template <class T>
+__global__ void weight_dequant_t_k(const float* __restrict__ w, const float* __restrict__ sw, int N, int K, float qp, int on,
+                                   T* __restrict__ what_t) {
+  __shared__ float tile[64][65];
+  const int n0 = blockIdx.y * 64, k0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int rr = ty; rr < 64; rr += 4) {
+    const int n = n0 + rr, k = k0 + tx;
+    float v = 0.f;
+    if (n < N && k < K) {
+      v = w[(size_t)n * K + k];
+      if (on) { const float s = sw[n]; v = s * rintf(fminf(fmaxf(__fdiv_rn(v, s), -qp), qp)); }
+    }
+    tile[rr][tx] = v;
+  }
+  __syncthreads();
+  for (int cc = ty; cc < 64; cc += 4) {
+    const int k = k0 + cc, n = n0 + tx;
+    if (k < K && n < N) stf(what_t, (size_t)k * N + n, tile[tx][cc]);
+  }
+}
+void weight_prepare(int dt, const float* w, const float* sw, int N, int K, int bits, void* codes, void* what_t, float* zcorr,
+                    hipStream_t st) {
+  const int on = bits > 0;
+  const float qp = on ? (float)((1 << (bits - 1)) - 1) : 0.f;
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(weight_codes_k<T>, dim3(N), dim3(256), 0, st, w, sw, K, qp, on, (T*)codes, zcorr));
+  if (what_t) {
+    dim3 g((K + 63) / 64, (N + 63) / 64);
+    MREM_DISPATCH(dt, hipLaunchKernelGGL(weight_dequant_t_k<T>, g, dim3(256), 0, st, w, sw, N, K, qp, on, (T*)what_t));
+  }
+}
+
+// ------------------------------------------------------------------------------
+// calibration reductions
+// ------------------------------------------------------------------------------
+template <class T>
+__global__ void absminmax_k(const T* __restrict__ a, int rows, int cols, int ld, int gelu, float* __restrict__ partials) {
+  __shared__ float red[17];
+  float amax = 0.f, mn = FLT_MAX, mx = -FLT_MAX;
+  const int64_t n = (int64_t)rows * cols;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = i / cols, c = i - r * cols;
+    float v = ldf(a, (size_t)(r * ld + c));
+    if (gelu) v = gelu_f(v);
+    amax = fmaxf(amax, fabsf(v));
+    mn = fminf(mn, v);
+    mx = fmaxf(mx, v);
+  }
+  amax = block_max(amax, red);
+  mx = block_max(mx, red);
+  mn = -block_max(-mn, red);
+  if (threadIdx.x == 0) {
+    partials[blockIdx.x * 3 + 0] = amax;
+    partials[blockIdx.x * 3 + 1] = mn;
+    partials[blockIdx.x * 3 + 2] = mx;
+  }
+}
+int absminmax(int dt, const void* a, int rows, int cols, int ld, int gelu, float* partials, hipStream_t st) {
+  int64_t n = (int64_t)rows * cols;
+  int g = (int)((n + 255) / 256);
+  if (g > 1024) g = 1024;
+  if (g < 1) g = 1;
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(absminmax_k<T>, dim3(g), dim3(256), 0, st, (const T*)a, rows, cols, ld, gelu, partials));
+  return g;
+}
+__global__ void calib_finalize_k(const float* __restrict__ partials, int nparts, int mode, float qp, float* s_out, float* z_out) {
+  __shared__ float red[17];
+  float amax = 0.f, mn = FLT_MAX, mx = -FLT_MAX;
+  for (int p = threadIdx.x; p < nparts; p += blockDim.x) {
+    amax = fmaxf(amax, partials[p * 3]);
+    mn = fminf(mn, partials[p * 3 + 1]);
+    mx = fmaxf(mx, partials[p * 3 + 2]);
+  }
+  amax = block_max(amax, red);
+  mx = block_max(mx, red);
+  mn = -block_max(-mn, red);
+  if (threadIdx.x == 0) {
+    float s, z = 0.f;
+    if (mode == 0) s = __fdiv_rn(amax, qp);
+    else if (mode == 1) s = __fdiv_rn(mx, qp);
+    else { z = mn; s = __fdiv_rn(__fsub_rn(mx, z), qp); }
+    if (!(s > 0.f)) s = FLT_MIN;
+    *s_out = s;
+    *z_out = z;
+  }
+}
+void calib_finalize(const float* partials, int nparts, int mode, float qp, float* s_out, float* z_out, hipStream_t st) {
+  hipLaunchKernelGGL(calib_finalize_k, dim3(1), dim3(256), 0, st, partials, nparts, mode, qp, s_out, z_out);
+}
+
+// ------------------------------------------------------------------------------
+// AdamW (decoupled weight decay, bias-corrected), Section 5.1.2
+// ------------------------------------------------------------------------------
+__device__ __forceinline__ float adam_one(float p, float g, float& m, float& v, const AdamArg& a) {
+  m = a.beta1 * m + (1.f - a.beta1) * g;
+  v = a.beta2 * v + (1.f - a.beta2) * g * g;
+  const float mhat = m / a.bc1, vhat = v / a.bc2;
+  return p - a.lr * (mhat / (sqrtf(vhat) + a.eps) + a.wd * p);
+}
+
+// One block per output channel.  g_w holds d(loss)/d(w_hat) on entry; the
+// straight-through mask and the step-size gradient (row reduction) are formed
+// here, from the weights and the step before their update.
+__global__ void adam_matrix_k(float* __restrict__ w, float* __restrict__ sw, float* __restrict__ g_w, float* __restrict__ g_sw,
+                              float* __restrict__ m_w, float* __restrict__ v_w, float* __restrict__ m_sw, float* __restrict__ v_sw,
+                              int K, float qp, int on, AdamArg a, int write_grads) {
+  __shared__ float red[17];
+  const int n = blockIdx.x;
+  const float s = on ? sw[n] : 1.f;
+  float acc = 0.f;
+  AdamArg aw = a;
+  for (int k = threadIdx.x; k < K; k += blockDim.x) {
+    const size_t i = (size_t)n * K + k;
+    const float x = w[i];
+    float g = g_w[i];
+    if (on) {
+      const float v = __fdiv_rn(x, s);
+      const bool in = (v >= -qp) && (v <= qp);
+      const float c = rintf(fminf(fmaxf(v, -qp), qp));
+      acc += g * (c - (in ? v : 0.f));
+      g = in ? g : 0.f;
+      if (write_grads) g_w[i] = g;
+    }
+    float m = m_w[i], vv = v_w[i];
+    w[i] = adam_one(x, g, m, vv, aw);
+    m_w[i] = m;
+    v_w[i] = vv;
+  }
+  if (on) {
+    acc = block_sum(acc, red);
+    if (threadIdx.x == 0) {
+      if (write_grads) g_sw[n] = acc;
+      AdamArg as = a;
+      as.wd = 0.f;
+      float m = m_sw[n], vv = v_sw[n];
+      const float ns = adam_one(s, acc, m, vv, as);
+      sw[n] = fmaxf(ns, a.floor);
+      m_sw[n] = m;
+      v_sw[n] = vv;
+    }
+  } else if (write_grads && threadIdx.x == 0) {
+    g_sw[n] = 0.f;
+  }
+}
+void adam_matrix(float* w, float* sw, float* g_w, float* g_sw, float* m_w, float* v_w, float* m_sw, float* v_sw, int N, int K,
+                 int bits, AdamArg a, int write_grads, hipStream_t st) {
+  const int on = bits > 0;
+  const float qp = on ? (float)((1 << (bits - 1)) - 1) : 0.f;
+  hipLaunchKernelGGL(adam_matrix_k, dim3(N), dim3(256), 0, st, w, sw, g_w, g_sw, m_w, v_w, m_sw, v_sw, K, qp, on, a, write_grads);
+}
+
+__global__ void adam_vector_k(float* __restrict__ p, const float* __restrict__ g, float* __restrict__ m, float* __restrict__ v,
+                              int64_t n, AdamArg a, int clamp) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    float mm = m[i], vv = v[i];
+    float np_ = adam_one(p[i], g[i], mm, vv, a);
+    if (clamp) np_ = fmaxf(np_, a.floor);
+    p[i] = np_;
+    m[i] = mm;
+    v[i] = vv;
+  }
+}
+void adam_vector(float* p, const float* g, float* m, float* v, int64_t n, AdamArg a, int clamp, hipStream_t st) {
+  int g_ = (int)((n + 255) / 256);
+  if (g_ > 4096) g_ = 4096;
+  if (g_ < 1) g_ = 1;
+  hipLaunchKernelGGL(adam_vector_k, dim3(g_), dim3(256), 0, st, p, g, m, v, n, a, clamp);
+}
+
+}  // namespace mrem

@@ -1,0 +1,127 @@
+// Host-side launchers of the gfx950 kernels.  Tensors whose element type depends
+// on the activation storage type are passed as void* together with `dt`
+// (0 = bfloat16, 1 = fp32).  Every launcher only enqueues work on `st`.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace mrem {
+
+enum { DT_BF16 = 0, DT_F32 = 1 };
+inline size_t dt_size(int dt) { return dt == DT_BF16 ? 2 : 4; }
+
+// One quantizer as the kernels see it: step and offset live in device memory
+// (they are trained), the integer range is a launch constant.
+struct QArg {
+  const float* s = nullptr;  // device scalar
+  const float* z = nullptr;  // device scalar or null (0)
+  float qn = 0.f, qp = 0.f;
+  int on = 0;
+};
+
+// out[m,n] = acc * (alpha * col_scale[n]) + beta * (col_vec[n] + row_vec[m]) + bias[n]
+// alpha/beta are device scalars (null: alpha = 1, beta = 0); vectors may be null.
+// gelu: out = round(gelu(round(out))) in the storage type.  out_f32: C is fp32.
+struct Epilogue {
+  const float* alpha = nullptr;
+  const float* col_scale = nullptr;
+  const float* beta = nullptr;
+  const float* col_vec = nullptr;
+  const float* row_vec = nullptr;
+  const float* bias = nullptr;
+  int gelu = 0;
+  int out_f32 = 0;
+};
+
+// C[M,N] = A[M,K] * B[N,K]^T  (both operands contiguous along K)
+void gemm_nt(int dt, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
+             const Epilogue& e, hipStream_t st);
+
+// ---- weights ------------------------------------------------------------------
+void weight_quantize_i8(const float* w, float* scale, int8_t* codes, int64_t N, int64_t K, int bits, int init_scale,
+                        hipStream_t st);
+void weight_step_init(const float* w, float* scale, int64_t N, int64_t K, int bits, hipStream_t st);
+// codes[N,K] (integer-valued, storage type), what_t[K,N] = round(s*q) transposed,
+// zcorr[N] = s[n] * sum_k q[n,k].  bits = 0: codes = round(w), what_t = round(w)^T, zcorr = 0.
+void weight_prepare(int dt, const float* w, const float* sw, int N, int K, int bits, void* codes, void* what_t,
+                    float* zcorr, hipStream_t st);
+void convert_f32(int dt, const float* src, void* dst, int64_t n, hipStream_t st);
+
+// ---- elementwise / normalisation ------------------------------------------------
+void act_quantize(int dt, const void* a, void* codes, int64_t n, QArg q, hipStream_t st);
+void gelu_quantize(int dt, const void* u, void* codes, int64_t n, QArg q, hipStream_t st);
+// du = dgh * inside(g) * gelu'(u); partials[grid] receive the step-size gradient terms
+int gelu_quant_bwd(int dt, const void* dgh, const void* u, void* du, int64_t n, QArg q, float* partials, hipStream_t st);
+// d_out = d_q * inside(a) (d_out may be null); partials[grid]: step-size gradient terms
+int quant_bwd(int dt, const void* d_q, const void* a, void* d_out, int64_t n, QArg q, float* partials, hipStream_t st);
+// partial sums of d_q * (code - v*inside) only (layer-0 input quantizer)
+int quant_bwd_reduce(int dt, const void* d_q, const void* a, int64_t n, QArg q, float* partials, hipStream_t st);
+
+// y = LN(x + r) * gamma + beta ; optional codes of y ; mean/rstd saved
+void ln_fwd(int dt, const void* x, const void* r, const float* gamma, const float* beta, void* y, void* ycodes, QArg q,
+            float* mu, float* rstd, int T, int H, float eps, hipStream_t st);
+// dy = d_a + d_b + d_q * inside(a_q)   (any of the three may be null)
+// dr = LN backward of dy through LN(x + r); partials[nparts][3H+1]: dgamma, dbeta, colsum(dr), ds
+int ln_bwd(int dt, const void* d_a, const void* d_b, const void* d_q, const void* a_q, QArg q, const void* x,
+           const void* r, const float* mu, const float* rstd, const float* gamma, void* dr, float* partials, int T,
+           int H, hipStream_t st);
+int ln_bwd_parts(int T);
+
+// loss partials + gradient 2*(fq - ffp)*scale ; returns number of partials
+int mse_loss_grad(int dt, const void* fq, const void* ffp, void* grad, int64_t n, float scale, float* partials,
+                  hipStream_t st);
+
+// out[C,R] = in[R,C]^T ; partials[R/64][C] column sums of `in` when partials != null
+int transpose_colsum(int dt, const void* in, int R, int C, int ld_in, void* out, float* partials, hipStream_t st);
+
+// out_k[c] = scale * sum_p partials[p*width + begin_k + c]  for up to 4 segments
+struct ReduceSeg {
+  int begin = 0, len = 0;
+  float* out = nullptr;
+};
+void reduce_partials(const float* partials, int nparts, int width, const ReduceSeg* segs, int nsegs, float scale,
+                     hipStream_t st);
+void loss_total(float* loss_out, int n_layers, hipStream_t st);
+void fill_f32(float* p, float v, int64_t n, hipStream_t st);
+void axpby(int dt, const void* a, const void* b, float wa, float wb, void* out, int64_t n, hipStream_t st);
+
+// ---- attention -----------------------------------------------------------------
+struct AttnQ {
+  QArg q, k, p, v, c;
+};
+// three column sections of qkv[T,3H] with their own quantizers -> integer codes
+void qkv_quantize(int dt, const void* qkv, void* codes, int T_, int H, QArg q, QArg k, QArg v, hipStream_t st);
+// d_qkv = d_qkvh * inside ; partials[grid][3]: step-size gradient terms of q, k, v
+int qkv_quant_bwd(int dt, const void* d_qkvh, const void* qkv, void* d_qkv, int T_, int H, QArg q, QArg k, QArg v, float* partials,
+                  hipStream_t st);
+// codes [T,3H] (or raw values when the quantizers are off); ctx [T,H] stored context,
+// ctx_codes [T,H] its codes under quantizer c (null: skip); pmax_rows [B*nh*S] row
+// maxima of the probabilities (null: skip); seqlens may be null
+void attn_fwd(int dt, const void* codes, void* ctx, void* ctx_codes, const AttnQ& aq, const int32_t* seqlens, int B, int S, int nh,
+              int d, float* pmax_rows, hipStream_t st);
+// dctx [T,H]: gradient w.r.t. the (unquantized) context; writes d_qkvh [T,3H], the
+// gradient w.r.t. the quantized q, k, v; scratch_da, scratch_ph: [B*nh*S*S] fp32;
+// ds_rows [B*nh*S]: per-row step-size gradient terms of the probability quantizer
+void attn_bwd(int dt, const void* codes, const void* dctx, void* d_qkvh, const AttnQ& aq, const int32_t* seqlens, int B, int S, int nh,
+              int d, float* scratch_da, float* scratch_ph, float* ds_rows, hipStream_t st);
+
+// ---- calibration reductions -------------------------------------------------------
+// partials[grid][3]: max|a|, min(f(a)), max(f(a)) over a strided [rows, cols] view; f = gelu if gelu != 0
+int absminmax(int dt, const void* a, int rows, int cols, int ld, int gelu, float* partials, hipStream_t st);
+// mode 0: s = max|a| / qp ; mode 1: s = max / qp (z = 0) ; mode 2: z = min, s = (max - z) / qp
+void calib_finalize(const float* partials, int nparts, int mode, float qp, float* s_out, float* z_out, hipStream_t st);
+
+// ---- update ----------------------------------------------------------------------
+struct AdamArg {
+  float lr, beta1, beta2, eps, wd, bc1, bc2;  // bc = 1 - beta^t
+  float floor;                                // lower bound applied when clamp != 0
+};
+// one block per row n of w[N,K]: straight-through mask on dw_hat (in grads), row
+// reduction for the step gradient, AdamW on w[n,:] and on sw[n]
+void adam_matrix(float* w, float* sw, float* g_w, float* g_sw, float* m_w, float* v_w, float* m_sw, float* v_sw, int N,
+                 int K, int bits, AdamArg a, int write_grads, hipStream_t st);
+void adam_vector(float* p, const float* g, float* m, float* v, int64_t n, AdamArg a, int clamp, hipStream_t st);
+
+}  // namespace mrem

@@ -1,0 +1,87 @@
+"""Shared plumbing of the parity tests: builds the same seeded case for the CPU
+oracle (numpy, fp64) and for the HIP library (torch device tensors)."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional
+
+import numpy as np
+
+from oracle import mrem_oracle as O
+from paper_2109_15082_amd import synth
+
+MATRICES = ("w_qkv", "w_o", "w_1", "w_2")
+
+
+@dataclass
+class Case:
+    wl: synth.Workload
+    cfg: O.Config
+    teacher: List[Dict[str, np.ndarray]]      # fp64 views of what the GPU teacher holds
+    student: List[Dict[str, np.ndarray]]      # fp64, with steps and clip ranges
+    x: np.ndarray                             # [B,S,H] fp32 values representable in act dtype
+    seqlens: Optional[np.ndarray]
+    layers_f32: List[Dict[str, np.ndarray]]   # the generator's fp32 parameters (teacher vector contents)
+
+
+def rel_err(a, ref) -> float:
+    a = np.asarray(a, dtype=np.float64).reshape(-1)
+    ref = np.asarray(ref, dtype=np.float64).reshape(-1)
+    return float(np.linalg.norm(a - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def make_case(wl: synth.Workload, weight_seed=1234, input_seed=5678, jitter=0.05, calib_seed=None, **cfg_kw) -> Case:
+    """Seeded case.  The student's weight steps are the oracle's initial steps and
+    its activation clip ranges come from the oracle's calibration (on the batch
+    drawn from calib_seed, default: the step's own batch)."""
+    layers, x, seqlens = synth.make_workload_inputs(wl, weight_seed, input_seed, jitter)
+    mode = "bf16" if wl.act_dtype == "bf16" else "f32"
+    cfg = O.Config(n_layers=wl.n_layers, hidden=wl.hidden, n_heads=wl.n_heads, ffn=wl.ffn, w_bits=wl.w_bits,
+                   a_bits=wl.a_bits, act_round=mode, **cfg_kw)
+    student = O.to_f64(layers)
+    teacher = O.to_f64(layers)
+    for lp in teacher:                          # the device teacher keeps its matrices in the activation type
+        for n in MATRICES:
+            lp[n] = synth.round_to_dtype(lp[n].astype(np.float32), wl.act_dtype).astype(np.float64)
+    for lp in student:
+        for n in MATRICES:
+            lp["s" + n] = O.weight_step_init(lp[n], wl.w_bits) if wl.w_bits else np.ones(lp[n].shape[0])
+        lp["s_a"], lp["z_a"] = np.ones(8), np.zeros(8)
+    if wl.a_bits:
+        xc = x if calib_seed is None else synth.make_hidden_states(wl.batch, wl.seq, wl.hidden, calib_seed, wl.act_dtype,
+                                                                    wl.outlier_frac, wl.outlier_scale)
+        cal = O.calibrate(xc.reshape(-1, wl.hidden), teacher, cfg, wl.batch, wl.seq, seqlens)
+        for lp, (s, z) in zip(student, cal):
+            lp["s_a"], lp["z_a"] = s.copy(), z.copy()
+    return Case(wl, cfg, teacher, student, x, seqlens, layers)
+
+
+def device_module(case: Case, **cfg_kw):
+    """MremModule loaded with the case's parameters (steps and ranges included)."""
+    import torch
+    from paper_2109_15082_amd import binding as B
+    wl = case.wl
+    c = case.cfg
+    mask = c.loss_layer_mask & 0xFFFFFFFF
+    mod = B.MremModule(wl.n_layers, wl.hidden, wl.n_heads, wl.ffn, wl.batch, wl.seq, act_dtype=wl.act_dtype,
+                       w_bits=wl.w_bits, a_bits=wl.a_bits, loss_layer_mask=mask, loss_mean=int(c.loss_mean),
+                       ln_eps=c.ln_eps, beta1=c.beta1, beta2=c.beta2, adam_eps=c.adam_eps, weight_decay=c.weight_decay,
+                       step_floor=c.step_floor, **cfg_kw)
+    # the teacher vector holds the unrounded fp32 weights; the library rounds the matrices to the
+    # activation type itself when it prepares its operand cache
+    mod.load(case.student, case.layers_f32)
+    return mod
+
+
+def device_inputs(case: Case):
+    import torch
+    wl = case.wl
+    td = torch.bfloat16 if wl.act_dtype == "bf16" else torch.float32
+    x = torch.from_numpy(case.x).to("cuda").to(td).contiguous()
+    sl = None if case.seqlens is None else torch.from_numpy(case.seqlens).to("cuda")
+    return x, sl
+
+
+def fresh_moments(student):
+    return ([{k: np.zeros_like(v) for k, v in lp.items()} for lp in student],
+            [{k: np.zeros_like(v) for k, v in lp.items()} for lp in student])
