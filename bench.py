@@ -1,0 +1,142 @@
+#!/usr/bin/env python3
+"""Throughput of one MREM module step (Algorithm 2) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_large_6l]
+
+A step = teacher forward + quantized forward + Eq. 3 loss + straight-through
+backward + AdamW update of weights and step sizes, on one synthetic batch that is
+already resident in HBM.  Prints ONE JSON line (see README / DESIGN for fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def step_flops(wl):
+    """Algorithmic flops of one step: the six matrix products of every layer (four
+    linear layers, Q*K^T and P*V), counted for the teacher forward, the quantized
+    forward and the two backward products (input and weight gradient) of each."""
+    T, H, F, S, d, nh = wl.tokens, wl.hidden, wl.ffn, wl.seq, wl.hidden // wl.n_heads, wl.n_heads
+    linear = 2.0 * T * (3 * H * H + H * H + 2 * H * F)
+    attn = 2.0 * wl.batch * nh * (2 * S * S * d)
+    return wl.n_layers * 4.0 * (linear + attn), wl.n_layers * 4.0 * linear
+
+
+def cpu_baseline(wl):
+    """The oracle as it stands, on the host cores, on a bounded sample: half of the
+    module's layers at the full batch; tokens/s is scaled to the full depth."""
+    import numpy as np
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import helpers as Hh
+    from oracle import mrem_oracle as O
+    from paper_2109_15082_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    batch = wl.batch
+    n_sample_layers = max(1, wl.n_layers // 2)
+    sample = synth.Workload(wl.name + "_sample", n_sample_layers, wl.hidden, wl.n_heads, wl.ffn, wl.seq, batch, act_dtype=wl.act_dtype,
+                            w_bits=wl.w_bits, a_bits=wl.a_bits, outlier_frac=wl.outlier_frac,
+                            seqlen_lo=wl.seqlen_lo, seqlen_hi=wl.seqlen_hi)
+    case = Hh.make_case(sample)
+    xo = case.x.reshape(-1, wl.hidden).astype(np.float64)
+    m, v = Hh.fresh_moments(case.student)
+    t0 = time.perf_counter()
+    O.module_step(xo, xo, case.teacher, case.student, m, v, 1, 1e-4, case.cfg, sample.batch, sample.seq, case.seqlens)
+    dt = time.perf_counter() - t0
+    value = sample.tokens / (dt * wl.n_layers / n_sample_layers)
+    return {"value": value, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"one full step of a {n_sample_layers}-layer module (of {wl.n_layers} layers) at the full batch {batch} x seq "
+                      f"{wl.seq} ({sample.tokens} tokens) in {dt:.2f} s, scaled by {n_sample_layers}/{wl.n_layers} to the module depth"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="bert_large_6l")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one module step on ONE GPU (the paper's per-module model parallelism reduces to "
+              "one module per device); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2109_15082_amd import synth, binding as B
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.workload]
+    layers, x_np, seqlens = synth.make_workload_inputs(wl)
+    mod = B.MremModule(wl.n_layers, wl.hidden, wl.n_heads, wl.ffn, wl.batch, wl.seq, act_dtype=wl.act_dtype,
+                       w_bits=wl.w_bits, a_bits=wl.a_bits)
+    mod.load(layers, layers)
+    td = torch.bfloat16 if wl.act_dtype == "bf16" else torch.float32
+    x = torch.from_numpy(x_np).cuda().to(td).contiguous()
+    sl = None if seqlens is None else torch.from_numpy(seqlens).cuda()
+    mod.init_steps()
+    mod.calibrate(x, sl)
+    out_fp, out_q = mod.new_outputs(wl.batch, wl.seq)
+    lr0, total = 1e-4, args.steps + args.warmup
+    torch.cuda.synchronize()
+
+    t = 0
+    for _ in range(args.warmup):
+        mod.step(x, x, lr0 * (1 - t / total), sl, out_fp, out_q)
+        t += 1
+    torch.cuda.synchronize()
+    B.mrem_profile_gemm_begin()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        mod.step(x, x, lr0 * (1 - t / total), sl, out_fp, out_q)
+        t += 1
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    gemm_ms, gemm_flops, gemm_launches = B.mrem_profile_gemm_end()
+    losses = mod.loss.cpu().numpy()
+    assert np.isfinite(losses).all(), losses
+
+    ms_per_step = dt * 1e3 / args.steps
+    tokens_per_s = wl.tokens * args.steps / dt
+    flops_total, flops_linear = step_flops(wl)
+    achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    result = {
+        "metric": "module fwd+bwd tokens/s at BERT-large W4A8",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.act_dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "n_layers": wl.n_layers, "hidden": wl.hidden, "n_heads": wl.n_heads, "ffn": wl.ffn,
+                   "seq_len": wl.seq, "batch": wl.batch, "w_bits": wl.w_bits, "a_bits": wl.a_bits,
+                   "tokens_per_step": wl.tokens, "step_tflop": flops_total / 1e12, "loss_last_step": float(losses[0])},
+        "roofline": {"bound": "mfma", "kernel": "gemm_nt (all matrix products of the linear layers)",
+                     "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "launches_per_step": gemm_launches / args.steps,
+                     "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
+                     "gemm_ms_per_step": gemm_ms / args.steps,
+                     "flops_per_launch": gemm_flops / max(gemm_launches, 1)},
+        "step_tflops": flops_total / 1e12 / (ms_per_step * 1e-3),
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl)
+    mod.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

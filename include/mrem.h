@@ -200,6 +200,16 @@ mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* adam_m, float*
 mrem_status mrem_mix_inputs(mrem_ctx* ctx, const void* x_fp, const void* x_q, float lambda, void* out, int64_t n,
                             void* hip_stream);
 
+/*
+ * Measurement aid (not part of the method): between mrem_profile_gemm_begin() and
+ * mrem_profile_gemm_end() every matrix-product kernel launch of this process is
+ * bracketed by a pair of HIP events on its stream.  _end waits for them and returns
+ * the summed kernel time in milliseconds (host double), the summed 2*M*N*K of those
+ * launches and their number.  Not thread-safe; events are host-side objects.
+ */
+void mrem_profile_gemm_begin(void);
+mrem_status mrem_profile_gemm_end(double* ms /*host*/, double* flops /*host*/, int64_t* launches /*host*/);
+
 #ifdef __cplusplus
 }
 #endif

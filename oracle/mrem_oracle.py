@@ -124,11 +124,10 @@ def unsigned_range(bits: int) -> Tuple[int, int]:
 
 def round_bf16(x: np.ndarray) -> np.ndarray:
     """fp64 -> fp32 -> bfloat16 (round-to-nearest-even), returned as fp64."""
-    f = np.asarray(x, dtype=np.float64).astype(np.float32)
-    u = f.view(np.uint32).astype(np.uint64)
-    lsb = (u >> np.uint64(16)) & np.uint64(1)
-    u = (u + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)
-    return u.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(x))
+    u = np.asarray(x, dtype=np.float64).astype(np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    u = (u + np.uint32(0x7FFF) + lsb) & np.uint32(0xFFFF0000)
+    return u.view(np.float32).astype(np.float64).reshape(np.shape(x))
 
 
 def round_store(x: np.ndarray, mode: Optional[str]) -> np.ndarray:
@@ -192,6 +191,23 @@ def fake_quant_backward(d_xhat, q, v, inside, reduce_axes=None):
     ds_elem = d_xhat * (q - v * inside)
     ds = ds_elem.sum() if reduce_axes is None else ds_elem.sum(axis=reduce_axes)
     return dx, ds
+
+
+def decision_margin(v, qn: int, qp: int, nonnegative: bool = False) -> float:
+    """Distance, in units of one quantization step, of the ratios v from the
+    points where the quantizer is discontinuous: a rounding tie k + 1/2 inside
+    the range, or a clip bound (where the straight-through mask switches).  A
+    perturbation of every v smaller than this changes no code and no mask.
+    Used by tests to choose seeded inputs on which a comparison at fp32
+    rounding level is meaningful."""
+    v = np.asarray(v, dtype=np.float64)
+    inside = (v > qn) & (v < qp)
+    frac = v - np.floor(v)
+    tie = np.where(inside, np.abs(frac - 0.5), np.inf)
+    # nonnegative: the quantized values cannot be below the lower bound 0 (softmax
+    # probabilities), so that bound is never crossed
+    edge = np.abs(v - qp) if nonnegative else np.minimum(np.abs(v - qn), np.abs(v - qp))
+    return float(min(tie.min(), edge.min()))
 
 
 def weight_step_init(w, bits: int) -> np.ndarray:
@@ -296,9 +312,11 @@ class _AQ:
         self.decide32 = cfg.act_round is not None
 
     def fwd(self, x):
+        self.margin = np.inf
         if not self.enabled:
             return x
         xh, self.q, self.v, self.inside = fake_quant_forward(x, self.s, self.qn, self.qp, self.z, self.decide32)
+        self.margin = decision_margin(self.v, self.qn, self.qp, nonnegative=(self.idx == AQ_P))
         return xh
 
     def bwd(self, d_xhat):

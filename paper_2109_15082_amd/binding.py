@@ -29,7 +29,8 @@ FIELD_ID = {n: i for i, n in enumerate(FIELDS)}
 EXPORTS = ("mrem_create", "mrem_destroy", "mrem_last_error", "mrem_param_count", "mrem_teacher_count",
            "mrem_param_offset", "mrem_param_size", "mrem_workspace_bytes", "mrem_teacher_cache_bytes",
            "mrem_quantize", "mrem_module_init_steps", "mrem_teacher_prepare", "mrem_module_calibrate",
-           "mrem_module_forward", "mrem_module_step", "mrem_mix_inputs")
+           "mrem_module_forward", "mrem_module_step", "mrem_mix_inputs", "mrem_profile_gemm_begin",
+           "mrem_profile_gemm_end")
 
 
 class mrem_config(C.Structure):
@@ -74,6 +75,12 @@ _lib.mrem_module_step.argtypes = [_vp, _vp, _vp, _vp, _i64, _f32, _vp, _vp, _vp,
 _lib.mrem_module_step.restype = C.c_int
 _lib.mrem_mix_inputs.argtypes = [_vp, _vp, _vp, _f32, _vp, _i64, _vp]
 _lib.mrem_mix_inputs.restype = C.c_int
+
+
+_lib.mrem_profile_gemm_begin.argtypes = []
+_lib.mrem_profile_gemm_begin.restype = None
+_lib.mrem_profile_gemm_end.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i64)]
+_lib.mrem_profile_gemm_end.restype = C.c_int
 
 
 class MremError(RuntimeError):
@@ -183,6 +190,17 @@ def mrem_module_step(ctx, params, adam_m, adam_v, step_index, lr, teacher, teach
 
 def mrem_mix_inputs(ctx, x_fp, x_q, lam, out, n, stream=None) -> None:
     _check(_lib.mrem_mix_inputs(ctx, _ptr(x_fp), _ptr(x_q), lam, _ptr(out), n, _stream(stream)), ctx)
+
+
+def mrem_profile_gemm_begin() -> None:
+    _lib.mrem_profile_gemm_begin()
+
+
+def mrem_profile_gemm_end():
+    """(milliseconds, flops, launches) of the matrix-product kernels since _begin."""
+    ms, fl, n = C.c_double(), C.c_double(), _i64()
+    _check(_lib.mrem_profile_gemm_end(C.byref(ms), C.byref(fl), C.byref(n)))
+    return ms.value, fl.value, n.value
 
 
 # ------------------------------------------------------------------------------

@@ -603,3 +603,9 @@ extern "C" mrem_status mrem_mix_inputs(mrem_ctx* ctx, const void* x_fp, const vo
   axpby(ctx->dt, x_fp, x_q, lambda, 1.f - lambda, out, n, (hipStream_t)hip_stream);
   return finish(ctx, "mrem_mix_inputs");
 }
+
+extern "C" void mrem_profile_gemm_begin(void) { gemm_profile_begin(); }
+extern "C" mrem_status mrem_profile_gemm_end(double* ms, double* flops, int64_t* launches) {
+  if (!ms || !flops || !launches) return fail(nullptr, MREM_EINVAL, "mrem_profile_gemm_end: null argument");
+  return gemm_profile_end(ms, flops, launches) == 0 ? MREM_OK : fail(nullptr, MREM_EHIP, "mrem_profile_gemm_end: event query failed");
+}

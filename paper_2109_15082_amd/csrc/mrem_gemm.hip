@@ -5,7 +5,43 @@
 #include "mrem_common.h"
 #include "mrem_kernels.h"
 
+#include <vector>
+
 namespace mrem {
+
+// ---- optional timing of every product launch with HIP events (measurement aid) ----
+namespace {
+struct GemmRecord {
+  hipEvent_t e0, e1;
+  double flops;
+};
+bool g_prof_on = false;
+std::vector<GemmRecord> g_prof;
+}  // namespace
+
+void gemm_profile_begin() {
+  for (auto& r : g_prof) { hipEventDestroy(r.e0); hipEventDestroy(r.e1); }
+  g_prof.clear();
+  g_prof_on = true;
+}
+int gemm_profile_end(double* ms, double* flops, int64_t* launches) {
+  g_prof_on = false;
+  double t = 0.0, f = 0.0;
+  int rc = 0;
+  for (auto& r : g_prof) {
+    float e = 0.f;
+    if (hipEventSynchronize(r.e1) != hipSuccess || hipEventElapsedTime(&e, r.e0, r.e1) != hipSuccess) rc = -1;
+    t += e;
+    f += r.flops;
+    hipEventDestroy(r.e0);
+    hipEventDestroy(r.e1);
+  }
+  *ms = t;
+  *flops = f;
+  *launches = (int64_t)g_prof.size();
+  g_prof.clear();
+  return rc;
+}
 
 struct EpiVals {
   float alpha, beta;
@@ -73,8 +109,27 @@ __global__ void gemm_nt_simt_k(const TA* __restrict__ A, int lda, const TA* __re
     }
 }
 
+static void gemm_nt_launch(int dt, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
+                           const Epilogue& e, hipStream_t st);
+
 void gemm_nt(int dt, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
              hipStream_t st) {
+  if (!g_prof_on) {
+    gemm_nt_launch(dt, A, lda, B, ldb, C, ldc, M, N, K, e, st);
+    return;
+  }
+  GemmRecord r;
+  r.flops = 2.0 * (double)M * (double)N * (double)K;
+  hipEventCreate(&r.e0);
+  hipEventCreate(&r.e1);
+  hipEventRecord(r.e0, st);
+  gemm_nt_launch(dt, A, lda, B, ldb, C, ldc, M, N, K, e, st);
+  hipEventRecord(r.e1, st);
+  g_prof.push_back(r);
+}
+
+static void gemm_nt_launch(int dt, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
+                           const Epilogue& e, hipStream_t st) {
   dim3 g((N + 63) / 64, (M + 63) / 64);
   if (dt == DT_BF16) {
     if (e.out_f32)

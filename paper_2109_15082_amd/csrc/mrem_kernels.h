@@ -39,6 +39,10 @@ struct Epilogue {
 void gemm_nt(int dt, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
              const Epilogue& e, hipStream_t st);
 
+// Timing of every gemm_nt launch with a pair of HIP events on its stream.
+void gemm_profile_begin();
+int gemm_profile_end(double* ms, double* flops, int64_t* launches);
+
 // ---- weights ------------------------------------------------------------------
 void weight_quantize_i8(const float* w, float* scale, int8_t* codes, int64_t N, int64_t K, int bits, int init_scale,
                         hipStream_t st);

@@ -85,3 +85,24 @@ def device_inputs(case: Case):
 def fresh_moments(student):
     return ([{k: np.zeros_like(v) for k, v in lp.items()} for lp in student],
             [{k: np.zeros_like(v) for k, v in lp.items()} for lp in student])
+
+
+def forward_margin(case: Case) -> float:
+    """Smallest relative distance of any activation-quantizer ratio of the quantized
+    forward pass to a rounding tie or clip bound (oracle only)."""
+    wl = case.wl
+    xo = case.x.reshape(-1, wl.hidden).astype(np.float64)
+    _, caches = O.module_forward(xo, case.student, case.cfg, wl.batch, wl.seq, case.seqlens, quant=True)
+    return min(a.margin for c in caches for a in c["aq"])
+
+
+def make_case_with_margin(wl: synth.Workload, min_margin: float, max_tries: int = 400, calib_seed: int = 777, **kw) -> Case:
+    """First input seed (5678, 5679, ...) whose quantized forward pass keeps every
+    ratio at least min_margin (relative) away from a discontinuity of the quantizer.
+    The clip ranges are calibrated on a different batch so that no element sits
+    exactly on a clip bound."""
+    for i in range(max_tries):
+        case = make_case(wl, input_seed=5678 + i, calib_seed=calib_seed, **kw)
+        if forward_margin(case) >= min_margin:
+            return case
+    raise RuntimeError(f"no seed with margin {min_margin} in {max_tries} tries")

@@ -88,27 +88,42 @@ def test_quantize_rejects_bad_arguments(B):
 # whole step
 # --------------------------------------------------------------------------------
 
-CASES = {
-    # the small workload of the benchmark definition (fp32 check mode)
+# fp32 check mode.  The quantizer is discontinuous at rounding ties and clip bounds, and
+# the two sides differ at fp32 rounding level, so these cases run on the first seeded
+# input for which the oracle reports that every quantizer ratio of the forward pass is at
+# least MARGIN quantization steps away from a discontinuity (helpers.make_case_with_margin).
+MARGIN = 2e-5
+CASES_F32 = {
+    # the small workload of the benchmark definition
     "tiny_f32": W("tiny_f32", 1, 64, 2, 256, 32, 4, act_dtype="f32"),
+    # several 64-wide tiles with ragged tails in every product (T = 80, H = 72, 3H = 216, F = 136), key padding, head dim 24
+    "ragged_f32": W("ragged_f32", 1, 72, 3, 136, 40, 2, act_dtype="f32", seqlen_lo=20, seqlen_hi=40),
+    # two layers: the backward pass crosses a layer boundary and its input quantizer
+    "two_layer_f32": W("two_layer_f32", 2, 64, 2, 128, 24, 2, act_dtype="f32"),
+    "d128_f32": W("d128_f32", 1, 256, 2, 64, 24, 1, act_dtype="f32"),
+    # other bit-widths of Tables 1-3
+    "w2a8_f32": W("w2a8_f32", 1, 64, 2, 128, 16, 2, act_dtype="f32", w_bits=2),
+    "w2a4_f32": W("w2a4_f32", 1, 64, 2, 128, 16, 2, act_dtype="f32", w_bits=2, a_bits=4),
+    "w8a8_f32": W("w8a8_f32", 1, 64, 2, 128, 16, 2, act_dtype="f32", w_bits=8),
+}
+# bf16 storage: a stored value that rounds the other way is a 2^-8 relative change of one
+# element, well inside the 2e-2 tolerance, so plain seeds are used.
+CASES_BF16 = {
     "tiny_bf16": W("tiny_bf16", 1, 64, 2, 256, 32, 4, act_dtype="bf16"),
     # several tiles and ragged tails (T = 240, S = 80), key padding, two layers, head dim 64
-    "mid_f32": W("mid_f32", 2, 128, 2, 512, 80, 3, act_dtype="f32", seqlen_lo=40, seqlen_hi=80),
     "mid_bf16": W("mid_bf16", 2, 128, 2, 512, 80, 3, act_dtype="bf16", seqlen_lo=40, seqlen_hi=80, outlier_frac=0.02),
     # MFMA-tile-aligned shapes (T = 512), head dim 32, three layers
     "aligned_bf16": W("aligned_bf16", 3, 256, 8, 1024, 128, 4, act_dtype="bf16", outlier_frac=0.01),
-    # other bit-widths of Tables 1-3
-    "w2a8_f32": W("w2a8_f32", 1, 64, 2, 256, 32, 4, act_dtype="f32", w_bits=2),
-    "w8a8_bf16": W("w8a8_bf16", 2, 128, 2, 512, 64, 2, act_dtype="bf16", w_bits=8),
-    "w2a4_f32": W("w2a4_f32", 1, 64, 2, 256, 32, 4, act_dtype="f32", w_bits=2, a_bits=4),
-    "w4a8_d128_f32": W("w4a8_d128_f32", 1, 256, 2, 256, 48, 2, act_dtype="f32"),
 }
+# fp32 mode at several tiles without the margin guarantee (about 7e5 quantized values:
+# no seed keeps all of them away from ties): a looser bound
+MID_F32 = W("mid_f32", 2, 128, 2, 512, 80, 3, act_dtype="f32", seqlen_lo=40, seqlen_hi=80)
 
 
-def _compare_step(B, wl, lr=1e-3, **cfg_kw):
+def _compare_step(B, wl, lr=1e-3, case=None, tol=None, **cfg_kw):
     torch = _torch()
-    tol = TOL[wl.act_dtype]
-    case = Hh.make_case(wl, **cfg_kw)
+    tol = tol or TOL[wl.act_dtype]
+    case = case or Hh.make_case(wl, **cfg_kw)
     mod = Hh.device_module(case)
     x, sl = Hh.device_inputs(case)
     xo = case.x.reshape(-1, wl.hidden).astype(np.float64)
@@ -153,15 +168,49 @@ def _compare_step(B, wl, lr=1e-3, **cfg_kw):
     return dict(report)
 
 
-@pytest.mark.parametrize("name", list(CASES))
-def test_step_matches_oracle(B, name):
-    _compare_step(B, CASES[name])
+@pytest.mark.parametrize("name", list(CASES_F32))
+def test_step_matches_oracle_fp32(B, name):
+    wl = CASES_F32[name]
+    # With 8-bit weights |f^ - f| is about 5e-4 |f|, so the loss gradient 2 (f^ - f) / n formed from two fp32
+    # tensors carries a relative error of 2^-23 |f| / |f^ - f|, about 2.5e-4, into every gradient: 1e-3 there.
+    tol = 1e-3 if wl.w_bits == 8 else None
+    _compare_step(B, wl, case=Hh.make_case_with_margin(wl, MARGIN), tol=tol)
+
+
+@pytest.mark.parametrize("name", list(CASES_BF16))
+def test_step_matches_oracle_bf16(B, name):
+    _compare_step(B, CASES_BF16[name])
+
+
+def test_step_fp32_several_tiles_no_margin(B):
+    _compare_step(B, MID_F32, tol=1e-2)
+
+
+def test_w8a8_bf16_forward_and_loss(B):
+    """W8A8 with bf16 storage: the reconstruction error f^ - f is of the size of the
+    bf16 rounding of f itself, so its gradient is not a well-conditioned quantity
+    to compare in this mode (the fp32 case above covers it); outputs and loss are."""
+    torch = _torch()
+    wl = W("w8a8_bf16", 2, 128, 2, 512, 64, 2, act_dtype="bf16", w_bits=8)
+    case = Hh.make_case(wl)
+    mod = Hh.device_module(case)
+    x, sl = Hh.device_inputs(case)
+    xo = case.x.reshape(-1, wl.hidden).astype(np.float64)
+    res = O.module_grads(xo, xo, case.teacher, case.student, case.cfg, wl.batch, wl.seq, case.seqlens)
+    ofp, oq = mod.step(x, x, 1e-4, sl)
+    torch.cuda.synchronize()
+    for l in range(wl.n_layers):
+        assert Hh.rel_err(ofp[l].float().cpu().numpy(), res.f_fp[l]) <= 2e-2
+        assert Hh.rel_err(oq[l].float().cpu().numpy(), res.f_q[l]) <= 2e-2
+    assert abs(mod.loss[0].item() / res.loss - 1) <= 2e-2
+    mod.close()
 
 
 def test_step_loss_options(B):
     """Last layer only in Eq. 3, and the raw sum of squares instead of the mean."""
-    _compare_step(B, CASES["mid_f32"], loss_layer_mask=0b10)
-    _compare_step(B, CASES["mid_f32"], loss_mean=False, lr=1e-4)
+    wl = CASES_F32["two_layer_f32"]
+    _compare_step(B, wl, case=Hh.make_case_with_margin(wl, MARGIN, loss_layer_mask=0b10))
+    _compare_step(B, wl, case=Hh.make_case_with_margin(wl, MARGIN, loss_mean=False), lr=1e-4)
 
 
 def test_quantizers_off_gives_zero_loss(B):
@@ -189,7 +238,7 @@ def test_quantizers_off_gives_zero_loss(B):
 
 def test_forward_entry_matches_step_outputs_and_is_deterministic(B):
     torch = _torch()
-    wl = CASES["mid_bf16"]
+    wl = CASES_BF16["mid_bf16"]
     case = Hh.make_case(wl)
     mod = Hh.device_module(case)
     x, sl = Hh.device_inputs(case)
@@ -211,8 +260,7 @@ def test_forward_entry_matches_step_outputs_and_is_deterministic(B):
 
 def test_calibrate_and_init_steps_match_oracle(B):
     torch = _torch()
-    for name in ("mid_f32", "mid_bf16"):
-        wl = CASES[name]
+    for name, wl in (("mid_f32", MID_F32), ("mid_bf16", CASES_BF16["mid_bf16"])):
         case = Hh.make_case(wl)
         mod = Hh.device_module(case)
         x, sl = Hh.device_inputs(case)
@@ -229,7 +277,7 @@ def test_calibrate_and_init_steps_match_oracle(B):
                 assert np.array_equal(got[l][k], ref[l][k].astype(np.float32)), (name, l, k)
             np.testing.assert_allclose(got[l]["s_a"], ref[l]["s_a"], rtol=1e-5)
             np.testing.assert_allclose(got[l]["z_a"], ref[l]["z_a"], rtol=1e-5, atol=1e-7)
-            assert np.array_equal(got[l]["w_1"], ref[l]["w_1"].astype(np.float32))
+            assert np.array_equal(got[l]["w_1"], ref[l]["w_1"].astype(np.float32).reshape(-1))
         mod.close()
 
 
@@ -253,7 +301,7 @@ def test_mix_inputs(B):
 def test_loss_decreases_over_steps(B):
     """Algorithm 2 iterated on the device: the reconstruction loss of a fixed batch goes down."""
     torch = _torch()
-    wl = CASES["mid_bf16"]
+    wl = CASES_BF16["mid_bf16"]
     case = Hh.make_case(wl)
     mod = Hh.device_module(case)
     x, sl = Hh.device_inputs(case)
