@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmrem.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["mrem_api.hip", "mrem_elem.hip", "mrem_gemm.hip", "mrem_attn.hip"]
+SOURCES = ["mrem_api.hip", "mrem_elem.hip", "mrem_gemm.hip", "mrem_attn.hip", "mrem_attn_mfma.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -39,7 +39,7 @@ def build(verbose: bool = True) -> str:
                 print("\n".join(lines), file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", OUT]
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -95,7 +95,7 @@ struct Bump {
 
 struct LayerWs {
   size_t wcodes[4], what_t[4], zcorr[4];
-  size_t xcodes, qkv, qkvcodes, ctx, ctxcodes, o, x1, x1codes, u, gcodes, y, mu1, rstd1, mu2, rstd2;
+  size_t xcodes, qkv, qkvcodes, ctx, ctxcodes, o, x1, x1codes, u, gcodes, y, mu1, rstd1, mu2, rstd2, stat_m, stat_l;
 };
 
 struct Plan {
@@ -124,6 +124,7 @@ Plan make_plan(const mrem_ctx* c, int B, int S) {
     w.x1 = b.take(T * H * es); w.x1codes = b.take(T * H * es); w.u = b.take(T * F * es); w.gcodes = b.take(T * F * es);
     w.y = b.take(T * H * es);
     w.mu1 = b.take(T * 4); w.rstd1 = b.take(T * 4); w.mu2 = b.take(T * 4); w.rstd2 = b.take(T * 4);
+    w.stat_m = b.take((size_t)B * c->nh * S * 4); w.stat_l = b.take((size_t)B * c->nh * S * 4);
   }
   p.t_qkv = b.take(T * 3 * H * es); p.t_ctx = b.take(T * H * es); p.t_o = b.take(T * H * es); p.t_x1 = b.take(T * H * es);
   p.t_g = b.take(T * F * es); p.t_y = b.take(T * H * es); p.t_mu = b.take(T * 4); p.t_rstd = b.take(T * 4);
@@ -132,7 +133,8 @@ Plan make_plan(const mrem_ctx* c, int B, int S) {
   p.dgh = b.take(T * F * es); p.du = b.take(T * F * es); p.dqkvh = b.take(T * 3 * H * es); p.dqkv = b.take(T * 3 * H * es);
   const size_t widest = (3 * H > F ? 3 * H : F);
   p.tA = b.take(widest * T * es); p.tB = b.take(widest * T * es);
-  const size_t pp = (size_t)B * c->nh * S * S;
+  const size_t s_pad = ((size_t)S + 31) / 32 * 32;
+  const size_t pp = (size_t)B * c->nh * s_pad * s_pad;
   p.s_da = b.take(pp * 4); p.s_ph = b.take(pp * 4); p.ds_rows = b.take((size_t)B * c->nh * S * 4);
   p.pmax = b.take((size_t)B * c->nh * S * 4);
   size_t np = (size_t)ln_bwd_parts((int)T) * (3 * H + 1);
@@ -218,7 +220,11 @@ void student_forward(const Run& r, const float* params, const void* x_q, void* p
     student_linear(r, params, l, 0, r.at(w.xcodes), r.at(w.qkv));
     const AttnQ aq = make_attn_q(c, params, l, true);
     qkv_quantize(c->dt, r.at(w.qkv), r.at(w.qkvcodes), T, H, aq.q, aq.k, aq.v, r.st);
-    attn_fwd(c->dt, r.at(w.qkvcodes), r.at(w.ctx), r.at(w.ctxcodes), aq, r.seqlens, r.B, r.S, c->nh, c->d, nullptr, r.st);
+    if (attn_mfma_ok(c->dt, r.S, c->d))
+      attn_fwd_mfma(r.at(w.qkvcodes), r.at(w.ctx), r.at(w.ctxcodes), aq, r.seqlens, r.B, r.S, c->nh, nullptr, r.at<float>(w.stat_m),
+                    r.at<float>(w.stat_l), r.st);
+    else
+      attn_fwd(c->dt, r.at(w.qkvcodes), r.at(w.ctx), r.at(w.ctxcodes), aq, r.seqlens, r.B, r.S, c->nh, c->d, nullptr, r.st);
     student_linear(r, params, l, 1, r.at(w.ctxcodes), r.at(w.o));
     ln_fwd(c->dt, x, r.at(w.o), base + c->foff[MREM_F_LN1_G], base + c->foff[MREM_F_LN1_B], r.at(w.x1), r.at(w.x1codes),
            make_q(c, params, l, 6), r.at<float>(w.mu1), r.at<float>(w.rstd1), T, H, c->cfg.ln_eps, r.st);
@@ -261,8 +267,12 @@ void teacher_forward(const Run& r, const float* teacher, const void* cache, cons
       calib(l, 2, q + (size_t)H * es, c->dt, T, H, 3 * H, 0, 0);
       calib(l, 4, q + (size_t)2 * H * es, c->dt, T, H, 3 * H, 0, 0);
     }
-    attn_fwd(c->dt, r.at(r.p.t_qkv), r.at(r.p.t_ctx), nullptr, AttnQ(), r.seqlens, r.B, r.S, c->nh, c->d,
-             calib_params ? r.at<float>(r.p.pmax) : nullptr, r.st);
+    if (attn_mfma_ok(c->dt, r.S, c->d))
+      attn_fwd_mfma(r.at(r.p.t_qkv), r.at(r.p.t_ctx), nullptr, AttnQ(), r.seqlens, r.B, r.S, c->nh,
+                    calib_params ? r.at<float>(r.p.pmax) : nullptr, nullptr, nullptr, r.st);
+    else
+      attn_fwd(c->dt, r.at(r.p.t_qkv), r.at(r.p.t_ctx), nullptr, AttnQ(), r.seqlens, r.B, r.S, c->nh, c->d,
+               calib_params ? r.at<float>(r.p.pmax) : nullptr, r.st);
     if (calib_params) {
       calib(l, 3, r.at(r.p.pmax), DT_F32, 1, r.B * c->nh * r.S, r.B * c->nh * r.S, 0, 1);
       calib(l, 5, r.at(r.p.t_ctx), c->dt, T, H, H, 0, 0);
@@ -384,11 +394,16 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
     }
     // attention
     const AttnQ aq = make_attn_q(c, params, l, true);
-    attn_bwd(c->dt, r.at(w.qkvcodes), r.at(r.p.dc), r.at(r.p.dqkvh), aq, r.seqlens, r.B, r.S, c->nh, c->d, r.at<float>(r.p.s_da),
-             r.at<float>(r.p.s_ph), r.at<float>(r.p.ds_rows), r.st);
     {
+      int n = r.B * c->nh * r.S;
+      if (attn_mfma_ok(c->dt, r.S, c->d))
+        n = attn_bwd_mfma(r.at(w.qkvcodes), r.at(r.p.dc), r.at(r.p.dqkvh), aq, r.seqlens, r.B, r.S, c->nh, r.at<float>(w.stat_m),
+                          r.at<float>(w.stat_l), r.at(r.p.s_ph), r.at(r.p.s_da), r.at<float>(r.p.ds_rows), r.st);
+      else
+        attn_bwd(c->dt, r.at(w.qkvcodes), r.at(r.p.dc), r.at(r.p.dqkvh), aq, r.seqlens, r.B, r.S, c->nh, c->d, r.at<float>(r.p.s_da),
+                 r.at<float>(r.p.s_ph), r.at<float>(r.p.ds_rows), r.st);
       ReduceSeg sg{0, 1, g + c->foff[MREM_F_S_A] + 3};
-      reduce_partials(r.at<float>(r.p.ds_rows), r.B * c->nh * r.S, 1, &sg, 1, 1.f, r.st);
+      reduce_partials(r.at<float>(r.p.ds_rows), n, 1, &sg, 1, 1.f, r.st);
     }
     {
       const int n = qkv_quant_bwd(c->dt, r.at(r.p.dqkvh), r.at(w.qkv), r.at(r.p.dqkv), T, H, aq.q, aq.k, aq.v, parts, r.st);

@@ -492,26 +492,41 @@ struct ReduceSegs {
   int n;
 };
 __global__ void reduce_partials_k(const float* __restrict__ partials, int nparts, int width, ReduceSegs segs, float scale) {
-  __shared__ float red[17];
-  // wide segments: one thread per column; scalar segments: the whole block cooperates
-  int base = 0;
+  // 256 threads = 64 columns x 4 groups of partial rows; the four group sums are added
+  // in group order, so the result does not depend on scheduling.
+  __shared__ float red[4][64];
+  __shared__ float sred[17];
+  const int col = threadIdx.x & 63, grp = threadIdx.x >> 6;
   for (int k = 0; k < segs.n; ++k) {
     const ReduceSeg sg = segs.s[k];
     if (sg.len == 1) {
       if (blockIdx.x == 0) {
         float t = 0.f;
         for (int p = threadIdx.x; p < nparts; p += blockDim.x) t += partials[(size_t)p * width + sg.begin];
-        t = block_sum(t, red);
+        t = block_sum(t, sred);
         if (threadIdx.x == 0) sg.out[0] = t * scale;
       }
-    } else {
-      for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < sg.len; c += gridDim.x * blockDim.x) {
-        float t = 0.f;
-        for (int p = 0; p < nparts; ++p) t += partials[(size_t)p * width + sg.begin + c];
-        sg.out[c] = t * scale;
-      }
+      continue;
     }
-    base += sg.len;
+    for (int c0 = blockIdx.x * 64; c0 < sg.len; c0 += gridDim.x * 64) {
+      const int c = c0 + col;
+      float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
+      if (c < sg.len) {
+        const float* src = partials + sg.begin + c;
+        int p = grp;
+        for (; p + 12 < nparts; p += 16) {
+          t0 += src[(size_t)p * width];
+          t1 += src[(size_t)(p + 4) * width];
+          t2 += src[(size_t)(p + 8) * width];
+          t3 += src[(size_t)(p + 12) * width];
+        }
+        for (; p < nparts; p += 4) t0 += src[(size_t)p * width];
+      }
+      red[grp][col] = (t0 + t1) + (t2 + t3);
+      __syncthreads();
+      if (grp == 0 && c < sg.len) sg.out[c] = ((red[0][col] + red[1][col]) + (red[2][col] + red[3][col])) * scale;
+      __syncthreads();
+    }
   }
 }
 void reduce_partials(const float* partials, int nparts, int width, const ReduceSeg* segs, int nsegs, float scale, hipStream_t st) {
@@ -519,7 +534,7 @@ void reduce_partials(const float* partials, int nparts, int width, const ReduceS
   s.n = nsegs;
   int maxlen = 1;
   for (int i = 0; i < nsegs; ++i) { s.s[i] = segs[i]; if (segs[i].len > maxlen) maxlen = segs[i].len; }
-  int g = (maxlen + 255) / 256;
+  int g = (maxlen + 63) / 64;
   hipLaunchKernelGGL(reduce_partials_k, dim3(g), dim3(256), 0, st, partials, nparts, width, s, scale);
 }
 

@@ -111,6 +111,16 @@ void attn_fwd(int dt, const void* codes, void* ctx, void* ctx_codes, const AttnQ
 void attn_bwd(int dt, const void* codes, const void* dctx, void* d_qkvh, const AttnQ& aq, const int32_t* seqlens, int B, int S, int nh,
               int d, float* scratch_da, float* scratch_ph, float* ds_rows, hipStream_t st);
 
+// Matrix-core versions (bf16, head dimension 64, 64 <= S <= 384).  The forward saves the
+// row maximum and row sum of the softmax (stat_m, stat_l: [B*nh*S], may be null); the
+// backward needs them, two bf16 scratch tiles of B*nh*s_pad^2 elements (s_pad = S rounded
+// up to 32) and returns the number of partial sums written to ds_parts.
+bool attn_mfma_ok(int dt, int S, int d);
+void attn_fwd_mfma(const void* codes, void* ctx, void* ctx_codes, const AttnQ& aq, const int32_t* seqlens, int B, int S, int nh,
+                   float* pmax_rows, float* stat_m, float* stat_l, hipStream_t st);
+int attn_bwd_mfma(const void* codes, const void* dctx, void* d_qkvh, const AttnQ& aq, const int32_t* seqlens, int B, int S, int nh,
+                  const float* stat_m, const float* stat_l, void* pt_scratch, void* dat_scratch, float* ds_parts, hipStream_t st);
+
 // ---- calibration reductions -------------------------------------------------------
 // partials[grid][3]: max|a|, min(f(a)), max(f(a)) over a strided [rows, cols] view; f = gelu if gelu != 0
 int absminmax(int dt, const void* a, int rows, int cols, int ld, int gelu, float* partials, hipStream_t st);
