@@ -304,33 +304,34 @@ void ln_fwd(int dt, const void* x, const void* r, const float* gamma, const floa
                                        (T*)y, (T*)ycodes, q, mu, rstd, T_, H, eps));
 }
 
-constexpr int kLnBwdRows = 16;  // token rows per block (4 per wavefront)
+constexpr int kLnBwdRows = 8;  // token rows per block: one per wavefront
 int ln_bwd_parts(int T_) { return (T_ + kLnBwdRows - 1) / kLnBwdRows; }
 
-template <class T>
-__global__ void ln_bwd_k(const T* __restrict__ d_a, const T* __restrict__ d_b, const T* __restrict__ d_q,
-                         const T* __restrict__ a_q, QArg qa, const T* __restrict__ x, const T* __restrict__ r,
-                         const float* __restrict__ mu, const float* __restrict__ rstd_in, const float* __restrict__ gamma,
-                         T* __restrict__ dr, float* __restrict__ partials, int T_, int H) {
-  extern __shared__ float red[];  // [3*H] + 4
+// NCH: 8-element chunks per lane (hidden <= 512 * NCH)
+template <class T, int NCH>
+__global__ __launch_bounds__(64 * kLnBwdRows) void ln_bwd_k(const T* __restrict__ d_a, const T* __restrict__ d_b, const T* __restrict__ d_q,
+                                                            const T* __restrict__ a_q, QArg qa, const T* __restrict__ x, const T* __restrict__ r,
+                                                            const float* __restrict__ mu, const float* __restrict__ rstd_in,
+                                                            const float* __restrict__ gamma, T* __restrict__ dr, float* __restrict__ partials,
+                                                            int T_, int H) {
+  extern __shared__ float red[];  // [3*H] + kLnBwdRows
   const QuantParam q = load_q(qa);
   const int lane = threadIdx.x & 63, wave = threadIdx.x / 64;
   const int nch = H / 8;
-  float acc_g[kLnMaxChunks][8], acc_b[kLnMaxChunks][8], acc_d[kLnMaxChunks][8];
+  float acc_g[NCH][8], acc_b[NCH][8], acc_d[NCH][8];
 #pragma unroll
-  for (int i = 0; i < kLnMaxChunks; ++i)
+  for (int i = 0; i < NCH; ++i)
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc_g[i][j] = acc_b[i][j] = acc_d[i][j] = 0.f;
   float ds_acc = 0.f;
 
-  for (int rr = wave; rr < kLnBwdRows; rr += 4) {
-    const int row = blockIdx.x * kLnBwdRows + rr;
-    if (row >= T_) break;
+  const int row = blockIdx.x * kLnBwdRows + wave;
+  if (row < T_) {
     const float mean = mu[row], rstd = rstd_in[row];
-    float dy[kLnMaxChunks][8], xh[kLnMaxChunks][8];
+    float dy[NCH][8], xh[NCH][8];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-    for (int i = 0; i < kLnMaxChunks; ++i) {
+    for (int i = 0; i < NCH; ++i) {
       const int c = lane + 64 * i;
       if (c < nch) {
         const size_t off = (size_t)row * H + c * 8;
@@ -365,8 +366,8 @@ __global__ void ln_bwd_k(const T* __restrict__ d_a, const T* __restrict__ d_b, c
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           xh[i][j] = (xa[j] + xb[j] - mean) * rstd;
-          acc_g[i][j] += dy[i][j] * xh[i][j];
-          acc_b[i][j] += dy[i][j];
+          acc_g[i][j] = dy[i][j] * xh[i][j];
+          acc_b[i][j] = dy[i][j];
           dy[i][j] *= g[j];  // now d(xhat)
           s1 += dy[i][j];
           s2 += dy[i][j] * xh[i][j];
@@ -375,25 +376,25 @@ __global__ void ln_bwd_k(const T* __restrict__ d_a, const T* __restrict__ d_b, c
     }
     const float m1 = wave_sum(s1) / (float)H, m2 = wave_sum(s2) / (float)H;
 #pragma unroll
-    for (int i = 0; i < kLnMaxChunks; ++i) {
+    for (int i = 0; i < NCH; ++i) {
       const int c = lane + 64 * i;
       if (c < nch) {
         float o[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           o[j] = rstd * (dy[i][j] - m1 - xh[i][j] * m2);
-          acc_d[i][j] += round_to<T>(o[j]);
+          acc_d[i][j] = round_to<T>(o[j]);
         }
         store8(dr + (size_t)row * H + c * 8, o);
       }
     }
   }
-  // combine the four wavefronts in a fixed order, then write this block's partial row
+  // combine the wavefronts (rows) of the block in a fixed order, then write this block's partial row
   ds_acc = wave_sum(ds_acc);
-  for (int w = 0; w < 4; ++w) {
+  for (int w = 0; w < kLnBwdRows; ++w) {
     if (wave == w) {
 #pragma unroll
-      for (int i = 0; i < kLnMaxChunks; ++i) {
+      for (int i = 0; i < NCH; ++i) {
         const int c = lane + 64 * i;
         if (c < nch) {
 #pragma unroll
@@ -411,14 +412,23 @@ __global__ void ln_bwd_k(const T* __restrict__ d_a, const T* __restrict__ d_b, c
   const int width = 3 * H + 1;
   float* out = partials + (size_t)blockIdx.x * width;
   for (int c = threadIdx.x; c < 3 * H; c += blockDim.x) out[c] = red[c];
-  if (threadIdx.x == 0) out[3 * H] = red[3 * H] + red[3 * H + 1] + red[3 * H + 2] + red[3 * H + 3];
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int w = 0; w < kLnBwdRows; ++w) t += red[3 * H + w];
+    out[3 * H] = t;
+  }
 }
 int ln_bwd(int dt, const void* d_a, const void* d_b, const void* d_q, const void* a_q, QArg q, const void* x, const void* r,
            const float* mu, const float* rstd, const float* gamma, void* dr, float* partials, int T_, int H, hipStream_t st) {
   const int g = ln_bwd_parts(T_);
-  const size_t lds = (3 * (size_t)H + 4) * sizeof(float);
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(ln_bwd_k<T>, dim3(g), dim3(256), lds, st, (const T*)d_a, (const T*)d_b, (const T*)d_q,
-                                       (const T*)a_q, q, (const T*)x, (const T*)r, mu, rstd, gamma, (T*)dr, partials, T_, H));
+  const size_t lds = (3 * (size_t)H + kLnBwdRows) * sizeof(float);
+#define MREM_LN_BWD(NCH)                                                                                                        \
+  MREM_DISPATCH(dt, hipLaunchKernelGGL((ln_bwd_k<T, NCH>), dim3(g), dim3(64 * kLnBwdRows), lds, st, (const T*)d_a, (const T*)d_b, \
+                                       (const T*)d_q, (const T*)a_q, q, (const T*)x, (const T*)r, mu, rstd, gamma, (T*)dr, partials, T_, H))
+  if (H <= 512) MREM_LN_BWD(1);
+  else if (H <= 1024) MREM_LN_BWD(2);
+  else MREM_LN_BWD(4);
+#undef MREM_LN_BWD
   return g;
 }
 
@@ -746,30 +756,43 @@ __device__ __forceinline__ float adam_one(float p, float g, float& m, float& v, 
 // One block per output channel.  g_w holds d(loss)/d(w_hat) on entry; the
 // straight-through mask and the step-size gradient (row reduction) are formed
 // here, from the weights and the step before their update.
-__global__ void adam_matrix_k(float* __restrict__ w, float* __restrict__ sw, float* __restrict__ g_w, float* __restrict__ g_sw,
-                              float* __restrict__ m_w, float* __restrict__ v_w, float* __restrict__ m_sw, float* __restrict__ v_sw,
-                              int K, float qp, int on, AdamArg a, int write_grads) {
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void adam_matrix_k(float* __restrict__ w, float* __restrict__ sw, float* __restrict__ g_w,
+                                                     float* __restrict__ g_sw, float* __restrict__ m_w, float* __restrict__ v_w,
+                                                     float* __restrict__ m_sw, float* __restrict__ v_sw, int K, float qp, int on, AdamArg a,
+                                                     int write_grads) {
   __shared__ float red[17];
   const int n = blockIdx.x;
   const float s = on ? sw[n] : 1.f;
   float acc = 0.f;
-  AdamArg aw = a;
-  for (int k = threadIdx.x; k < K; k += blockDim.x) {
-    const size_t i = (size_t)n * K + k;
-    const float x = w[i];
-    float g = g_w[i];
-    if (on) {
-      const float v = __fdiv_rn(x, s);
-      const bool in = (v >= -qp) && (v <= qp);
-      const float c = rintf(fminf(fmaxf(v, -qp), qp));
-      acc += g * (c - (in ? v : 0.f));
-      g = in ? g : 0.f;
-      if (write_grads) g_w[i] = g;
+  const size_t row = (size_t)n * K;
+  for (int k = threadIdx.x * 4; k < K; k += blockDim.x * 4) {
+    const size_t i = row + k;
+    f32x4_t x = *reinterpret_cast<const f32x4_t*>(w + i);
+    f32x4_t g = *reinterpret_cast<const f32x4_t*>(g_w + i);
+    f32x4_t m = *reinterpret_cast<const f32x4_t*>(m_w + i);
+    f32x4_t vv = *reinterpret_cast<const f32x4_t*>(v_w + i);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float gj = g[j];
+      if (on) {
+        const float v = __fdiv_rn(x[j], s);
+        const bool in = (v >= -qp) && (v <= qp);
+        const float c = rintf(fminf(fmaxf(v, -qp), qp));
+        acc += gj * (c - (in ? v : 0.f));
+        gj = in ? gj : 0.f;
+        g[j] = gj;
+      }
+      float mj = m[j], vj = vv[j];
+      x[j] = adam_one(x[j], gj, mj, vj, a);
+      m[j] = mj;
+      vv[j] = vj;
     }
-    float m = m_w[i], vv = v_w[i];
-    w[i] = adam_one(x, g, m, vv, aw);
-    m_w[i] = m;
-    v_w[i] = vv;
+    *reinterpret_cast<f32x4_t*>(w + i) = x;
+    *reinterpret_cast<f32x4_t*>(m_w + i) = m;
+    *reinterpret_cast<f32x4_t*>(v_w + i) = vv;
+    if (on && write_grads) *reinterpret_cast<f32x4_t*>(g_w + i) = g;
   }
   if (on) {
     acc = block_sum(acc, red);
