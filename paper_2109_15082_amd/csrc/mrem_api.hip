@@ -94,7 +94,7 @@ struct Bump {
 };
 
 struct LayerWs {
-  size_t wcodes[4], what_t[4], zcorr[4];
+  size_t wcodes[4], what[4], zcorr[4];
   size_t xcodes, qkv, qkvcodes, ctx, ctxcodes, o, x1, x1codes, u, gcodes, y, mu1, rstd1, mu2, rstd2, stat_m, stat_l;
 };
 
@@ -103,7 +103,7 @@ struct Plan {
   // teacher scratch
   size_t t_qkv, t_ctx, t_o, t_x1, t_g, t_y, t_mu, t_rstd;
   // backward scratch
-  size_t lg, dr2, dr1, dxh, dx1h, dch, dc, dgh, du, dqkvh, dqkv, tA, tB, s_da, s_ph, ds_rows, partials, grads, pmax;
+  size_t lg, dr2, dr1, dxh, dx1h, dch, dc, dgh, du, dqkvh, dqkv, s_da, s_ph, ds_rows, partials, grads, pmax;
   size_t total;
 };
 
@@ -116,7 +116,7 @@ Plan make_plan(const mrem_ctx* c, int B, int S) {
     for (int i = 0; i < 4; ++i) {
       const size_t n = (size_t)c->wN[i] * c->wK[i];
       w.wcodes[i] = b.take(n * es);
-      w.what_t[i] = b.take(n * es);
+      w.what[i] = b.take(n * es);
       w.zcorr[i] = b.take((size_t)c->wN[i] * 4);
     }
     w.xcodes = b.take(T * H * es); w.qkv = b.take(T * 3 * H * es); w.qkvcodes = b.take(T * 3 * H * es);
@@ -132,13 +132,12 @@ Plan make_plan(const mrem_ctx* c, int B, int S) {
   p.dx1h = b.take(T * H * es); p.dch = b.take(T * H * es); p.dc = b.take(T * H * es);
   p.dgh = b.take(T * F * es); p.du = b.take(T * F * es); p.dqkvh = b.take(T * 3 * H * es); p.dqkv = b.take(T * 3 * H * es);
   const size_t widest = (3 * H > F ? 3 * H : F);
-  p.tA = b.take(widest * T * es); p.tB = b.take(widest * T * es);
   const size_t s_pad = ((size_t)S + 31) / 32 * 32;
   const size_t pp = (size_t)B * c->nh * s_pad * s_pad;
   p.s_da = b.take(pp * 4); p.s_ph = b.take(pp * 4); p.ds_rows = b.take((size_t)B * c->nh * S * 4);
   p.pmax = b.take((size_t)B * c->nh * S * 4);
   size_t np = (size_t)ln_bwd_parts((int)T) * (3 * H + 1);
-  const size_t np2 = ((T + 63) / 64) * widest;
+  const size_t np2 = ((T + 31) / 32) * widest;
   if (np2 > np) np = np2;
   if (np < 2048 * 3) np = 2048 * 3;
   p.partials = b.take(np * 4);
@@ -202,7 +201,7 @@ void prepare_weights(const Run& r, const float* params) {
     const float* base = params + c->layer_stride * l;
     for (int i = 0; i < 4; ++i)
       weight_prepare(c->dt, base + c->foff[kWField[i]], base + c->foff[kSField[i]], c->wN[i], c->wK[i], c->cfg.w_bits,
-                     r.at(r.p.lw[l].wcodes[i]), r.at(r.p.lw[l].what_t[i]), r.at<float>(r.p.lw[l].zcorr[i]), r.st);
+                     r.at(r.p.lw[l].wcodes[i]), r.at(r.p.lw[l].what[i]), r.at<float>(r.p.lw[l].zcorr[i]), r.st);
   }
 }
 
@@ -300,8 +299,9 @@ void teacher_forward(const Run& r, const float* teacher, const void* cache, cons
   }
 }
 
-// weight-gradient product of linear layer i: grads[w] = (dY^T * codes_in) * s_a (+ z * db)
-void wgrad(const Run& r, const float* params, float* grads, int l, int i, const void* dyT, const void* codesT) {
+// weight-gradient product of linear layer i: grads[w] = (dY^T * codes_in) * s_a (+ z * db);
+// dy is [T, N_out], codes_in is [T, K_in]: the token index is the contraction index of both
+void wgrad(const Run& r, const float* params, float* grads, int l, int i, const void* dy, const void* codes_in) {
   const mrem_ctx* c = r.c;
   float* g = grads + c->layer_stride * l;
   Epilogue e;
@@ -309,13 +309,22 @@ void wgrad(const Run& r, const float* params, float* grads, int l, int i, const 
   if (q.on) e.alpha = q.s;
   if (q.on && q.z) { e.beta = q.z; e.row_vec = g + c->foff[kBField[i]]; }
   e.out_f32 = 1;
-  gemm_nt(c->dt, dyT, r.T, codesT, r.T, g + c->foff[kWField[i]], c->wK[i], c->wN[i], c->wK[i], r.T, e, r.st);
+  gemm(c->dt, 1, 1, dy, c->wN[i], codes_in, c->wK[i], g + c->foff[kWField[i]], c->wK[i], c->wN[i], c->wK[i], r.T, e, r.st);
 }
-// input-gradient product: d(in^) = dY * W^  via the transposed dequantized copy
+// input-gradient product: d(in^) = dY * W^ with the dequantized weights [N_out, K_in]
 void dgrad(const Run& r, int l, int i, const void* dy, void* out) {
   const mrem_ctx* c = r.c;
   Epilogue e;
-  gemm_nt(c->dt, dy, c->wN[i], r.at(r.p.lw[l].what_t[i]), c->wN[i], out, c->wK[i], r.T, c->wK[i], c->wN[i], e, r.st);
+  gemm(c->dt, 0, 1, dy, c->wN[i], r.at(r.p.lw[l].what[i]), c->wK[i], out, c->wK[i], r.T, c->wK[i], c->wN[i], e, r.st);
+}
+
+// column sums of a [T, C] tensor into out[C] (bias gradients)
+void colsum(const Run& r, const void* a, int C, float* out) {
+  const mrem_ctx* c = r.c;
+  float* parts = r.at<float>(r.p.partials);
+  const int n = colsum_partials(c->dt, a, r.T, C, parts, r.st);
+  ReduceSeg sg{0, C, out};
+  reduce_partials(parts, n, C, &sg, 1, 1.f, r.st);
 }
 
 void student_backward(const Run& r, const float* params, const void* x_q, const void* per_layer_fp, const void* per_layer_q,
@@ -355,9 +364,7 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       reduce_partials(parts, n, 3 * H + 1, sg, top ? 3 : 4, 1.f, r.st);
     }
     // second feed-forward projection
-    transpose_colsum(c->dt, r.at(r.p.dr2), T, H, H, r.at(r.p.tA), nullptr, r.st);
-    transpose_colsum(c->dt, r.at(w.gcodes), T, F, F, r.at(r.p.tB), nullptr, r.st);
-    wgrad(r, params, grads, l, 3, r.at(r.p.tA), r.at(r.p.tB));
+    wgrad(r, params, grads, l, 3, r.at(r.p.dr2), r.at(w.gcodes));
     dgrad(r, l, 3, r.at(r.p.dr2), r.at(r.p.dgh));
     // GELU and its output quantizer
     {
@@ -366,13 +373,8 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       reduce_partials(parts, n, 1, &sg, 1, 1.f, r.st);
     }
     // first feed-forward projection
-    {
-      const int n = transpose_colsum(c->dt, r.at(r.p.du), T, F, F, r.at(r.p.tA), parts, r.st);
-      ReduceSeg sg{0, F, g + c->foff[MREM_F_B_1]};
-      reduce_partials(parts, n, F, &sg, 1, 1.f, r.st);
-    }
-    transpose_colsum(c->dt, r.at(w.x1codes), T, H, H, r.at(r.p.tB), nullptr, r.st);
-    wgrad(r, params, grads, l, 2, r.at(r.p.tA), r.at(r.p.tB));
+    colsum(r, r.at(r.p.du), F, g + c->foff[MREM_F_B_1]);
+    wgrad(r, params, grads, l, 2, r.at(r.p.du), r.at(w.x1codes));
     dgrad(r, l, 2, r.at(r.p.du), r.at(r.p.dx1h));
     // first LayerNorm: dy = dr2 (residual) + dx1h through the FFN-input quantizer
     {
@@ -383,9 +385,7 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       reduce_partials(parts, n, 3 * H + 1, sg, 4, 1.f, r.st);
     }
     // attention output projection
-    transpose_colsum(c->dt, r.at(r.p.dr1), T, H, H, r.at(r.p.tA), nullptr, r.st);
-    transpose_colsum(c->dt, r.at(w.ctxcodes), T, H, H, r.at(r.p.tB), nullptr, r.st);
-    wgrad(r, params, grads, l, 1, r.at(r.p.tA), r.at(r.p.tB));
+    wgrad(r, params, grads, l, 1, r.at(r.p.dr1), r.at(w.ctxcodes));
     dgrad(r, l, 1, r.at(r.p.dr1), r.at(r.p.dch));
     {
       const int n = quant_bwd(c->dt, r.at(r.p.dch), r.at(w.ctx), r.at(r.p.dc), numel, make_q(c, params, l, 5), parts, r.st);
@@ -411,13 +411,8 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       reduce_partials(parts, n, 3, sg, 3, 1.f, r.st);
     }
     // query/key/value projection
-    {
-      const int n = transpose_colsum(c->dt, r.at(r.p.dqkv), T, 3 * H, 3 * H, r.at(r.p.tA), parts, r.st);
-      ReduceSeg sg{0, 3 * H, g + c->foff[MREM_F_B_QKV]};
-      reduce_partials(parts, n, 3 * H, &sg, 1, 1.f, r.st);
-    }
-    transpose_colsum(c->dt, r.at(w.xcodes), T, H, H, r.at(r.p.tB), nullptr, r.st);
-    wgrad(r, params, grads, l, 0, r.at(r.p.tA), r.at(r.p.tB));
+    colsum(r, r.at(r.p.dqkv), 3 * H, g + c->foff[MREM_F_B_QKV]);
+    wgrad(r, params, grads, l, 0, r.at(r.p.dqkv), r.at(w.xcodes));
     dgrad(r, l, 0, r.at(r.p.dqkv), r.at(r.p.dxh));
     if (l == 0) {
       // nothing flows out of the module (Section 4.2); only the input quantizer's step needs dxh

@@ -463,34 +463,26 @@ int mse_loss_grad(int dt, const void* fq, const void* ffp, void* grad, int64_t n
 }
 
 // ------------------------------------------------------------------------------
-// transpose (for the token-contracted weight-gradient products) + column sums
+// column sums of a [R, C] tensor (bias gradients): partials[R/32][C]
 // ------------------------------------------------------------------------------
+constexpr int kColsumRows = 32;
 template <class T>
-__global__ void transpose_k(const T* __restrict__ in, int R, int C, int ld_in, T* __restrict__ out, float* __restrict__ partials) {
-  __shared__ float tile[64][65];
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;  // 256 threads: 4 rows at a time
-  for (int rr = ty; rr < 64; rr += 4) {
-    const int r = r0 + rr, c = c0 + tx;
-    tile[rr][tx] = (r < R && c < C) ? ldf(in, (size_t)r * ld_in + c) : 0.f;
+__global__ __launch_bounds__(256) void colsum_k(const T* __restrict__ a, int R, int C, float* __restrict__ partials) {
+  const int chunk = blockIdx.x * 256 + threadIdx.x;
+  if (chunk * 8 >= C) return;
+  const int r0 = blockIdx.y * kColsumRows;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int r = r0; r < r0 + kColsumRows && r < R; ++r) {
+    float v[8];
+    load8(a + (size_t)r * C + chunk * 8, v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] += v[j];
   }
-  __syncthreads();
-  for (int cc = ty; cc < 64; cc += 4) {
-    const int c = c0 + cc, r = r0 + tx;
-    if (c < C && r < R) stf(out, (size_t)c * R + r, tile[tx][cc]);
-  }
-  if (partials && threadIdx.x < 64) {
-    const int c = c0 + threadIdx.x;
-    if (c < C) {
-      float s = 0.f;
-      for (int rr = 0; rr < 64; ++rr) s += tile[rr][threadIdx.x];
-      partials[(size_t)blockIdx.y * C + c] = s;
-    }
-  }
+  store8(partials + (size_t)blockIdx.y * C + chunk * 8, acc);
 }
-int transpose_colsum(int dt, const void* in, int R, int C, int ld_in, void* out, float* partials, hipStream_t st) {
-  dim3 g((C + 63) / 64, (R + 63) / 64);
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(transpose_k<T>, g, dim3(256), 0, st, (const T*)in, R, C, ld_in, (T*)out, partials));
+int colsum_partials(int dt, const void* a, int R, int C, float* partials, hipStream_t st) {
+  dim3 g((C / 8 + 255) / 256, (R + kColsumRows - 1) / kColsumRows);
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(colsum_k<T>, g, dim3(256), 0, st, (const T*)a, R, C, partials));
   return (int)g.y;
 }
 
@@ -501,12 +493,13 @@ struct ReduceSegs {
   ReduceSeg s[4];
   int n;
 };
-__global__ void reduce_partials_k(const float* __restrict__ partials, int nparts, int width, ReduceSegs segs, float scale) {
-  // 256 threads = 64 columns x 4 groups of partial rows; the four group sums are added
-  // in group order, so the result does not depend on scheduling.
-  __shared__ float red[4][64];
+__global__ __launch_bounds__(256) void reduce_partials_k(const float* __restrict__ partials, int nparts, int width, ReduceSegs segs,
+                                                         float scale) {
+  // 256 threads = 16 columns x 16 groups of partial rows; the group sums are added in group
+  // order, so the result does not depend on scheduling.
+  __shared__ float red[16][17];
   __shared__ float sred[17];
-  const int col = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int col = threadIdx.x & 15, grp = threadIdx.x >> 4;
   for (int k = 0; k < segs.n; ++k) {
     const ReduceSeg sg = segs.s[k];
     if (sg.len == 1) {
@@ -518,23 +511,26 @@ __global__ void reduce_partials_k(const float* __restrict__ partials, int nparts
       }
       continue;
     }
-    for (int c0 = blockIdx.x * 64; c0 < sg.len; c0 += gridDim.x * 64) {
+    for (int c0 = blockIdx.x * 16; c0 < sg.len; c0 += gridDim.x * 16) {
       const int c = c0 + col;
-      float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
+      float t0 = 0.f, t1 = 0.f;
       if (c < sg.len) {
         const float* src = partials + sg.begin + c;
         int p = grp;
-        for (; p + 12 < nparts; p += 16) {
+        for (; p + 16 < nparts; p += 32) {
           t0 += src[(size_t)p * width];
-          t1 += src[(size_t)(p + 4) * width];
-          t2 += src[(size_t)(p + 8) * width];
-          t3 += src[(size_t)(p + 12) * width];
+          t1 += src[(size_t)(p + 16) * width];
         }
-        for (; p < nparts; p += 4) t0 += src[(size_t)p * width];
+        for (; p < nparts; p += 16) t0 += src[(size_t)p * width];
       }
-      red[grp][col] = (t0 + t1) + (t2 + t3);
+      red[grp][col] = t0 + t1;
       __syncthreads();
-      if (grp == 0 && c < sg.len) sg.out[c] = ((red[0][col] + red[1][col]) + (red[2][col] + red[3][col])) * scale;
+      if (grp == 0 && c < sg.len) {
+        float t = 0.f;
+#pragma unroll
+        for (int g = 0; g < 16; ++g) t += red[g][col];
+        sg.out[c] = t * scale;
+      }
       __syncthreads();
     }
   }
@@ -544,7 +540,7 @@ void reduce_partials(const float* partials, int nparts, int width, const ReduceS
   s.n = nsegs;
   int maxlen = 1;
   for (int i = 0; i < nsegs; ++i) { s.s[i] = segs[i]; if (segs[i].len > maxlen) maxlen = segs[i].len; }
-  int g = (maxlen + 63) / 64;
+  int g = (maxlen + 15) / 16;
   hipLaunchKernelGGL(reduce_partials_k, dim3(g), dim3(256), 0, st, partials, nparts, width, s, scale);
 }
 
@@ -635,54 +631,35 @@ void weight_step_init(const float* w, float* scale, int64_t N, int64_t K, int bi
   hipLaunchKernelGGL(weight_step_init_k, dim3((unsigned)N), dim3(256), 0, st, w, scale, K, qp);
 }
 
-// codes (integer-valued, storage type) + zcorr[n] = s[n] * sum_k code
+// codes (integer-valued, storage type), dequantized weights s*code (same layout), and
+// zcorr[n] = s[n] * sum_k code; one block per output channel
 template <class T>
-__global__ void weight_codes_k(const float* __restrict__ w, const float* __restrict__ sw, int K, float qp, int on,
-                               T* __restrict__ codes, float* __restrict__ zcorr) {
+__global__ __launch_bounds__(256) void weight_codes_k(const float* __restrict__ w, const float* __restrict__ sw, int K, float qp, int on,
+                                                      T* __restrict__ codes, T* __restrict__ what, float* __restrict__ zcorr) {
   __shared__ float red[17];
   const int n = blockIdx.x;
   const float s = on ? sw[n] : 1.f;
   float acc = 0.f;
-  for (int k = threadIdx.x; k < K; k += blockDim.x) {
-    const float x = w[(size_t)n * K + k];
-    float c = x;
-    if (on) { c = rintf(fminf(fmaxf(__fdiv_rn(x, s), -qp), qp)); acc += c; }
-    stf(codes, (size_t)n * K + k, c);
+  const size_t row = (size_t)n * K;
+  for (int k = threadIdx.x * 8; k < K; k += blockDim.x * 8) {
+    float x[8], c[8];
+    load8(w + row + k, x);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      c[j] = x[j];
+      if (on) { c[j] = rintf(fminf(fmaxf(__fdiv_rn(x[j], s), -qp), qp)); acc += c[j]; x[j] = s * c[j]; }
+    }
+    store8(codes + row + k, c);
+    if (what) store8(what + row + k, x);
   }
   acc = block_sum(acc, red);
   if (threadIdx.x == 0) zcorr[n] = on ? s * acc : 0.f;
 }
-// what_t[k][n] = round(s[n] * code[n][k])
-template <class T>
-__global__ void weight_dequant_t_k(const float* __restrict__ w, const float* __restrict__ sw, int N, int K, float qp, int on,
-                                   T* __restrict__ what_t) {
-  __shared__ float tile[64][65];
-  const int n0 = blockIdx.y * 64, k0 = blockIdx.x * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int rr = ty; rr < 64; rr += 4) {
-    const int n = n0 + rr, k = k0 + tx;
-    float v = 0.f;
-    if (n < N && k < K) {
-      v = w[(size_t)n * K + k];
-      if (on) { const float s = sw[n]; v = s * rintf(fminf(fmaxf(__fdiv_rn(v, s), -qp), qp)); }
-    }
-    tile[rr][tx] = v;
-  }
-  __syncthreads();
-  for (int cc = ty; cc < 64; cc += 4) {
-    const int k = k0 + cc, n = n0 + tx;
-    if (k < K && n < N) stf(what_t, (size_t)k * N + n, tile[tx][cc]);
-  }
-}
-void weight_prepare(int dt, const float* w, const float* sw, int N, int K, int bits, void* codes, void* what_t, float* zcorr,
+void weight_prepare(int dt, const float* w, const float* sw, int N, int K, int bits, void* codes, void* what, float* zcorr,
                     hipStream_t st) {
   const int on = bits > 0;
   const float qp = on ? (float)((1 << (bits - 1)) - 1) : 0.f;
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(weight_codes_k<T>, dim3(N), dim3(256), 0, st, w, sw, K, qp, on, (T*)codes, zcorr));
-  if (what_t) {
-    dim3 g((K + 63) / 64, (N + 63) / 64);
-    MREM_DISPATCH(dt, hipLaunchKernelGGL(weight_dequant_t_k<T>, g, dim3(256), 0, st, w, sw, N, K, qp, on, (T*)what_t));
-  }
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(weight_codes_k<T>, dim3(N), dim3(256), 0, st, w, sw, K, qp, on, (T*)codes, (T*)what, zcorr));
 }
 
 // ------------------------------------------------------------------------------

@@ -62,7 +62,7 @@ __device__ __forceinline__ void epilogue_store(TO* C, int ldc, int m, int n, flo
 // ------------------------------------------------------------------------------
 template <class TA, class TO>
 __global__ void gemm_nt_simt_k(const TA* __restrict__ A, int lda, const TA* __restrict__ B, int ldb, TO* __restrict__ C, int ldc, int M,
-                               int N, int K, Epilogue e) {
+                               int N, int K, Epilogue e, int a_t = 0, int b_t = 0) {
   __shared__ float As[16][64 + 4];
   __shared__ float Bs[16][64 + 4];
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -79,8 +79,8 @@ __global__ void gemm_nt_simt_k(const TA* __restrict__ A, int lda, const TA* __re
       const int idx = threadIdx.x + 256 * t;
       const int r = idx >> 4, kk = idx & 15;
       const int k = k0 + kk;
-      As[kk][r] = (m0 + r < M && k < K) ? ldf(A, (size_t)(m0 + r) * lda + k) : 0.f;
-      Bs[kk][r] = (n0 + r < N && k < K) ? ldf(B, (size_t)(n0 + r) * ldb + k) : 0.f;
+      As[kk][r] = (m0 + r < M && k < K) ? ldf(A, a_t ? (size_t)k * lda + m0 + r : (size_t)(m0 + r) * lda + k) : 0.f;
+      Bs[kk][r] = (n0 + r < N && k < K) ? ldf(B, b_t ? (size_t)k * ldb + n0 + r : (size_t)(n0 + r) * ldb + k) : 0.f;
     }
     __syncthreads();
 #pragma unroll
@@ -129,19 +129,57 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kBK = 64;
 constexpr int kLdsStride = kBK + 8;  // elements per LDS row (144 bytes)
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, class TO>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_nt_mfma_k(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb,
-                                                      TO* __restrict__ C, int ldc, int M, int N, int K, Epilogue e, int tiles_m,
-                                                      int tiles_n) {
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+
+// One operand of the product as the register-staged kernel sees it.
+//   TR = false: the matrix is stored [rows][k] (k contiguous); LDS tile [ROWS][64 + 8].
+//   TR = true : the matrix is stored [k][rows] (the contraction index is the slow one, as for
+//               both operands of a weight-gradient product and for the weight in an
+//               input-gradient product); LDS tile [64][ROWS + 16], and MFMA fragments are
+//               gathered with the transposing LDS read (ds_read_b64_tr_b16): in a group of 16
+//               lanes, lane s supplies the 8-byte chunk of row s/4, columns 4*(s%4)..+3, and
+//               receives column s of the four rows.
+template <bool TR, int ROWS, int NTHREADS>
+struct OperandTile {
+  static constexpr int PITCH = TR ? ROWS + 16 : kBK + 8;
+  static constexpr int ELEMS = TR ? kBK * PITCH : ROWS * PITCH;
+  static constexpr int NCH = ROWS * 8 / NTHREADS;  // 16-byte chunks per thread per k-step
+  // chunk q of the tile: (tile row, first element) in the matrix, and offset in LDS
+  static __device__ __forceinline__ size_t gofs(int q, int ld, int tile0, int k0) {
+    if (TR) { const int row = q / (ROWS / 8), ch = q % (ROWS / 8); return (size_t)(k0 + row) * ld + tile0 + ch * 8; }
+    const int row = q >> 3, ch = q & 7;
+    return (size_t)(tile0 + row) * ld + k0 + ch * 8;
+  }
+  static __device__ __forceinline__ int lofs(int q) {
+    if (TR) { const int row = q / (ROWS / 8), ch = q % (ROWS / 8); return row * PITCH + ch * 8; }
+    return (q >> 3) * PITCH + (q & 7) * 8;
+  }
+  // fragment of 32 tile rows starting at row0 for k-substep kk (16 of the 64 k values)
+  static __device__ __forceinline__ bf16x8_t frag(const bf16_t* tile, int row0, int kk, int lane) {
+    if (TR) {
+      const int g = lane >> 4, s = lane & 15;
+      const bf16_t* p = tile + (16 * kk + 8 * (g >> 1) + (s >> 2)) * PITCH + row0 + 16 * (g & 1) + 4 * (s & 3);
+      union { bf16x8_t v; s16x4_t h[2]; } u;
+      u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(p));
+      u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(p + 4 * PITCH));
+      return u.v;
+    }
+    return *reinterpret_cast<const bf16x8_t*>(tile + (row0 + (lane & 31)) * PITCH + kk * 16 + (lane >> 5) * 8);
+  }
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, class TO>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B,
+                                                                      int ldb, TO* __restrict__ C, int ldc, int M, int N, int K, Epilogue e,
+                                                                      int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
   constexpr int NTHREADS = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wavefront sub-tile
   constexpr int MT = WM / 32, NT = WN / 32;            // MFMA tiles per wavefront
-  constexpr int A_ELEMS = BM * kLdsStride, B_ELEMS = BN * kLdsStride;
-  constexpr int STAGE = A_ELEMS + B_ELEMS;
-  constexpr int A_CH = BM * 8 / NTHREADS, B_CH = BN * 8 / NTHREADS;  // 16-byte chunks per thread per k-step
-  constexpr int ROWS_PER_PASS = NTHREADS / 8;
+  typedef OperandTile<AT, BM, NTHREADS> OpA;
+  typedef OperandTile<BT, BN, NTHREADS> OpB;
+  constexpr int STAGE = OpA::ELEMS + OpB::ELEMS;
 
   // Tile order: consecutive block ids land on different XCDs (8 of them, each with its
   // own L2), so give each XCD a contiguous range of tiles, walked in groups of 8 tile
@@ -169,48 +207,43 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_nt_mfma_k(const b
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  u32x4_t ra[A_CH], rb[B_CH];
-  const bf16_t* Ag = A + (size_t)m0 * lda;
-  const bf16_t* Bg = B + (size_t)n0 * ldb;
-  const int ld_row = tid >> 3, ld_ch = tid & 7;  // this thread's chunk in rows ld_row + 32*i
-  const bf16_t* Agt = Ag + (size_t)ld_row * lda + ld_ch * 8;
-  const bf16_t* Bgt = Bg + (size_t)ld_row * ldb + ld_ch * 8;
-  const int lds_off = ld_row * kLdsStride + ld_ch * 8;
+  // gridDim.y > 1: split-K, each y-slice accumulates its share of the k-steps into fp32 C with atomic adds
+  const int KT = K / kBK / (int)gridDim.y;
+  const int kbase = (int)blockIdx.y * KT * kBK;
 
-#define MREM_LOAD_GLOBAL(k0)                                                                           \
-  {                                                                                                    \
-    _Pragma("unroll") for (int i = 0; i < A_CH; ++i)                                                   \
-        ra[i] = *reinterpret_cast<const u32x4_t*>(Agt + (size_t)(ROWS_PER_PASS * i) * lda + (k0));                  \
-    _Pragma("unroll") for (int i = 0; i < B_CH; ++i)                                                   \
-        rb[i] = *reinterpret_cast<const u32x4_t*>(Bgt + (size_t)(ROWS_PER_PASS * i) * ldb + (k0));                  \
+  u32x4_t ra[OpA::NCH], rb[OpB::NCH];
+#define MREM_LOAD_GLOBAL(k0)                                                                                       \
+  {                                                                                                                \
+    _Pragma("unroll") for (int i = 0; i < OpA::NCH; ++i)                                                           \
+        ra[i] = *reinterpret_cast<const u32x4_t*>(A + OpA::gofs(tid + NTHREADS * i, lda, m0, kbase + (k0)));       \
+    _Pragma("unroll") for (int i = 0; i < OpB::NCH; ++i)                                                           \
+        rb[i] = *reinterpret_cast<const u32x4_t*>(B + OpB::gofs(tid + NTHREADS * i, ldb, n0, kbase + (k0)));       \
   }
-#define MREM_STORE_LDS(stage)                                                                          \
-  {                                                                                                    \
-    bf16_t* As_ = smem + (stage) * STAGE + lds_off;                                                    \
-    bf16_t* Bs_ = As_ + A_ELEMS;                                                                       \
-    _Pragma("unroll") for (int i = 0; i < A_CH; ++i)                                                   \
-        *reinterpret_cast<u32x4_t*>(As_ + ROWS_PER_PASS * i * kLdsStride) = ra[i];                                  \
-    _Pragma("unroll") for (int i = 0; i < B_CH; ++i)                                                   \
-        *reinterpret_cast<u32x4_t*>(Bs_ + ROWS_PER_PASS * i * kLdsStride) = rb[i];                                  \
+#define MREM_STORE_LDS(stage)                                                                                      \
+  {                                                                                                                \
+    bf16_t* As_ = smem + (stage) * STAGE;                                                                          \
+    bf16_t* Bs_ = As_ + OpA::ELEMS;                                                                                \
+    _Pragma("unroll") for (int i = 0; i < OpA::NCH; ++i)                                                           \
+        *reinterpret_cast<u32x4_t*>(As_ + OpA::lofs(tid + NTHREADS * i)) = ra[i];                                  \
+    _Pragma("unroll") for (int i = 0; i < OpB::NCH; ++i)                                                           \
+        *reinterpret_cast<u32x4_t*>(Bs_ + OpB::lofs(tid + NTHREADS * i)) = rb[i];                                  \
   }
 
-  const int KT = K / kBK;
   MREM_LOAD_GLOBAL(0)
   MREM_STORE_LDS(0)
   __syncthreads();
-  const int frag_row = lane & 31, frag_ch = lane >> 5;
   for (int kt = 0; kt < KT; ++kt) {
     const int cur = kt & 1;
     if (kt + 1 < KT) MREM_LOAD_GLOBAL((kt + 1) * kBK)
-    const bf16_t* As = smem + cur * STAGE + (wm * WM + frag_row) * kLdsStride + frag_ch * 8;
-    const bf16_t* Bs = smem + cur * STAGE + A_ELEMS + (wn * WN + frag_row) * kLdsStride + frag_ch * 8;
+    const bf16_t* As = smem + cur * STAGE;
+    const bf16_t* Bs = As + OpA::ELEMS;
 #pragma unroll
     for (int kk = 0; kk < kBK / 16; ++kk) {
       bf16x8_t af[MT], bfr[NT];
 #pragma unroll
-      for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(As + i * 32 * kLdsStride + kk * 16);
+      for (int i = 0; i < MT; ++i) af[i] = OpA::frag(As, wm * WM + i * 32, kk, lane);
 #pragma unroll
-      for (int j = 0; j < NT; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bs + j * 32 * kLdsStride + kk * 16);
+      for (int j = 0; j < NT; ++j) bfr[j] = OpB::frag(Bs, wn * WN + j * 32, kk, lane);
 #pragma unroll
       for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -225,12 +258,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_nt_mfma_k(const b
   // epilogue: out = acc * (alpha * col_scale[n]) + beta * (col_vec[n] + row_vec[m]) + bias[n]
   const float alpha = e.alpha ? *e.alpha : 1.f;
   const float beta = e.beta ? *e.beta : 0.f;
+  const bool split = gridDim.y > 1, lead = blockIdx.y == 0;  // the additive terms go in once, with slice 0
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
     const int n = n0 + wn * WN + j * 32 + (lane & 31);
     const float cs = alpha * (e.col_scale ? e.col_scale[n] : 1.f);
-    float cb = e.bias ? e.bias[n] : 0.f;
-    if (e.beta && e.col_vec) cb += beta * e.col_vec[n];
+    float cb = (e.bias && lead) ? e.bias[n] : 0.f;
+    if (e.beta && e.col_vec && lead) cb += beta * e.col_vec[n];
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
       const int mb = m0 + wm * WM + i * 32 + 4 * (lane >> 5);
@@ -238,7 +272,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_nt_mfma_k(const b
       for (int r = 0; r < 16; ++r) {
         const int m = mb + 8 * (r >> 2) + (r & 3);
         float v = acc[i][j][r] * cs + cb;
-        if (e.beta && e.row_vec) v += beta * e.row_vec[m];
+        if (e.beta && e.row_vec && lead) v += beta * e.row_vec[m];
+        if constexpr (sizeof(TO) == 4) {
+          if (split) {
+            atomicAdd(reinterpret_cast<float*>(C) + (size_t)m * ldc + n, v);
+            continue;
+          }
+        }
         if (e.gelu) v = gelu_f(round_to<TO>(v));
         stf(C, (size_t)m * ldc + n, v);
       }
@@ -246,20 +286,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_nt_mfma_k(const b
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, class TO>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, class TO>
 static void launch_mfma(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
-                        hipStream_t st) {
-  constexpr size_t lds = 2 * (size_t)(BM + BN) * kLdsStride * sizeof(bf16_t);
+                        hipStream_t st, int k_splits = 1) {
+  constexpr int NTHREADS = 64 * WAVES_M * WAVES_N;
+  constexpr size_t lds = 2 * (size_t)(OperandTile<AT, BM, NTHREADS>::ELEMS + OperandTile<BT, BN, NTHREADS>::ELEMS) * sizeof(bf16_t);
   static bool configured = false;
   if (!configured) {
-    hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_mfma_k<BM, BN, WAVES_M, WAVES_N, TO>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, TO>),
+                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     configured = true;
   }
   const int tiles_m = M / BM, tiles_n = N / BN;
-  hipLaunchKernelGGL((gemm_nt_mfma_k<BM, BN, WAVES_M, WAVES_N, TO>), dim3(tiles_m * tiles_n), dim3(64 * WAVES_M * WAVES_N), lds, st, (const bf16_t*)A, lda, (const bf16_t*)B, ldb,
-                     (TO*)C, ldc, M, N, K, e, tiles_m, tiles_n);
+  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, TO>), dim3(tiles_m * tiles_n, k_splits), dim3(NTHREADS), lds, st,
+                     (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (TO*)C, ldc, M, N, K, e, tiles_m, tiles_n);
 }
-
 
 // ------------------------------------------------------------------------------
 // Producer/consumer variant.  Two extra wavefronts do nothing but move operand tiles
@@ -471,13 +512,13 @@ static bool mfma_ok(const void* A, int lda, const void* B, int ldb, int M, int N
          (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (reinterpret_cast<uintptr_t>(B) & 15) == 0;
 }
 
-static void gemm_nt_launch(int dt, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
-                           const Epilogue& e, hipStream_t st);
+static void gemm_launch(int dt, int a_t, int b_t, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
+                        const Epilogue& e, hipStream_t st);
 
-void gemm_nt(int dt, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
-             hipStream_t st) {
+void gemm(int dt, int a_t, int b_t, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
+          const Epilogue& e, hipStream_t st) {
   if (!g_prof_on) {
-    gemm_nt_launch(dt, A, lda, B, ldb, C, ldc, M, N, K, e, st);
+    gemm_launch(dt, a_t, b_t, A, lda, B, ldb, C, ldc, M, N, K, e, st);
     return;
   }
   GemmRecord r;
@@ -485,33 +526,52 @@ void gemm_nt(int dt, const void* A, int lda, const void* B, int ldb, void* C, in
   hipEventCreate(&r.e0);
   hipEventCreate(&r.e1);
   hipEventRecord(r.e0, st);
-  gemm_nt_launch(dt, A, lda, B, ldb, C, ldc, M, N, K, e, st);
+  gemm_launch(dt, a_t, b_t, A, lda, B, ldb, C, ldc, M, N, K, e, st);
   hipEventRecord(r.e1, st);
   g_prof.push_back(r);
 }
 
-static void gemm_nt_launch(int dt, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
-                           const Epilogue& e, hipStream_t st) {
+void gemm_nt(int dt, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
+             hipStream_t st) {
+  gemm(dt, 0, 0, A, lda, B, ldb, C, ldc, M, N, K, e, st);
+}
+
+template <bool AT, bool BT>
+static void launch_mfma_modes(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
+                              hipStream_t st) {
+  const int tiles = (M / 128) * (N / 128);
+  if (e.out_f32) {
+    // Few tiles and a long contraction (weight gradients of the square projections): two
+    // k-slices.  Two atomic adds onto a zeroed fp32 value commute exactly, so the result
+    // does not depend on which slice arrives first.
+    const int splits = (tiles <= 128 && K >= 2048 && (K / kBK) % 2 == 0 && !e.gelu) ? 2 : 1;
+    if (splits > 1) fill_f32((float*)C, 0.f, (int64_t)M * ldc, st);
+    launch_mfma<128, 128, 2, 2, AT, BT, float>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
+  } else {
+    launch_mfma<128, 128, 2, 2, AT, BT, bf16_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+  }
+}
+
+static void gemm_launch(int dt, int a_t, int b_t, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
+                        const Epilogue& e, hipStream_t st) {
   if (dt == DT_BF16 && mfma_ok(A, lda, B, ldb, M, N, K)) {
-    // Measured on MI355X: with at most one 128x128 tile per compute unit the producer/consumer
-    // kernel (three stages in flight) is faster; with two or more tiles per compute unit two
-    // co-resident blocks of the register-staged kernel hide each other's latencies better.
     const int tiles = (M / 128) * (N / 128);
-    if (tiles <= 256) {
-      if (e.out_f32) {
-        // Few tiles and a long contraction (weight gradients of the square projections): two
-        // k-slices.  Two atomic adds onto a zeroed fp32 value commute exactly, so the result
-        // does not depend on which slice arrives first.
-        const int splits = (tiles <= 128 && K >= 2048 && (K / kBK) % 2 == 0 && !e.gelu) ? 2 : 1;
-        if (splits > 1) fill_f32((float*)C, 0.f, (int64_t)M * ldc, st);
-        launch_pc<128, 128, 2, 2, 3, float>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
+    if (!a_t && !b_t) {
+      // Measured on MI355X: with at most one 128x128 tile per compute unit the producer/consumer
+      // kernel (three stages in flight) is faster; with two or more tiles per compute unit two
+      // co-resident blocks of the register-staged kernel hide each other's latencies better.
+      if (tiles <= 256) {
+        if (e.out_f32) launch_pc<128, 128, 2, 2, 3, float>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+        else launch_pc<128, 128, 2, 2, 3, bf16_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
       } else {
-        launch_pc<128, 128, 2, 2, 3, bf16_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+        launch_mfma_modes<false, false>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
       }
-    } else if (e.out_f32) {
-      launch_mfma<128, 128, 2, 2, float>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+    } else if (!a_t && b_t) {
+      launch_mfma_modes<false, true>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+    } else if (a_t && b_t) {
+      launch_mfma_modes<true, true>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
     } else {
-      launch_mfma<128, 128, 2, 2, bf16_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+      launch_mfma_modes<true, false>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
     }
     return;
   }
@@ -519,13 +579,13 @@ static void gemm_nt_launch(int dt, const void* A, int lda, const void* B, int ld
   if (dt == DT_BF16) {
     if (e.out_f32)
       hipLaunchKernelGGL((gemm_nt_simt_k<bf16_t, float>), g, dim3(256), 0, st, (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (float*)C, ldc,
-                         M, N, K, e);
+                         M, N, K, e, a_t, b_t);
     else
       hipLaunchKernelGGL((gemm_nt_simt_k<bf16_t, bf16_t>), g, dim3(256), 0, st, (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (bf16_t*)C,
-                         ldc, M, N, K, e);
+                         ldc, M, N, K, e, a_t, b_t);
   } else {
     hipLaunchKernelGGL((gemm_nt_simt_k<float, float>), g, dim3(256), 0, st, (const float*)A, lda, (const float*)B, ldb, (float*)C, ldc, M,
-                       N, K, e);
+                       N, K, e, a_t, b_t);
   }
 }
 

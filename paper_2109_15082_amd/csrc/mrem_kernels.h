@@ -35,6 +35,10 @@ struct Epilogue {
   int out_f32 = 0;
 };
 
+// C[M,N] = op(A) * op(B)^T.  a_t = 0: A is stored [M,K] (K contiguous); a_t = 1: A is stored
+// [K,M] (the contraction index is the slow one).  Same for B with N.  lda/ldb: row pitch.
+void gemm(int dt, int a_t, int b_t, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
+          const Epilogue& e, hipStream_t st);
 // C[M,N] = A[M,K] * B[N,K]^T  (both operands contiguous along K)
 void gemm_nt(int dt, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
              const Epilogue& e, hipStream_t st);
@@ -47,9 +51,9 @@ int gemm_profile_end(double* ms, double* flops, int64_t* launches);
 void weight_quantize_i8(const float* w, float* scale, int8_t* codes, int64_t N, int64_t K, int bits, int init_scale,
                         hipStream_t st);
 void weight_step_init(const float* w, float* scale, int64_t N, int64_t K, int bits, hipStream_t st);
-// codes[N,K] (integer-valued, storage type), what_t[K,N] = round(s*q) transposed,
-// zcorr[N] = s[n] * sum_k q[n,k].  bits = 0: codes = round(w), what_t = round(w)^T, zcorr = 0.
-void weight_prepare(int dt, const float* w, const float* sw, int N, int K, int bits, void* codes, void* what_t,
+// codes[N,K] (integer-valued, storage type), what[N,K] = round(s*q),
+// zcorr[N] = s[n] * sum_k q[n,k].  bits = 0: codes = what = round(w), zcorr = 0.
+void weight_prepare(int dt, const float* w, const float* sw, int N, int K, int bits, void* codes, void* what,
                     float* zcorr, hipStream_t st);
 void convert_f32(int dt, const float* src, void* dst, int64_t n, hipStream_t st);
 
@@ -77,8 +81,8 @@ int ln_bwd_parts(int T);
 int mse_loss_grad(int dt, const void* fq, const void* ffp, void* grad, int64_t n, float scale, float* partials,
                   hipStream_t st);
 
-// out[C,R] = in[R,C]^T ; partials[R/64][C] column sums of `in` when partials != null
-int transpose_colsum(int dt, const void* in, int R, int C, int ld_in, void* out, float* partials, hipStream_t st);
+// partials[R/32][C]: column sums of 32-row slabs of a[R,C]; returns the number of slabs
+int colsum_partials(int dt, const void* a, int R, int C, float* partials, hipStream_t st);
 
 // out_k[c] = scale * sum_p partials[p*width + begin_k + c]  for up to 4 segments
 struct ReduceSeg {
