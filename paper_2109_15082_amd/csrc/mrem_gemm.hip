@@ -127,6 +127,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kBK = 64;
+constexpr int kRegBK = 64;  // k-step of the register-staged kernel
 constexpr int kLdsStride = kBK + 8;  // elements per LDS row (144 bytes)
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
@@ -139,20 +140,21 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 //               gathered with the transposing LDS read (ds_read_b64_tr_b16): in a group of 16
 //               lanes, lane s supplies the 8-byte chunk of row s/4, columns 4*(s%4)..+3, and
 //               receives column s of the four rows.
-template <bool TR, int ROWS, int NTHREADS>
+template <bool TR, int ROWS, int NTHREADS, int BK>
 struct OperandTile {
-  static constexpr int PITCH = TR ? ROWS + 16 : kBK + 8;
-  static constexpr int ELEMS = TR ? kBK * PITCH : ROWS * PITCH;
-  static constexpr int NCH = ROWS * 8 / NTHREADS;  // 16-byte chunks per thread per k-step
+  static constexpr int PITCH = TR ? ROWS + 16 : BK + 8;
+  static constexpr int ELEMS = TR ? BK * PITCH : ROWS * PITCH;
+  static constexpr int CPR = BK / 8;                   // 16-byte chunks per row of a k-contiguous tile
+  static constexpr int NCH = ROWS * CPR / NTHREADS;    // 16-byte chunks per thread per k-step
   // chunk q of the tile: (tile row, first element) in the matrix, and offset in LDS
   static __device__ __forceinline__ size_t gofs(int q, int ld, int tile0, int k0) {
     if (TR) { const int row = q / (ROWS / 8), ch = q % (ROWS / 8); return (size_t)(k0 + row) * ld + tile0 + ch * 8; }
-    const int row = q >> 3, ch = q & 7;
+    const int row = q / CPR, ch = q % CPR;
     return (size_t)(tile0 + row) * ld + k0 + ch * 8;
   }
   static __device__ __forceinline__ int lofs(int q) {
     if (TR) { const int row = q / (ROWS / 8), ch = q % (ROWS / 8); return row * PITCH + ch * 8; }
-    return (q >> 3) * PITCH + (q & 7) * 8;
+    return (q / CPR) * PITCH + (q % CPR) * 8;
   }
   // fragment of 32 tile rows starting at row0 for k-substep kk (16 of the 64 k values)
   static __device__ __forceinline__ bf16x8_t frag(const bf16_t* tile, int row0, int kk, int lane) {
@@ -168,7 +170,7 @@ struct OperandTile {
   }
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, class TO>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, int BK, class TO>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B,
                                                                       int ldb, TO* __restrict__ C, int ldc, int M, int N, int K, Epilogue e,
                                                                       int tiles_m, int tiles_n) {
@@ -177,8 +179,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16
   constexpr int NTHREADS = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wavefront sub-tile
   constexpr int MT = WM / 32, NT = WN / 32;            // MFMA tiles per wavefront
-  typedef OperandTile<AT, BM, NTHREADS> OpA;
-  typedef OperandTile<BT, BN, NTHREADS> OpB;
+  typedef OperandTile<AT, BM, NTHREADS, BK> OpA;
+  typedef OperandTile<BT, BN, NTHREADS, BK> OpB;
   constexpr int STAGE = OpA::ELEMS + OpB::ELEMS;
 
   // Tile order: consecutive block ids land on different XCDs (8 of them, each with its
@@ -208,8 +210,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // gridDim.y > 1: split-K, each y-slice accumulates its share of the k-steps into fp32 C with atomic adds
-  const int KT = K / kBK / (int)gridDim.y;
-  const int kbase = (int)blockIdx.y * KT * kBK;
+  const int KT = K / BK / (int)gridDim.y;
+  const int kbase = (int)blockIdx.y * KT * BK;
 
   u32x4_t ra[OpA::NCH], rb[OpB::NCH];
 #define MREM_LOAD_GLOBAL(k0)                                                                                       \
@@ -234,11 +236,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16
   __syncthreads();
   for (int kt = 0; kt < KT; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < KT) MREM_LOAD_GLOBAL((kt + 1) * kBK)
+    if (kt + 1 < KT) MREM_LOAD_GLOBAL((kt + 1) * BK)
     const bf16_t* As = smem + cur * STAGE;
     const bf16_t* Bs = As + OpA::ELEMS;
 #pragma unroll
-    for (int kk = 0; kk < kBK / 16; ++kk) {
+    for (int kk = 0; kk < BK / 16; ++kk) {
       bf16x8_t af[MT], bfr[NT];
 #pragma unroll
       for (int i = 0; i < MT; ++i) af[i] = OpA::frag(As, wm * WM + i * 32, kk, lane);
@@ -286,19 +288,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, class TO>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, int BK, class TO>
 static void launch_mfma(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
                         hipStream_t st, int k_splits = 1) {
   constexpr int NTHREADS = 64 * WAVES_M * WAVES_N;
-  constexpr size_t lds = 2 * (size_t)(OperandTile<AT, BM, NTHREADS>::ELEMS + OperandTile<BT, BN, NTHREADS>::ELEMS) * sizeof(bf16_t);
+  constexpr size_t lds = 2 * (size_t)(OperandTile<AT, BM, NTHREADS, BK>::ELEMS + OperandTile<BT, BN, NTHREADS, BK>::ELEMS) * sizeof(bf16_t);
   static bool configured = false;
   if (!configured) {
-    hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, TO>),
+    hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, BK, TO>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     configured = true;
   }
   const int tiles_m = M / BM, tiles_n = N / BN;
-  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, TO>), dim3(tiles_m * tiles_n, k_splits), dim3(NTHREADS), lds, st,
+  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, BK, TO>), dim3(tiles_m * tiles_n, k_splits), dim3(NTHREADS), lds, st,
                      (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (TO*)C, ldc, M, N, K, e, tiles_m, tiles_n);
 }
 
@@ -546,9 +548,9 @@ static void launch_mfma_modes(const void* A, int lda, const void* B, int ldb, vo
     // does not depend on which slice arrives first.
     const int splits = (tiles <= 128 && K >= 2048 && (K / kBK) % 2 == 0 && !e.gelu) ? 2 : 1;
     if (splits > 1) fill_f32((float*)C, 0.f, (int64_t)M * ldc, st);
-    launch_mfma<128, 128, 2, 2, AT, BT, float>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
+    launch_mfma<128, 128, 2, 2, AT, BT, kRegBK, float>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
   } else {
-    launch_mfma<128, 128, 2, 2, AT, BT, bf16_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+    launch_mfma<128, 128, 2, 2, AT, BT, kRegBK, bf16_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
   }
 }
 
