@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstring>
 #include <string>
+#include <vector>
 
 using namespace mrem;
 
@@ -103,7 +104,7 @@ struct Plan {
   // teacher scratch
   size_t t_qkv, t_ctx, t_o, t_x1, t_g, t_y, t_mu, t_rstd;
   // backward scratch
-  size_t lg, dr2, dr1, dxh, dx1h, dch, dc, dgh, du, dqkvh, dqkv, s_da, s_ph, ds_rows, partials, grads, pmax;
+  size_t lg, dr2, dr1, dxh, dx1h, dch, dc, dgh, du, dqkvh, dqkv, s_da, s_ph, partials, partials_per_layer, grads, pmax;
   size_t total;
 };
 
@@ -134,13 +135,15 @@ Plan make_plan(const mrem_ctx* c, int B, int S) {
   const size_t widest = (3 * H > F ? 3 * H : F);
   const size_t s_pad = ((size_t)S + 31) / 32 * 32;
   const size_t pp = (size_t)B * c->nh * s_pad * s_pad;
-  p.s_da = b.take(pp * 4); p.s_ph = b.take(pp * 4); p.ds_rows = b.take((size_t)B * c->nh * S * 4);
+  p.s_da = b.take(pp * 4); p.s_ph = b.take(pp * 4);
   p.pmax = b.take((size_t)B * c->nh * S * 4);
-  size_t np = (size_t)ln_bwd_parts((int)T) * (3 * H + 1);
-  const size_t np2 = ((T + 31) / 32) * widest;
-  if (np2 > np) np = np2;
-  if (np < 2048 * 3) np = 2048 * 3;
-  p.partials = b.take(np * 4);
+  // first-stage partial sums of one layer's backward pass (all of them stay until the single
+  // second-stage launch at the end of the backward pass): two LayerNorms, two bias column sums,
+  // the elementwise kernels (at most 2048 blocks, up to 3 values each) and the attention rows
+  size_t np = 2 * (size_t)ln_bwd_parts((int)T) * (3 * H + 1) + ((T + 31) / 32) * (F + 3 * H) + 8 * 2048 + (size_t)B * c->nh * S;
+  np = (np + 63) & ~size_t(63);
+  p.partials_per_layer = np;
+  p.partials = b.take(np * 4 * c->L);
   p.grads = b.take((size_t)mrem_param_count(c) * 4);
   p.total = b.off;
   return p;
@@ -154,6 +157,18 @@ struct Run {
   int B, S, T;
   const int32_t* seqlens;
   template <class X = void> X* at(size_t off) const { return reinterpret_cast<X*>(ws + off); }
+};
+
+// Second-stage reductions of a backward pass, collected while the first-stage kernels are enqueued.
+struct Reductions {
+  std::vector<ReduceJob> jobs;
+  float* next = nullptr;  // bump pointer into the partials area
+  float* take(size_t n) { float* p = next; next += (n + 63) & ~size_t(63); return p; }
+  void add(const float* partials, int nparts, int width, int begin, int len, float* out, float scale = 1.f) {
+    ReduceJob j;
+    j.partials = partials; j.nparts = nparts; j.width = width; j.begin = begin; j.len = len; j.out = out; j.scale = scale;
+    jobs.push_back(j);
+  }
 };
 
 QArg make_q(const mrem_ctx* c, const float* params, int layer, int idx) {
@@ -306,8 +321,7 @@ void wgrad(const Run& r, const float* params, float* grads, int l, int i, const 
   float* g = grads + c->layer_stride * l;
   Epilogue e;
   const QArg q = make_q(c, params, l, kInQuant[i]);
-  if (q.on) e.alpha = q.s;
-  if (q.on && q.z) { e.beta = q.z; e.row_vec = g + c->foff[kBField[i]]; }
+  if (q.on) e.alpha = q.s;  // the offset term z * db[n] of an asymmetric input quantizer is added by the update kernel
   e.out_f32 = 1;
   gemm(c->dt, 1, 1, dy, c->wN[i], codes_in, c->wK[i], g + c->foff[kWField[i]], c->wK[i], c->wN[i], c->wK[i], r.T, e, r.st);
 }
@@ -319,12 +333,10 @@ void dgrad(const Run& r, int l, int i, const void* dy, void* out) {
 }
 
 // column sums of a [T, C] tensor into out[C] (bias gradients)
-void colsum(const Run& r, const void* a, int C, float* out) {
-  const mrem_ctx* c = r.c;
-  float* parts = r.at<float>(r.p.partials);
-  const int n = colsum_partials(c->dt, a, r.T, C, parts, r.st);
-  ReduceSeg sg{0, C, out};
-  reduce_partials(parts, n, C, &sg, 1, 1.f, r.st);
+void colsum(const Run& r, Reductions& red, const void* a, int C, float* out) {
+  float* parts = red.take((size_t)((r.T + 31) / 32) * C);
+  const int n = colsum_partials(r.c->dt, a, r.T, C, parts, r.st);
+  red.add(parts, n, C, 0, C, out);
 }
 
 void student_backward(const Run& r, const float* params, const void* x_q, const void* per_layer_fp, const void* per_layer_q,
@@ -333,8 +345,8 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
   const size_t es = dt_size(c->dt);
   const int H = c->H, F = c->F, T = r.T, L = c->L;
   const size_t slice = (size_t)T * H * es;
-  float* parts = r.at<float>(r.p.partials);
   const int64_t numel = (int64_t)T * H;
+  Reductions red;
   for (int l = L - 1; l >= 0; --l) {
     const LayerWs& w = r.p.lw[l];
     const float* base = params + c->layer_stride * l;
@@ -343,12 +355,13 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
     const void* fq = (const char*)per_layer_q + slice * l;
     const void* ffp = (const char*)per_layer_fp + slice * l;
     const bool in_loss = (c->cfg.loss_layer_mask >> l) & 1u;
+    red.next = r.at<float>(r.p.partials) + r.p.partials_per_layer * l;
     // Eq. 3 term of this layer and its gradient
     if (in_loss) {
       const float scale = c->cfg.loss_mean ? 1.0f / (float)numel : 1.0f;
+      float* parts = red.take(2048);
       const int n = mse_loss_grad(c->dt, fq, ffp, r.at(r.p.lg), numel, scale, parts, r.st);
-      ReduceSeg sg{0, 1, loss_out + 1 + l};
-      reduce_partials(parts, n, 1, &sg, 1, scale, r.st);
+      red.add(parts, n, 1, 0, 1, loss_out + 1 + l, scale);
     } else {
       fill_f32(loss_out + 1 + l, 0.f, 1, r.st);
     }
@@ -356,72 +369,81 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
     {
       const bool top = (l == L - 1);
       const QArg q_above = top ? QArg() : make_q(c, params, l + 1, 0);
+      float* parts = red.take((size_t)ln_bwd_parts(T) * (3 * H + 1));
       const int n = ln_bwd(c->dt, top ? nullptr : r.at(r.p.dr1), in_loss ? r.at(r.p.lg) : nullptr, top ? nullptr : r.at(r.p.dxh), fq,
                            q_above, r.at(w.x1), r.at(w.y), r.at<float>(w.mu2), r.at<float>(w.rstd2), base + c->foff[MREM_F_LN2_G],
                            r.at(r.p.dr2), parts, T, H, r.st);
-      ReduceSeg sg[4] = {{0, H, g + c->foff[MREM_F_LN2_G]}, {H, H, g + c->foff[MREM_F_LN2_B]}, {2 * H, H, g + c->foff[MREM_F_B_2]},
-                         {3 * H, 1, top ? nullptr : grads + c->layer_stride * (l + 1) + c->foff[MREM_F_S_A] + 0}};
-      reduce_partials(parts, n, 3 * H + 1, sg, top ? 3 : 4, 1.f, r.st);
+      const int wd = 3 * H + 1;
+      red.add(parts, n, wd, 0, H, g + c->foff[MREM_F_LN2_G]);
+      red.add(parts, n, wd, H, H, g + c->foff[MREM_F_LN2_B]);
+      red.add(parts, n, wd, 2 * H, H, g + c->foff[MREM_F_B_2]);
+      if (!top) red.add(parts, n, wd, 3 * H, 1, grads + c->layer_stride * (l + 1) + c->foff[MREM_F_S_A] + 0);
     }
     // second feed-forward projection
     wgrad(r, params, grads, l, 3, r.at(r.p.dr2), r.at(w.gcodes));
     dgrad(r, l, 3, r.at(r.p.dr2), r.at(r.p.dgh));
     // GELU and its output quantizer
     {
+      float* parts = red.take(2048);
       const int n = gelu_quant_bwd(c->dt, r.at(r.p.dgh), r.at(w.u), r.at(r.p.du), (int64_t)T * F, make_q(c, params, l, 7), parts, r.st);
-      ReduceSeg sg{0, 1, g + c->foff[MREM_F_S_A] + 7};
-      reduce_partials(parts, n, 1, &sg, 1, 1.f, r.st);
+      red.add(parts, n, 1, 0, 1, g + c->foff[MREM_F_S_A] + 7);
     }
     // first feed-forward projection
-    colsum(r, r.at(r.p.du), F, g + c->foff[MREM_F_B_1]);
+    colsum(r, red, r.at(r.p.du), F, g + c->foff[MREM_F_B_1]);
     wgrad(r, params, grads, l, 2, r.at(r.p.du), r.at(w.x1codes));
     dgrad(r, l, 2, r.at(r.p.du), r.at(r.p.dx1h));
     // first LayerNorm: dy = dr2 (residual) + dx1h through the FFN-input quantizer
     {
+      float* parts = red.take((size_t)ln_bwd_parts(T) * (3 * H + 1));
       const int n = ln_bwd(c->dt, r.at(r.p.dr2), nullptr, r.at(r.p.dx1h), r.at(w.x1), make_q(c, params, l, 6), x, r.at(w.o),
                            r.at<float>(w.mu1), r.at<float>(w.rstd1), base + c->foff[MREM_F_LN1_G], r.at(r.p.dr1), parts, T, H, r.st);
-      ReduceSeg sg[4] = {{0, H, g + c->foff[MREM_F_LN1_G]}, {H, H, g + c->foff[MREM_F_LN1_B]}, {2 * H, H, g + c->foff[MREM_F_B_O]},
-                         {3 * H, 1, g + c->foff[MREM_F_S_A] + 6}};
-      reduce_partials(parts, n, 3 * H + 1, sg, 4, 1.f, r.st);
+      const int wd = 3 * H + 1;
+      red.add(parts, n, wd, 0, H, g + c->foff[MREM_F_LN1_G]);
+      red.add(parts, n, wd, H, H, g + c->foff[MREM_F_LN1_B]);
+      red.add(parts, n, wd, 2 * H, H, g + c->foff[MREM_F_B_O]);
+      red.add(parts, n, wd, 3 * H, 1, g + c->foff[MREM_F_S_A] + 6);
     }
     // attention output projection
     wgrad(r, params, grads, l, 1, r.at(r.p.dr1), r.at(w.ctxcodes));
     dgrad(r, l, 1, r.at(r.p.dr1), r.at(r.p.dch));
     {
+      float* parts = red.take(2048);
       const int n = quant_bwd(c->dt, r.at(r.p.dch), r.at(w.ctx), r.at(r.p.dc), numel, make_q(c, params, l, 5), parts, r.st);
-      ReduceSeg sg{0, 1, g + c->foff[MREM_F_S_A] + 5};
-      reduce_partials(parts, n, 1, &sg, 1, 1.f, r.st);
+      red.add(parts, n, 1, 0, 1, g + c->foff[MREM_F_S_A] + 5);
     }
     // attention
     const AttnQ aq = make_attn_q(c, params, l, true);
     {
       int n = r.B * c->nh * r.S;
+      float* parts = red.take((size_t)n);
       if (attn_mfma_ok(c->dt, r.S, c->d))
         n = attn_bwd_mfma(r.at(w.qkvcodes), r.at(r.p.dc), r.at(r.p.dqkvh), aq, r.seqlens, r.B, r.S, c->nh, r.at<float>(w.stat_m),
-                          r.at<float>(w.stat_l), r.at(r.p.s_ph), r.at(r.p.s_da), r.at<float>(r.p.ds_rows), r.st);
+                          r.at<float>(w.stat_l), r.at(r.p.s_ph), r.at(r.p.s_da), parts, r.st);
       else
         attn_bwd(c->dt, r.at(w.qkvcodes), r.at(r.p.dc), r.at(r.p.dqkvh), aq, r.seqlens, r.B, r.S, c->nh, c->d, r.at<float>(r.p.s_da),
-                 r.at<float>(r.p.s_ph), r.at<float>(r.p.ds_rows), r.st);
-      ReduceSeg sg{0, 1, g + c->foff[MREM_F_S_A] + 3};
-      reduce_partials(r.at<float>(r.p.ds_rows), n, 1, &sg, 1, 1.f, r.st);
+                 r.at<float>(r.p.s_ph), parts, r.st);
+      red.add(parts, n, 1, 0, 1, g + c->foff[MREM_F_S_A] + 3);
     }
     {
+      float* parts = red.take(2048 * 3);
       const int n = qkv_quant_bwd(c->dt, r.at(r.p.dqkvh), r.at(w.qkv), r.at(r.p.dqkv), T, H, aq.q, aq.k, aq.v, parts, r.st);
-      ReduceSeg sg[3] = {{0, 1, g + c->foff[MREM_F_S_A] + 1}, {1, 1, g + c->foff[MREM_F_S_A] + 2}, {2, 1, g + c->foff[MREM_F_S_A] + 4}};
-      reduce_partials(parts, n, 3, sg, 3, 1.f, r.st);
+      red.add(parts, n, 3, 0, 1, g + c->foff[MREM_F_S_A] + 1);
+      red.add(parts, n, 3, 1, 1, g + c->foff[MREM_F_S_A] + 2);
+      red.add(parts, n, 3, 2, 1, g + c->foff[MREM_F_S_A] + 4);
     }
     // query/key/value projection
-    colsum(r, r.at(r.p.dqkv), 3 * H, g + c->foff[MREM_F_B_QKV]);
+    colsum(r, red, r.at(r.p.dqkv), 3 * H, g + c->foff[MREM_F_B_QKV]);
     wgrad(r, params, grads, l, 0, r.at(r.p.dqkv), r.at(w.xcodes));
     dgrad(r, l, 0, r.at(r.p.dqkv), r.at(r.p.dxh));
     if (l == 0) {
       // nothing flows out of the module (Section 4.2); only the input quantizer's step needs dxh
+      float* parts = red.take(2048);
       const int n = quant_bwd_reduce(c->dt, r.at(r.p.dxh), x, numel, make_q(c, params, 0, 0), parts, r.st);
-      ReduceSeg sg{0, 1, g + c->foff[MREM_F_S_A] + 0};
-      reduce_partials(parts, n, 1, &sg, 1, 1.f, r.st);
+      red.add(parts, n, 1, 0, 1, g + c->foff[MREM_F_S_A] + 0);
     }
     fill_f32(g + c->foff[MREM_F_Z_A], 0.f, 8, r.st);
   }
+  reduce_jobs(red.jobs.data(), (int)red.jobs.size(), r.st);
   loss_total(loss_out, L, r.st);
 }
 
@@ -438,8 +460,11 @@ void apply_update(const Run& r, float* params, float* grads, float* m, float* v,
     const int64_t o = c->layer_stride * l;
     for (int i = 0; i < 4; ++i) {
       const int64_t ow = o + c->foff[kWField[i]], os = o + c->foff[kSField[i]];
+      // the second feed-forward projection reads the GELU output through an asymmetric quantizer with offset z
+      const bool zterm = (i == 3 && c->cfg.a_bits > 0);
       adam_matrix(params + ow, params + os, grads + ow, grads + os, m + ow, v + ow, m + os, v + os, c->wN[i], c->wK[i], c->cfg.w_bits, a,
-                  write_grads, r.st);
+                  write_grads, zterm ? params + o + c->foff[MREM_F_Z_A] + 7 : nullptr, zterm ? grads + o + c->foff[MREM_F_B_2] : nullptr,
+                  r.st);
     }
     const int64_t ob = o + c->foff[MREM_F_B_QKV];
     const int64_t nb = c->foff[MREM_F_SW_QKV] - c->foff[MREM_F_B_QKV];

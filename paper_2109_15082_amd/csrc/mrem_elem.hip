@@ -487,61 +487,65 @@ int colsum_partials(int dt, const void* a, int R, int C, float* partials, hipStr
 }
 
 // ------------------------------------------------------------------------------
-// second stage of the two-stage reductions (fixed order => run-to-run identical)
+// second stage of the two-stage reductions (fixed order => run-to-run identical).
+// All first-stage kernels of a backward pass leave their partial sums in the workspace;
+// one launch of this kernel then finishes up to kMaxReduceJobs of them.
 // ------------------------------------------------------------------------------
-struct ReduceSegs {
-  ReduceSeg s[4];
+struct ReduceJobTable {
+  ReduceJob j[kMaxReduceJobs];
+  int unit_start[kMaxReduceJobs + 1];  // prefix sums of work units (16 columns each; 1 for a scalar)
   int n;
 };
-__global__ __launch_bounds__(256) void reduce_partials_k(const float* __restrict__ partials, int nparts, int width, ReduceSegs segs,
-                                                         float scale) {
+__global__ __launch_bounds__(256) void reduce_jobs_k(ReduceJobTable t) {
   // 256 threads = 16 columns x 16 groups of partial rows; the group sums are added in group
   // order, so the result does not depend on scheduling.
   __shared__ float red[16][17];
   __shared__ float sred[17];
+  int ji = 0;
+  while (ji + 1 < t.n && (int)blockIdx.x >= t.unit_start[ji + 1]) ++ji;
+  const ReduceJob jb = t.j[ji];
+  const int unit = blockIdx.x - t.unit_start[ji];
+  if (jb.len == 1) {
+    float v = 0.f;
+    for (int p = threadIdx.x; p < jb.nparts; p += blockDim.x) v += jb.partials[(size_t)p * jb.width + jb.begin];
+    v = block_sum(v, sred);
+    if (threadIdx.x == 0) jb.out[0] = v * jb.scale;
+    return;
+  }
   const int col = threadIdx.x & 15, grp = threadIdx.x >> 4;
-  for (int k = 0; k < segs.n; ++k) {
-    const ReduceSeg sg = segs.s[k];
-    if (sg.len == 1) {
-      if (blockIdx.x == 0) {
-        float t = 0.f;
-        for (int p = threadIdx.x; p < nparts; p += blockDim.x) t += partials[(size_t)p * width + sg.begin];
-        t = block_sum(t, sred);
-        if (threadIdx.x == 0) sg.out[0] = t * scale;
-      }
-      continue;
+  const int c = unit * 16 + col;
+  float t0 = 0.f, t1 = 0.f;
+  if (c < jb.len) {
+    const float* src = jb.partials + jb.begin + c;
+    int p = grp;
+    for (; p + 16 < jb.nparts; p += 32) {
+      t0 += src[(size_t)p * jb.width];
+      t1 += src[(size_t)(p + 16) * jb.width];
     }
-    for (int c0 = blockIdx.x * 16; c0 < sg.len; c0 += gridDim.x * 16) {
-      const int c = c0 + col;
-      float t0 = 0.f, t1 = 0.f;
-      if (c < sg.len) {
-        const float* src = partials + sg.begin + c;
-        int p = grp;
-        for (; p + 16 < nparts; p += 32) {
-          t0 += src[(size_t)p * width];
-          t1 += src[(size_t)(p + 16) * width];
-        }
-        for (; p < nparts; p += 16) t0 += src[(size_t)p * width];
-      }
-      red[grp][col] = t0 + t1;
-      __syncthreads();
-      if (grp == 0 && c < sg.len) {
-        float t = 0.f;
+    for (; p < jb.nparts; p += 16) t0 += src[(size_t)p * jb.width];
+  }
+  red[grp][col] = t0 + t1;
+  __syncthreads();
+  if (grp == 0 && c < jb.len) {
+    float v = 0.f;
 #pragma unroll
-        for (int g = 0; g < 16; ++g) t += red[g][col];
-        sg.out[c] = t * scale;
-      }
-      __syncthreads();
-    }
+    for (int g = 0; g < 16; ++g) v += red[g][col];
+    jb.out[c] = v * jb.scale;
   }
 }
-void reduce_partials(const float* partials, int nparts, int width, const ReduceSeg* segs, int nsegs, float scale, hipStream_t st) {
-  ReduceSegs s;
-  s.n = nsegs;
-  int maxlen = 1;
-  for (int i = 0; i < nsegs; ++i) { s.s[i] = segs[i]; if (segs[i].len > maxlen) maxlen = segs[i].len; }
-  int g = (maxlen + 15) / 16;
-  hipLaunchKernelGGL(reduce_partials_k, dim3(g), dim3(256), 0, st, partials, nparts, width, s, scale);
+void reduce_jobs(const ReduceJob* jobs, int njobs, hipStream_t st) {
+  for (int first = 0; first < njobs; first += kMaxReduceJobs) {
+    ReduceJobTable t;
+    t.n = njobs - first < kMaxReduceJobs ? njobs - first : kMaxReduceJobs;
+    int units = 0;
+    for (int i = 0; i < t.n; ++i) {
+      t.j[i] = jobs[first + i];
+      t.unit_start[i] = units;
+      units += t.j[i].len == 1 ? 1 : (t.j[i].len + 15) / 16;
+    }
+    t.unit_start[t.n] = units;
+    hipLaunchKernelGGL(reduce_jobs_k, dim3(units), dim3(256), 0, st, t);
+  }
 }
 
 __global__ void loss_total_k(float* loss_out, int n_layers) {
@@ -738,10 +742,12 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void adam_matrix_k(float* __restrict__ w, float* __restrict__ sw, float* __restrict__ g_w,
                                                      float* __restrict__ g_sw, float* __restrict__ m_w, float* __restrict__ v_w,
                                                      float* __restrict__ m_sw, float* __restrict__ v_sw, int K, float qp, int on, AdamArg a,
-                                                     int write_grads) {
+                                                     int write_grads, const float* __restrict__ z_in, const float* __restrict__ db) {
   __shared__ float red[17];
   const int n = blockIdx.x;
   const float s = on ? sw[n] : 1.f;
+  // offset term of an asymmetric input quantizer: d(loss)/d(w_hat[n,:]) += z * sum_t dy[t,n]
+  const float zterm = z_in ? (*z_in) * db[n] : 0.f;
   float acc = 0.f;
   const size_t row = (size_t)n * K;
   for (int k = threadIdx.x * 4; k < K; k += blockDim.x * 4) {
@@ -752,7 +758,8 @@ __global__ __launch_bounds__(256) void adam_matrix_k(float* __restrict__ w, floa
     f32x4_t vv = *reinterpret_cast<const f32x4_t*>(v_w + i);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      float gj = g[j];
+      float gj = g[j] + zterm;
+      g[j] = gj;
       if (on) {
         const float v = __fdiv_rn(x[j], s);
         const bool in = (v >= -qp) && (v <= qp);
@@ -769,7 +776,7 @@ __global__ __launch_bounds__(256) void adam_matrix_k(float* __restrict__ w, floa
     *reinterpret_cast<f32x4_t*>(w + i) = x;
     *reinterpret_cast<f32x4_t*>(m_w + i) = m;
     *reinterpret_cast<f32x4_t*>(v_w + i) = vv;
-    if (on && write_grads) *reinterpret_cast<f32x4_t*>(g_w + i) = g;
+    if (write_grads && (on || z_in)) *reinterpret_cast<f32x4_t*>(g_w + i) = g;
   }
   if (on) {
     acc = block_sum(acc, red);
@@ -788,10 +795,10 @@ __global__ __launch_bounds__(256) void adam_matrix_k(float* __restrict__ w, floa
   }
 }
 void adam_matrix(float* w, float* sw, float* g_w, float* g_sw, float* m_w, float* v_w, float* m_sw, float* v_sw, int N, int K,
-                 int bits, AdamArg a, int write_grads, hipStream_t st) {
+                 int bits, AdamArg a, int write_grads, const float* z_in, const float* db, hipStream_t st) {
   const int on = bits > 0;
   const float qp = on ? (float)((1 << (bits - 1)) - 1) : 0.f;
-  hipLaunchKernelGGL(adam_matrix_k, dim3(N), dim3(256), 0, st, w, sw, g_w, g_sw, m_w, v_w, m_sw, v_sw, K, qp, on, a, write_grads);
+  hipLaunchKernelGGL(adam_matrix_k, dim3(N), dim3(256), 0, st, w, sw, g_w, g_sw, m_w, v_w, m_sw, v_sw, K, qp, on, a, write_grads, z_in, db);
 }
 
 __global__ void adam_vector_k(float* __restrict__ p, const float* __restrict__ g, float* __restrict__ m, float* __restrict__ v,

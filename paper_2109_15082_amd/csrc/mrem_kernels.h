@@ -84,13 +84,16 @@ int mse_loss_grad(int dt, const void* fq, const void* ffp, void* grad, int64_t n
 // partials[R/32][C]: column sums of 32-row slabs of a[R,C]; returns the number of slabs
 int colsum_partials(int dt, const void* a, int R, int C, float* partials, hipStream_t st);
 
-// out_k[c] = scale * sum_p partials[p*width + begin_k + c]  for up to 4 segments
-struct ReduceSeg {
-  int begin = 0, len = 0;
+// out[c] = scale * sum_p partials[p*width + begin + c], c < len.  Jobs are collected on the
+// host while the first-stage kernels are enqueued and finished by reduce_jobs afterwards.
+struct ReduceJob {
+  const float* partials = nullptr;
   float* out = nullptr;
+  int nparts = 0, width = 0, begin = 0, len = 0;
+  float scale = 1.f;
 };
-void reduce_partials(const float* partials, int nparts, int width, const ReduceSeg* segs, int nsegs, float scale,
-                     hipStream_t st);
+constexpr int kMaxReduceJobs = 64;
+void reduce_jobs(const ReduceJob* jobs, int njobs, hipStream_t st);
 void loss_total(float* loss_out, int n_layers, hipStream_t st);
 void fill_f32(float* p, float v, int64_t n, hipStream_t st);
 void axpby(int dt, const void* a, const void* b, float wa, float wb, void* out, int64_t n, hipStream_t st);
@@ -137,9 +140,10 @@ struct AdamArg {
   float floor;                                // lower bound applied when clamp != 0
 };
 // one block per row n of w[N,K]: straight-through mask on dw_hat (in grads), row
-// reduction for the step gradient, AdamW on w[n,:] and on sw[n]
+// reduction for the step gradient, AdamW on w[n,:] and on sw[n].  z_in/db (may be null):
+// offset of an asymmetric input quantizer and the bias gradient, dw_hat[n,:] += z * db[n].
 void adam_matrix(float* w, float* sw, float* g_w, float* g_sw, float* m_w, float* v_w, float* m_sw, float* v_sw, int N,
-                 int K, int bits, AdamArg a, int write_grads, hipStream_t st);
+                 int K, int bits, AdamArg a, int write_grads, const float* z_in, const float* db, hipStream_t st);
 void adam_vector(float* p, const float* g, float* m, float* v, int64_t n, AdamArg a, int clamp, hipStream_t st);
 
 }  // namespace mrem
