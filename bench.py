@@ -18,6 +18,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per matrix-product launch (read + written), from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE), each scaled by what the counter reads for a 256 MiB device copy; summary with the commands in
+# profiles/module_step_bert_large_6l_hbm_traffic.md.  Only for the workload it was measured on.
+MEASURED_GEMM_TRAFFIC_BYTES = {"bert_large_6l": 89.8e6}
 
 
 def step_flops(wl):
@@ -67,6 +71,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="bert_large_6l")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 256 MiB device copy before the steps (the known-size kernel that scales "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one module step on ONE GPU (the paper's per-module model parallelism reduces to "
@@ -93,6 +100,11 @@ def main():
     mod.calibrate(x, sl)
     out_fp, out_q = mod.new_outputs(wl.batch, wl.seq)
     lr0, total = 1e-4, args.steps + args.warmup
+    if args.copy_probe:
+        probe = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        probe_dst = torch.empty_like(probe)
+        torch.cuda.synchronize()
+        probe_dst.copy_(probe)   # reads 256 MiB, writes 256 MiB
     torch.cuda.synchronize()
 
     t = 0
@@ -125,7 +137,8 @@ def main():
                    "tokens_per_step": wl.tokens, "step_tflop": flops_total / 1e12, "loss_last_step": float(losses[0])},
         "roofline": {"bound": "mfma", "kernel": "gemm_nt (all matrix products of the linear layers)",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(wl.name),
+                     "traffic_unit": "bytes/launch",
                      "launches_per_step": gemm_launches / args.steps,
                      "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
                      "gemm_ms_per_step": gemm_ms / args.steps,
