@@ -29,10 +29,27 @@ __device__ __forceinline__ float round_to<bf16_t>(float v) { return static_cast<
 // inside = [qn <= v <= qp] is the straight-through mask (Section 3.1.1).
 struct QuantParam {
   float s, z, qn, qp;
-  int on;  // 0: quantizer disabled (identity)
+  int on;    // 0: quantizer disabled (identity)
+  float rs;  // correctly rounded 1 / s (only for q_ratio_fma)
 };
 
 __device__ __forceinline__ float q_ratio(float a, const QuantParam& q) { return __fdiv_rn(__fsub_rn(a, q.z), q.s); }
+// The same quotient without the division sequence: t = fl(n * rs), then t + fl(n - s * t) * rs with
+// fused multiply-adds.  With rs the correctly rounded reciprocal, the residual n - s * t is exact
+// and the last operation rounds the true quotient (the residual-correction step of FMA division);
+// activations and step sizes are far from the overflow and underflow ranges where that needs
+// care.  One step size serves millions of elements, so the reciprocal is taken once per thread.
+__device__ __forceinline__ float q_ratio_fma(float a, const QuantParam& q) {
+  const float n = __fsub_rn(a, q.z);
+  const float t = __fmul_rn(n, q.rs);
+  return __fmaf_rn(__fmaf_rn(-q.s, t, n), q.rs, t);
+}
+// fp32 storage (the check mode) divides; bf16 storage uses the FMA form
+template <class T>
+__device__ __forceinline__ float q_ratio_t(float a, const QuantParam& q) {
+  if constexpr (sizeof(T) == 4) return q_ratio(a, q);
+  else return q_ratio_fma(a, q);
+}
 __device__ __forceinline__ float q_code(float v, const QuantParam& q) { return rintf(fminf(fmaxf(v, q.qn), q.qp)); }
 __device__ __forceinline__ bool q_inside(float v, const QuantParam& q) { return v >= q.qn && v <= q.qp; }
 
@@ -106,6 +123,33 @@ __device__ __forceinline__ bool last_block_arrives(unsigned* counter, unsigned n
 __device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f)); }
 __device__ __forceinline__ float gelu_grad_f(float u) {
   return 0.5f * (1.0f + erff(u * 0.70710678118654752440f)) + u * __expf(-0.5f * u * u) * 0.39894228040143267794f;
+}
+
+// erf(x) = 1 - 1 / (1 + a1 x + ... + a6 x^6)^16 for x >= 0 (Abramowitz & Stegun 7.1.28; absolute
+// error below 3e-7 in exact arithmetic, about 2e-6 in fp32): a fraction of the instructions of
+// erff, and far inside what survives the rounding of GELU outputs to bf16.
+__device__ __forceinline__ float erf_rational(float x) {
+  const float ax = fabsf(x);
+  float p = 0.0000430638f;
+  p = fmaf(p, ax, 0.0002765672f);
+  p = fmaf(p, ax, 0.0001520143f);
+  p = fmaf(p, ax, 0.0092705272f);
+  p = fmaf(p, ax, 0.0422820123f);
+  p = fmaf(p, ax, 0.0705230784f);
+  p = fmaf(p, ax, 1.0f);
+  p *= p; p *= p; p *= p; p *= p;
+  return copysignf(1.0f - __builtin_amdgcn_rcpf(p), x);
+}
+// GELU and its derivative for values stored as T: fp32 storage (the check mode) uses erff
+template <class T>
+__device__ __forceinline__ float gelu_t(float u) {
+  if constexpr (sizeof(T) == 4) return gelu_f(u);
+  else return 0.5f * u * (1.0f + erf_rational(u * 0.70710678118654752440f));
+}
+template <class T>
+__device__ __forceinline__ float gelu_grad_t(float u) {
+  if constexpr (sizeof(T) == 4) return gelu_grad_f(u);
+  else return 0.5f * (1.0f + erf_rational(u * 0.70710678118654752440f)) + u * __expf(-0.5f * u * u) * 0.39894228040143267794f;
 }
 
 }  // namespace mrem

@@ -47,6 +47,7 @@ __device__ __forceinline__ QuantParam load_q(const QArg& a) {
   q.z = (a.on && a.z) ? *a.z : 0.f;
   q.qn = a.qn;
   q.qp = a.qp;
+  q.rs = __fdiv_rn(1.0f, q.s);
   return q;
 }
 
@@ -74,7 +75,7 @@ __global__ void act_quantize_k(const T* __restrict__ a, T* __restrict__ codes, i
     load8(a + c * 8, v);
     if (q.on) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) v[j] = q_code(q_ratio(v[j], q), q);
+      for (int j = 0; j < 8; ++j) v[j] = q_code(q_ratio_t<T>(v[j], q), q);
     }
     store8(codes + c * 8, v);
   }
@@ -83,69 +84,102 @@ void act_quantize(int dt, const void* a, void* codes, int64_t n, QArg q, hipStre
   MREM_DISPATCH(dt, hipLaunchKernelGGL(act_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)a, (T*)codes, n / 8, q));
 }
 
-// three column sections of qkv[T,3H] with their own quantizers
+// Three column sections of qkv[T,3H] with their own quantizers.  A thread owns one 8-element
+// column chunk (so its quantizer is fixed) and walks down the rows, four rows in flight; a block
+// of 128 threads covers 2 KiB of a row.
+constexpr int kQkvThreads = 128, kQkvRows = 4;
+struct QkvGrid { int gx, gy; };
+static inline QkvGrid qkv_grid(int T_, int H) {
+  QkvGrid g;
+  g.gx = (3 * H / 8 + kQkvThreads - 1) / kQkvThreads;
+  const int groups = (T_ + kQkvRows - 1) / kQkvRows;
+  const int cap = 2048 / g.gx > 0 ? 2048 / g.gx : 1;  // the reductions downstream hold at most 2048 blocks
+  const int iters = (groups + cap - 1) / cap;          // every block walks the same number of row groups
+  g.gy = iters > 0 ? (groups + iters - 1) / iters : 1;
+  if (g.gy < 1) g.gy = 1;
+  return g;
+}
+__device__ __forceinline__ QuantParam pick_q(int sec, const QuantParam& a, const QuantParam& b, const QuantParam& c) {
+  return sec == 0 ? a : (sec == 1 ? b : c);
+}
+
 template <class T>
-__global__ void qkv_quantize_k(const T* __restrict__ a, T* __restrict__ codes, int64_t nchunks, int H8, QArg q0, QArg q1,
-                               QArg q2) {
-  const QuantParam qs[3] = {load_q(q0), load_q(q1), load_q(q2)};
-  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
-    const int sec = (int)((c % (3 * (int64_t)H8)) / H8);
-    const QuantParam q = qs[sec];
-    float v[8];
-    load8(a + c * 8, v);
-    if (q.on) {
+__global__ __launch_bounds__(kQkvThreads) void qkv_quantize_k(const T* __restrict__ a, T* __restrict__ codes, int T_, int H8, QArg q0,
+                                                               QArg q1, QArg q2) {
+  const int cc = blockIdx.x * kQkvThreads + threadIdx.x, row_chunks = 3 * H8;
+  if (cc >= row_chunks) return;
+  const QuantParam q = pick_q(cc / H8, load_q(q0), load_q(q1), load_q(q2));
+  for (int r0 = blockIdx.y * kQkvRows; r0 < T_; r0 += gridDim.y * kQkvRows) {
+    float v[kQkvRows][8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) v[j] = q_code(q_ratio(v[j], q), q);
+    for (int i = 0; i < kQkvRows; ++i)
+      if (r0 + i < T_) load8(a + ((size_t)(r0 + i) * row_chunks + cc) * 8, v[i]);
+#pragma unroll
+    for (int i = 0; i < kQkvRows; ++i) {
+      if (r0 + i >= T_) break;
+      if (q.on) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[i][j] = q_code(q_ratio_t<T>(v[i][j], q), q);
+      }
+      store8(codes + ((size_t)(r0 + i) * row_chunks + cc) * 8, v[i]);
     }
-    store8(codes + c * 8, v);
   }
 }
 void qkv_quantize(int dt, const void* qkv, void* codes, int T_, int H, QArg q, QArg k, QArg v, hipStream_t st) {
-  const int64_t n = (int64_t)T_ * 3 * H;
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(qkv_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)qkv, (T*)codes, n / 8,
+  const QkvGrid g = qkv_grid(T_, H);
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(qkv_quantize_k<T>, dim3(g.gx, g.gy), dim3(kQkvThreads), 0, st, (const T*)qkv, (T*)codes, T_,
                                        H / 8, q, k, v));
 }
 
 // d_out = d_q * inside ; partial[block][sec] += d_q * (code - v * inside)
 template <class T>
-__global__ void qkv_quant_bwd_k(const T* __restrict__ dq, const T* __restrict__ a, T* __restrict__ dout, int64_t nchunks,
-                                int H8, QArg q0, QArg q1, QArg q2, float* __restrict__ partials) {
+__global__ __launch_bounds__(kQkvThreads) void qkv_quant_bwd_k(const T* __restrict__ dq, const T* __restrict__ a, T* __restrict__ dout,
+                                                                int T_, int H8, QArg q0, QArg q1, QArg q2, float* __restrict__ partials) {
   __shared__ float red[17];
-  const QuantParam qs[3] = {load_q(q0), load_q(q1), load_q(q2)};
-  float acc[3] = {0.f, 0.f, 0.f};
-  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
-    const int sec = (int)((c % (3 * (int64_t)H8)) / H8);
-    const QuantParam q = qs[sec];
-    float g[8], x[8];
-    load8(dq + c * 8, g);
-    if (q.on) {
-      load8(a + c * 8, x);
-      float t = 0.f;
+  const int cc = blockIdx.x * kQkvThreads + threadIdx.x, row_chunks = 3 * H8;
+  const bool live = cc < row_chunks;
+  const int sec = live ? cc / H8 : 0;
+  const QuantParam q = pick_q(sec, load_q(q0), load_q(q1), load_q(q2));
+  float acc = 0.f;
+  if (live) {
+    for (int r0 = blockIdx.y * kQkvRows; r0 < T_; r0 += gridDim.y * kQkvRows) {
+      float g[kQkvRows][8], x[kQkvRows][8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float v = q_ratio(x[j], q);
-        const bool in = q_inside(v, q);
-        t += g[j] * (q_code(v, q) - (in ? v : 0.f));
-        g[j] = in ? g[j] : 0.f;
+      for (int i = 0; i < kQkvRows; ++i) {
+        if (r0 + i < T_) {
+          const size_t o = ((size_t)(r0 + i) * row_chunks + cc) * 8;
+          load8(dq + o, g[i]);
+          if (q.on) load8(a + o, x[i]);
+        }
       }
-      acc[0] += sec == 0 ? t : 0.f;
-      acc[1] += sec == 1 ? t : 0.f;
-      acc[2] += sec == 2 ? t : 0.f;
+#pragma unroll
+      for (int i = 0; i < kQkvRows; ++i) {
+        if (r0 + i >= T_) break;
+        if (q.on) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float v = q_ratio_t<T>(x[i][j], q);
+            const bool in = q_inside(v, q);
+            acc += g[i][j] * (q_code(v, q) - (in ? v : 0.f));
+            g[i][j] = in ? g[i][j] : 0.f;
+          }
+        }
+        if (dout) store8(dout + ((size_t)(r0 + i) * row_chunks + cc) * 8, g[i]);
+      }
     }
-    if (dout) store8(dout + c * 8, g);
   }
+  const int block = blockIdx.y * gridDim.x + blockIdx.x;
   for (int s = 0; s < 3; ++s) {
-    const float t = block_sum(acc[s], red);
-    if (threadIdx.x == 0) partials[blockIdx.x * 3 + s] = t;
+    const float t = block_sum((live && sec == s) ? acc : 0.f, red);
+    if (threadIdx.x == 0) partials[block * 3 + s] = t;
   }
 }
 int qkv_quant_bwd(int dt, const void* d_qkvh, const void* qkv, void* d_qkv, int T_, int H, QArg q, QArg k, QArg v,
                   float* partials, hipStream_t st) {
-  const int64_t n = (int64_t)T_ * 3 * H;
-  const int g = ew_grid(n);
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(qkv_quant_bwd_k<T>, dim3(g), dim3(256), 0, st, (const T*)d_qkvh, (const T*)qkv,
-                                       (T*)d_qkv, n / 8, H / 8, q, k, v, partials));
-  return g;
+  const QkvGrid g = qkv_grid(T_, H);
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(qkv_quant_bwd_k<T>, dim3(g.gx, g.gy), dim3(kQkvThreads), 0, st, (const T*)d_qkvh, (const T*)qkv,
+                                       (T*)d_qkv, T_, H / 8, q, k, v, partials));
+  return g.gx * g.gy;
 }
 
 // generic single-quantizer backward (d_out may be null: reduction only)
@@ -162,7 +196,7 @@ __global__ void quant_bwd_k(const T* __restrict__ dq, const T* __restrict__ a, T
       load8(a + c * 8, x);
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const float v = q_ratio(x[j], q);
+        const float v = q_ratio_t<T>(x[j], q);
         const bool in = q_inside(v, q);
         acc += g[j] * (q_code(v, q) - (in ? v : 0.f));
         g[j] = in ? g[j] : 0.f;
@@ -194,8 +228,8 @@ __global__ void gelu_quantize_k(const T* __restrict__ u, T* __restrict__ codes, 
     load8(u + c * 8, v);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const float g = gelu_f(v[j]);
-      v[j] = q.on ? q_code(q_ratio(g, q), q) : g;
+      const float g = gelu_t<T>(v[j]);
+      v[j] = q.on ? q_code(q_ratio_t<T>(g, q), q) : g;
     }
     store8(codes + c * 8, v);
   }
@@ -218,12 +252,12 @@ __global__ void gelu_quant_bwd_k(const T* __restrict__ dgh, const T* __restrict_
     for (int j = 0; j < 8; ++j) {
       float dg = g[j];
       if (q.on) {
-        const float v = q_ratio(gelu_f(x[j]), q);
+        const float v = q_ratio_t<T>(gelu_t<T>(x[j]), q);
         const bool in = q_inside(v, q);
         acc += dg * (q_code(v, q) - (in ? v : 0.f));
         dg = in ? dg : 0.f;
       }
-      g[j] = dg * gelu_grad_f(x[j]);
+      g[j] = dg * gelu_grad_t<T>(x[j]);
     }
     store8(du + c * 8, g);
   }
@@ -291,7 +325,7 @@ __global__ void ln_fwd_k(const T* __restrict__ x, const T* __restrict__ r, const
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const float s = round_to<T>(o[j]);
-          o[j] = q.on ? q_code(q_ratio(s, q), q) : s;
+          o[j] = q.on ? q_code(q_ratio_t<T>(s, q), q) : s;
         }
         store8(ycodes + (size_t)row * H + c * 8, o);
       }
@@ -351,7 +385,7 @@ __global__ __launch_bounds__(64 * kLnBwdRows) void ln_bwd_k(const T* __restrict_
             load8(a_q + off, av);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-              const float v = q_ratio(av[j], q);
+              const float v = q_ratio_t<T>(av[j], q);
               const bool in = q_inside(v, q);
               ds_acc += t[j] * (q_code(v, q) - (in ? v : 0.f));
               t[j] = in ? t[j] : 0.f;
@@ -677,7 +711,7 @@ __global__ void absminmax_k(const T* __restrict__ a, int rows, int cols, int ld,
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
     const int64_t r = i / cols, c = i - r * cols;
     float v = ldf(a, (size_t)(r * ld + c));
-    if (gelu) v = gelu_f(v);
+    if (gelu) v = gelu_t<T>(v);
     amax = fmaxf(amax, fabsf(v));
     mn = fminf(mn, v);
     mx = fmaxf(mx, v);

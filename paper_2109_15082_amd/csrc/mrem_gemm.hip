@@ -52,7 +52,7 @@ __device__ __forceinline__ void epilogue_store(TO* C, int ldc, int m, int n, flo
   float v = acc * (ev.alpha * (e.col_scale ? e.col_scale[n] : 1.f));
   if (e.beta) v += ev.beta * ((e.col_vec ? e.col_vec[n] : 0.f) + (e.row_vec ? e.row_vec[m] : 0.f));
   if (e.bias) v += e.bias[n];
-  if (e.gelu) v = gelu_f(round_to<TO>(v));
+  if (e.gelu) v = gelu_t<TO>(round_to<TO>(v));
   stf(C, (size_t)m * ldc + n, v);
 }
 
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16
             continue;
           }
         }
-        if (e.gelu) v = gelu_f(round_to<TO>(v));
+        if (e.gelu) v = gelu_t<TO>(round_to<TO>(v));
         stf(C, (size_t)m * ldc + n, v);
       }
     }
@@ -486,7 +486,7 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + kProducers)) void gemm_nt
             continue;
           }
         }
-        if (e.gelu) v = gelu_f(round_to<TO>(v));
+        if (e.gelu) v = gelu_t<TO>(round_to<TO>(v));
         stf(C, (size_t)m * ldc + n, v);
       }
     }
