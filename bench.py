@@ -111,14 +111,24 @@ def main():
     for _ in range(args.warmup):
         mod.step(x, x, lr0 * (1 - t / total), sl, out_fp, out_q)
         t += 1
+    # pass 1, the timed region: K steps, nothing but the steps on the stream
     torch.cuda.synchronize()
-    B.mrem_profile_gemm_begin()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         mod.step(x, x, lr0 * (1 - t / total), sl, out_fp, out_q)
         t += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # pass 2, the same K steps again with a HIP event pair around every matrix-product launch (on the
+    # stream the products run on).  Kept out of pass 1 because each recorded event stalls the queue for
+    # about 5 us, which with 96 products a step would add about a millisecond to every step.
+    B.mrem_profile_gemm_begin()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        mod.step(x, x, lr0 * (1 - (t % total) / total), sl, out_fp, out_q)
+        t += 1
+    torch.cuda.synchronize()
+    dt_events = time.perf_counter() - t1
     gemm_ms, gemm_flops, gemm_launches = B.mrem_profile_gemm_end()
     losses = mod.loss.cpu().numpy()
     assert np.isfinite(losses).all(), losses
@@ -142,6 +152,8 @@ def main():
                      "launches_per_step": gemm_launches / args.steps,
                      "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
                      "gemm_ms_per_step": gemm_ms / args.steps,
+                     "measured_on": "a second pass of the same K steps with an event pair around every product launch",
+                     "ms_per_step_with_events": dt_events * 1e3 / args.steps,
                      "flops_per_launch": gemm_flops / max(gemm_launches, 1)},
         "step_tflops": flops_total / 1e12 / (ms_per_step * 1e-3),
     }
