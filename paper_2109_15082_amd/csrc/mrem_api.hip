@@ -212,12 +212,19 @@ void student_linear(const Run& r, const float* params, int l, int i, const void*
 
 void prepare_weights(const Run& r, const float* params) {
   const mrem_ctx* c = r.c;
+  std::vector<WeightJob> jobs;
+  jobs.reserve((size_t)c->L * 4);
   for (int l = 0; l < c->L; ++l) {
     const float* base = params + c->layer_stride * l;
-    for (int i = 0; i < 4; ++i)
-      weight_prepare(c->dt, base + c->foff[kWField[i]], base + c->foff[kSField[i]], c->wN[i], c->wK[i], c->cfg.w_bits,
-                     r.at(r.p.lw[l].wcodes[i]), r.at(r.p.lw[l].what[i]), r.at<float>(r.p.lw[l].zcorr[i]), r.st);
+    for (int i = 0; i < 4; ++i) {
+      WeightJob j;
+      j.w = base + c->foff[kWField[i]]; j.sw = base + c->foff[kSField[i]];
+      j.codes = r.at(r.p.lw[l].wcodes[i]); j.what = r.at(r.p.lw[l].what[i]); j.zcorr = r.at<float>(r.p.lw[l].zcorr[i]);
+      j.N = c->wN[i]; j.K = c->wK[i];
+      jobs.push_back(j);
+    }
   }
+  weight_prepare(c->dt, jobs.data(), (int)jobs.size(), c->cfg.w_bits, r.st);
 }
 
 void student_forward(const Run& r, const float* params, const void* x_q, void* per_layer_q) {
@@ -456,16 +463,27 @@ void apply_update(const Run& r, float* params, float* grads, float* m, float* v,
   a.floor = c->cfg.step_floor;
   AdamArg nodecay = a;
   nodecay.wd = 0.f;
+  // the matrices first (they read the bias gradient and the activation offset of their layer), then the vectors
+  std::vector<AdamJob> jobs;
+  jobs.reserve((size_t)c->L * 4);
   for (int l = 0; l < c->L; ++l) {
     const int64_t o = c->layer_stride * l;
     for (int i = 0; i < 4; ++i) {
       const int64_t ow = o + c->foff[kWField[i]], os = o + c->foff[kSField[i]];
       // the second feed-forward projection reads the GELU output through an asymmetric quantizer with offset z
       const bool zterm = (i == 3 && c->cfg.a_bits > 0);
-      adam_matrix(params + ow, params + os, grads + ow, grads + os, m + ow, v + ow, m + os, v + os, c->wN[i], c->wK[i], c->cfg.w_bits, a,
-                  write_grads, zterm ? params + o + c->foff[MREM_F_Z_A] + 7 : nullptr, zterm ? grads + o + c->foff[MREM_F_B_2] : nullptr,
-                  r.st);
+      AdamJob j;
+      j.w = params + ow; j.sw = params + os; j.g_w = grads + ow; j.g_sw = grads + os;
+      j.m_w = m + ow; j.v_w = v + ow; j.m_sw = m + os; j.v_sw = v + os;
+      j.z_in = zterm ? params + o + c->foff[MREM_F_Z_A] + 7 : nullptr;
+      j.db = zterm ? grads + o + c->foff[MREM_F_B_2] : nullptr;
+      j.N = c->wN[i]; j.K = c->wK[i];
+      jobs.push_back(j);
     }
+  }
+  adam_matrix(jobs.data(), (int)jobs.size(), c->cfg.w_bits, a, write_grads, r.st);
+  for (int l = 0; l < c->L; ++l) {
+    const int64_t o = c->layer_stride * l;
     const int64_t ob = o + c->foff[MREM_F_B_QKV];
     const int64_t nb = c->foff[MREM_F_SW_QKV] - c->foff[MREM_F_B_QKV];
     adam_vector(params + ob, grads + ob, m + ob, v + ob, nb, nodecay, 0, r.st);

@@ -40,6 +40,30 @@ __device__ __forceinline__ void store8(bf16_t* p, const float* v) {
   *reinterpret_cast<uint4*>(p) = r;
 }
 
+// eight stored values kept as loaded (4 registers for bf16, 8 for fp32) until they are needed
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4v_t __attribute__((ext_vector_type(4)));
+template <class T>
+struct Raw8;
+template <>
+struct Raw8<bf16_t> {
+  u32x4_t r;
+  __device__ __forceinline__ void load(const bf16_t* p) { r = *reinterpret_cast<const u32x4_t*>(p); }
+  __device__ __forceinline__ float get(int j) const {
+    const unsigned w = r[j >> 1];
+    return __uint_as_float((j & 1) ? (w & 0xffff0000u) : (w << 16));
+  }
+};
+template <>
+struct Raw8<float> {
+  f32x4v_t a, b;
+  __device__ __forceinline__ void load(const float* p) {
+    a = *reinterpret_cast<const f32x4v_t*>(p);
+    b = *reinterpret_cast<const f32x4v_t*>(p + 4);
+  }
+  __device__ __forceinline__ float get(int j) const { return j < 4 ? a[j] : b[j - 4]; }
+};
+
 __device__ __forceinline__ QuantParam load_q(const QArg& a) {
   QuantParam q;
   q.on = a.on;
@@ -338,126 +362,178 @@ void ln_fwd(int dt, const void* x, const void* r, const float* gamma, const floa
                                        (T*)y, (T*)ycodes, q, mu, rstd, T_, H, eps));
 }
 
-constexpr int kLnBwdRows = 8;  // token rows per block: one per wavefront
+constexpr int kLnBwdWaves = 8;       // wavefronts per block
+constexpr int kLnBwdRowsPerWave = 2;  // token rows per wavefront, both in flight when registers allow
+constexpr int kLnBwdRows = kLnBwdWaves * kLnBwdRowsPerWave;  // token rows per block
 int ln_bwd_parts(int T_) { return (T_ + kLnBwdRows - 1) / kLnBwdRows; }
 
+// One wavefront per token row, kLnBwdRowsPerWave rows per wavefront with the column sums
+// (gamma, beta and residual-bias gradients) accumulated in registers; the wavefronts of a block
+// then meet in LDS (upper half onto lower half, then the lower half) and the block writes one partial row
+// [3H + 1] (the last value is the step-size gradient of the quantizer in front of the next layer).
 // NCH: 8-element chunks per lane (hidden <= 512 * NCH)
 template <class T, int NCH>
-__global__ __launch_bounds__(64 * kLnBwdRows) void ln_bwd_k(const T* __restrict__ d_a, const T* __restrict__ d_b, const T* __restrict__ d_q,
-                                                            const T* __restrict__ a_q, QArg qa, const T* __restrict__ x, const T* __restrict__ r,
-                                                            const float* __restrict__ mu, const float* __restrict__ rstd_in,
-                                                            const float* __restrict__ gamma, T* __restrict__ dr, float* __restrict__ partials,
-                                                            int T_, int H) {
-  extern __shared__ float red[];  // [3*H] + kLnBwdRows
+__global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict__ d_a, const T* __restrict__ d_b, const T* __restrict__ d_q,
+                                                             const T* __restrict__ a_q, QArg qa, const T* __restrict__ x, const T* __restrict__ r,
+                                                             const float* __restrict__ mu, const float* __restrict__ rstd_in,
+                                                             const float* __restrict__ gamma, T* __restrict__ dr, float* __restrict__ partials,
+                                                             int T_, int H) {
+  extern __shared__ float red[];  // [kLnBwdWaves/2][3*H] + kLnBwdWaves
+  constexpr int HALF = kLnBwdWaves / 2;
   const QuantParam q = load_q(qa);
   const int lane = threadIdx.x & 63, wave = threadIdx.x / 64;
   const int nch = H / 8;
-  float acc_g[NCH][8], acc_b[NCH][8], acc_d[NCH][8];
+  float acc_g[NCH][8], acc_b[NCH][8], acc_d[NCH][8], gam[NCH][8];
 #pragma unroll
-  for (int i = 0; i < NCH; ++i)
+  for (int i = 0; i < NCH; ++i) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc_g[i][j] = acc_b[i][j] = acc_d[i][j] = 0.f;
+    for (int j = 0; j < 8; ++j) acc_g[i][j] = acc_b[i][j] = acc_d[i][j] = gam[i][j] = 0.f;
+    if (lane + 64 * i < nch) load8(gamma + (lane + 64 * i) * 8, gam[i]);
+  }
   float ds_acc = 0.f;
 
-  const int row = blockIdx.x * kLnBwdRows + wave;
-  if (row < T_) {
-    const float mean = mu[row], rstd = rstd_in[row];
-    float dy[NCH][8], xh[NCH][8];
-    float s1 = 0.f, s2 = 0.f;
+  constexpr int INF = NCH * sizeof(T) <= 4 ? 2 : 1;  // rows in flight: two when their loaded values fit the registers
+  const int row_base = blockIdx.x * kLnBwdRows + wave * kLnBwdRowsPerWave;
+#pragma unroll 1
+  for (int pair = 0; pair < kLnBwdRowsPerWave; pair += INF) {
+    float dy[INF][NCH][8], xh[INF][NCH][8], mean[INF], rstd[INF];
+    // issue the loads of the rows in flight, then do the arithmetic
+    Raw8<T> t_a[INF][NCH], t_b[INF][NCH], t_q[INF][NCH], t_v[INF][NCH], t_x[INF][NCH], t_r[INF][NCH];
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int c = lane + 64 * i;
-      if (c < nch) {
-        const size_t off = (size_t)row * H + c * 8;
-        float t[8], g[8], xa[8], xb[8];
+    for (int k = 0; k < INF; ++k) {
+      const int row = row_base + pair + k;
+      const bool live = row < T_;
+      mean[k] = live ? mu[row] : 0.f;
+      rstd[k] = live ? rstd_in[row] : 0.f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) dy[i][j] = 0.f;
-        if (d_a) { load8(d_a + off, t);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) dy[i][j] += t[j]; }
-        if (d_b) { load8(d_b + off, t);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) dy[i][j] += t[j]; }
-        if (d_q) {
-          load8(d_q + off, t);
-          if (q.on) {
-            float av[8];
-            load8(a_q + off, av);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-              const float v = q_ratio_t<T>(av[j], q);
-              const bool in = q_inside(v, q);
-              ds_acc += t[j] * (q_code(v, q) - (in ? v : 0.f));
-              t[j] = in ? t[j] : 0.f;
-            }
+      for (int i = 0; i < NCH; ++i) {
+        const int c = lane + 64 * i;
+        if (live && c < nch) {
+          const size_t off = (size_t)row * H + c * 8;
+          if (d_a) t_a[k][i].load(d_a + off);
+          if (d_b) t_b[k][i].load(d_b + off);
+          if (d_q) {
+            t_q[k][i].load(d_q + off);
+            if (q.on) t_v[k][i].load(a_q + off);
           }
-#pragma unroll
-          for (int j = 0; j < 8; ++j) dy[i][j] += t[j];
-        }
-        load8(gamma + c * 8, g);
-        load8(x + off, xa);
-        load8(r + off, xb);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          xh[i][j] = (xa[j] + xb[j] - mean) * rstd;
-          acc_g[i][j] = dy[i][j] * xh[i][j];
-          acc_b[i][j] = dy[i][j];
-          dy[i][j] *= g[j];  // now d(xhat)
-          s1 += dy[i][j];
-          s2 += dy[i][j] * xh[i][j];
+          t_x[k][i].load(x + off);
+          t_r[k][i].load(r + off);
         }
       }
     }
-    const float m1 = wave_sum(s1) / (float)H, m2 = wave_sum(s2) / (float)H;
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int c = lane + 64 * i;
-      if (c < nch) {
-        float o[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          o[j] = rstd * (dy[i][j] - m1 - xh[i][j] * m2);
-          acc_d[i][j] = round_to<T>(o[j]);
-        }
-        store8(dr + (size_t)row * H + c * 8, o);
-      }
-    }
-  }
-  // combine the wavefronts (rows) of the block in a fixed order, then write this block's partial row
-  ds_acc = wave_sum(ds_acc);
-  for (int w = 0; w < kLnBwdRows; ++w) {
-    if (wave == w) {
+    for (int k = 0; k < INF; ++k) {
+      const int row = row_base + pair + k;
+      if (row >= T_) continue;
+      float s1 = 0.f, s2 = 0.f;
 #pragma unroll
       for (int i = 0; i < NCH; ++i) {
         const int c = lane + 64 * i;
         if (c < nch) {
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
-            const int col = c * 8 + j;
-            if (w == 0) { red[col] = acc_g[i][j]; red[H + col] = acc_b[i][j]; red[2 * H + col] = acc_d[i][j]; }
-            else { red[col] += acc_g[i][j]; red[H + col] += acc_b[i][j]; red[2 * H + col] += acc_d[i][j]; }
+            float d = 0.f;
+            if (d_a) d += t_a[k][i].get(j);
+            if (d_b) d += t_b[k][i].get(j);
+            if (d_q) {
+              float t = t_q[k][i].get(j);
+              if (q.on) {
+                const float v = q_ratio_t<T>(t_v[k][i].get(j), q);
+                const bool in = q_inside(v, q);
+                ds_acc += t * (q_code(v, q) - (in ? v : 0.f));
+                t = in ? t : 0.f;
+              }
+              d += t;
+            }
+            const float xhat = (t_x[k][i].get(j) + t_r[k][i].get(j) - mean[k]) * rstd[k];
+            xh[k][i][j] = xhat;
+            acc_g[i][j] += d * xhat;
+            acc_b[i][j] += d;
+            d *= gam[i][j];  // now d(xhat)
+            dy[k][i][j] = d;
+            s1 += d;
+            s2 += d * xhat;
           }
         }
       }
-      if (lane == 0) red[3 * H + w] = ds_acc;
+      const float m1 = wave_sum(s1) / (float)H, m2 = wave_sum(s2) / (float)H;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nch) {
+          float o[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            o[j] = rstd[k] * (dy[k][i][j] - m1 - xh[k][i][j] * m2);
+            acc_d[i][j] += round_to<T>(o[j]);
+          }
+          store8(dr + (size_t)row * H + c * 8, o);
+        }
+      }
     }
-    __syncthreads();
   }
+  // the wavefronts meet in LDS: the upper half adds onto the lower half, whose sum in wavefront
+  // order is the block's partial row
+  ds_acc = wave_sum(ds_acc);
+  float* mine = red + (size_t)(wave % HALF) * 3 * H;
+  float* dsv = red + (size_t)HALF * 3 * H;
+  if (lane == 0) dsv[wave] = ds_acc;
+  if (wave >= HALF) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nch) {
+        store8(mine + c * 8, acc_g[i]);
+        store8(mine + H + c * 8, acc_b[i]);
+        store8(mine + 2 * H + c * 8, acc_d[i]);
+      }
+    }
+  }
+  __syncthreads();
+  if (wave < HALF) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nch) {
+        float t[8];
+        load8(mine + c * 8, t);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc_g[i][j] += t[j];
+        load8(mine + H + c * 8, t);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc_b[i][j] += t[j];
+        load8(mine + 2 * H + c * 8, t);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc_d[i][j] += t[j];
+        store8(mine + c * 8, acc_g[i]);
+        store8(mine + H + c * 8, acc_b[i]);
+        store8(mine + 2 * H + c * 8, acc_d[i]);
+      }
+    }
+  }
+  __syncthreads();
   const int width = 3 * H + 1;
   float* out = partials + (size_t)blockIdx.x * width;
-  for (int c = threadIdx.x; c < 3 * H; c += blockDim.x) out[c] = red[c];
+  for (int c = threadIdx.x; c < 3 * H; c += blockDim.x) {
+    float t = red[c];
+#pragma unroll
+    for (int w = 1; w < HALF; ++w) t += red[(size_t)w * 3 * H + c];
+    out[c] = t;
+  }
   if (threadIdx.x == 0) {
     float t = 0.f;
-    for (int w = 0; w < kLnBwdRows; ++w) t += red[3 * H + w];
+    for (int w = 0; w < kLnBwdWaves; ++w) t += dsv[w];
     out[3 * H] = t;
   }
 }
 int ln_bwd(int dt, const void* d_a, const void* d_b, const void* d_q, const void* a_q, QArg q, const void* x, const void* r,
            const float* mu, const float* rstd, const float* gamma, void* dr, float* partials, int T_, int H, hipStream_t st) {
   const int g = ln_bwd_parts(T_);
-  const size_t lds = (3 * (size_t)H + kLnBwdRows) * sizeof(float);
+  const size_t lds = ((size_t)(kLnBwdWaves / 2) * 3 * H + kLnBwdWaves) * sizeof(float);
 #define MREM_LN_BWD(NCH)                                                                                                        \
-  MREM_DISPATCH(dt, hipLaunchKernelGGL((ln_bwd_k<T, NCH>), dim3(g), dim3(64 * kLnBwdRows), lds, st, (const T*)d_a, (const T*)d_b, \
+  MREM_DISPATCH(dt, if (lds > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ln_bwd_k<T, NCH>),                   \
+                                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);            \
+                    hipLaunchKernelGGL((ln_bwd_k<T, NCH>), dim3(g), dim3(64 * kLnBwdWaves), lds, st, (const T*)d_a, (const T*)d_b, \
                                        (const T*)d_q, (const T*)a_q, q, (const T*)x, (const T*)r, mu, rstd, gamma, (T*)dr, partials, T_, H))
   if (H <= 512) MREM_LN_BWD(1);
   else if (H <= 1024) MREM_LN_BWD(2);
@@ -670,13 +746,23 @@ void weight_step_init(const float* w, float* scale, int64_t N, int64_t K, int bi
 }
 
 // codes (integer-valued, storage type), dequantized weights s*code (same layout), and
-// zcorr[n] = s[n] * sum_k code; one block per output channel
+// zcorr[n] = s[n] * sum_k code; one block per output channel, all matrices of a table in one launch
+struct WeightJobTable {
+  WeightJob job[kMaxMatrixJobs];
+  int first_row[kMaxMatrixJobs + 1];
+  int njobs;
+};
 template <class T>
-__global__ __launch_bounds__(256) void weight_codes_k(const float* __restrict__ w, const float* __restrict__ sw, int K, float qp, int on,
-                                                      T* __restrict__ codes, T* __restrict__ what, float* __restrict__ zcorr) {
+__global__ __launch_bounds__(128) void weight_codes_k(WeightJobTable tab, float qp, int on) {
   __shared__ float red[17];
-  const int n = blockIdx.x;
-  const float s = on ? sw[n] : 1.f;
+  int ji = 0;
+  while (ji + 1 < tab.njobs && (int)blockIdx.x >= tab.first_row[ji + 1]) ++ji;
+  const WeightJob& jb = tab.job[ji];
+  const int n = blockIdx.x - tab.first_row[ji], K = jb.K;
+  const float* __restrict__ w = jb.w;
+  T* __restrict__ codes = reinterpret_cast<T*>(jb.codes);
+  T* __restrict__ what = reinterpret_cast<T*>(jb.what);
+  const float s = on ? jb.sw[n] : 1.f;
   float acc = 0.f;
   const size_t row = (size_t)n * K;
   for (int k = threadIdx.x * 8; k < K; k += blockDim.x * 8) {
@@ -691,13 +777,20 @@ __global__ __launch_bounds__(256) void weight_codes_k(const float* __restrict__ 
     if (what) store8(what + row + k, x);
   }
   acc = block_sum(acc, red);
-  if (threadIdx.x == 0) zcorr[n] = on ? s * acc : 0.f;
+  if (threadIdx.x == 0) jb.zcorr[n] = on ? s * acc : 0.f;
 }
-void weight_prepare(int dt, const float* w, const float* sw, int N, int K, int bits, void* codes, void* what, float* zcorr,
-                    hipStream_t st) {
+void weight_prepare(int dt, const WeightJob* jobs, int njobs, int bits, hipStream_t st) {
   const int on = bits > 0;
   const float qp = on ? (float)((1 << (bits - 1)) - 1) : 0.f;
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(weight_codes_k<T>, dim3(N), dim3(256), 0, st, w, sw, K, qp, on, (T*)codes, (T*)what, zcorr));
+  for (int j0 = 0; j0 < njobs; j0 += kMaxMatrixJobs) {
+    WeightJobTable tab;
+    tab.njobs = njobs - j0 < kMaxMatrixJobs ? njobs - j0 : kMaxMatrixJobs;
+    int rows = 0;
+    for (int j = 0; j < tab.njobs; ++j) { tab.job[j] = jobs[j0 + j]; tab.first_row[j] = rows; rows += jobs[j0 + j].N; }
+    tab.first_row[tab.njobs] = rows;
+    if (rows == 0) continue;
+    MREM_DISPATCH(dt, hipLaunchKernelGGL(weight_codes_k<T>, dim3(rows), dim3(128), 0, st, tab, qp, on));
+  }
 }
 
 // ------------------------------------------------------------------------------
@@ -773,15 +866,25 @@ __device__ __forceinline__ float adam_one(float p, float g, float& m, float& v, 
 // here, from the weights and the step before their update.
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(256) void adam_matrix_k(float* __restrict__ w, float* __restrict__ sw, float* __restrict__ g_w,
-                                                     float* __restrict__ g_sw, float* __restrict__ m_w, float* __restrict__ v_w,
-                                                     float* __restrict__ m_sw, float* __restrict__ v_sw, int K, float qp, int on, AdamArg a,
-                                                     int write_grads, const float* __restrict__ z_in, const float* __restrict__ db) {
+struct AdamJobTable {
+  AdamJob job[kMaxMatrixJobs];
+  int first_row[kMaxMatrixJobs + 1];
+  int njobs;
+};
+__global__ __launch_bounds__(256) void adam_matrix_k(AdamJobTable tab, float qp, int on, AdamArg a, int write_grads) {
   __shared__ float red[17];
-  const int n = blockIdx.x;
-  const float s = on ? sw[n] : 1.f;
+  int ji = 0;
+  while (ji + 1 < tab.njobs && (int)blockIdx.x >= tab.first_row[ji + 1]) ++ji;
+  const AdamJob& jb = tab.job[ji];
+  const int n = blockIdx.x - tab.first_row[ji], K = jb.K;
+  float* __restrict__ w = jb.w;
+  float* __restrict__ g_w = jb.g_w;
+  float* __restrict__ m_w = jb.m_w;
+  float* __restrict__ v_w = jb.v_w;
+  const float s = on ? jb.sw[n] : 1.f;
   // offset term of an asymmetric input quantizer: d(loss)/d(w_hat[n,:]) += z * sum_t dy[t,n]
-  const float zterm = z_in ? (*z_in) * db[n] : 0.f;
+  const float zterm = jb.z_in ? (*jb.z_in) * jb.db[n] : 0.f;
+  const bool store_g = write_grads && (on || jb.z_in);
   float acc = 0.f;
   const size_t row = (size_t)n * K;
   for (int k = threadIdx.x * 4; k < K; k += blockDim.x * 4) {
@@ -810,29 +913,36 @@ __global__ __launch_bounds__(256) void adam_matrix_k(float* __restrict__ w, floa
     *reinterpret_cast<f32x4_t*>(w + i) = x;
     *reinterpret_cast<f32x4_t*>(m_w + i) = m;
     *reinterpret_cast<f32x4_t*>(v_w + i) = vv;
-    if (write_grads && (on || z_in)) *reinterpret_cast<f32x4_t*>(g_w + i) = g;
+    if (store_g) *reinterpret_cast<f32x4_t*>(g_w + i) = g;
   }
   if (on) {
     acc = block_sum(acc, red);
     if (threadIdx.x == 0) {
-      if (write_grads) g_sw[n] = acc;
+      if (write_grads) jb.g_sw[n] = acc;
       AdamArg as = a;
       as.wd = 0.f;
-      float m = m_sw[n], vv = v_sw[n];
+      float m = jb.m_sw[n], vv = jb.v_sw[n];
       const float ns = adam_one(s, acc, m, vv, as);
-      sw[n] = fmaxf(ns, a.floor);
-      m_sw[n] = m;
-      v_sw[n] = vv;
+      jb.sw[n] = fmaxf(ns, a.floor);
+      jb.m_sw[n] = m;
+      jb.v_sw[n] = vv;
     }
   } else if (write_grads && threadIdx.x == 0) {
-    g_sw[n] = 0.f;
+    jb.g_sw[n] = 0.f;
   }
 }
-void adam_matrix(float* w, float* sw, float* g_w, float* g_sw, float* m_w, float* v_w, float* m_sw, float* v_sw, int N, int K,
-                 int bits, AdamArg a, int write_grads, const float* z_in, const float* db, hipStream_t st) {
+void adam_matrix(const AdamJob* jobs, int njobs, int bits, AdamArg a, int write_grads, hipStream_t st) {
   const int on = bits > 0;
   const float qp = on ? (float)((1 << (bits - 1)) - 1) : 0.f;
-  hipLaunchKernelGGL(adam_matrix_k, dim3(N), dim3(256), 0, st, w, sw, g_w, g_sw, m_w, v_w, m_sw, v_sw, K, qp, on, a, write_grads, z_in, db);
+  for (int j0 = 0; j0 < njobs; j0 += kMaxMatrixJobs) {
+    AdamJobTable tab;
+    tab.njobs = njobs - j0 < kMaxMatrixJobs ? njobs - j0 : kMaxMatrixJobs;
+    int rows = 0;
+    for (int j = 0; j < tab.njobs; ++j) { tab.job[j] = jobs[j0 + j]; tab.first_row[j] = rows; rows += jobs[j0 + j].N; }
+    tab.first_row[tab.njobs] = rows;
+    if (rows == 0) continue;
+    hipLaunchKernelGGL(adam_matrix_k, dim3(rows), dim3(256), 0, st, tab, qp, on, a, write_grads);
+  }
 }
 
 __global__ void adam_vector_k(float* __restrict__ p, const float* __restrict__ g, float* __restrict__ m, float* __restrict__ v,

@@ -51,10 +51,19 @@ int gemm_profile_end(double* ms, double* flops, int64_t* launches);
 void weight_quantize_i8(const float* w, float* scale, int8_t* codes, int64_t N, int64_t K, int bits, int init_scale,
                         hipStream_t st);
 void weight_step_init(const float* w, float* scale, int64_t N, int64_t K, int bits, hipStream_t st);
-// codes[N,K] (integer-valued, storage type), what[N,K] = round(s*q),
-// zcorr[N] = s[n] * sum_k q[n,k].  bits = 0: codes = what = round(w), zcorr = 0.
-void weight_prepare(int dt, const float* w, const float* sw, int N, int K, int bits, void* codes, void* what,
-                    float* zcorr, hipStream_t st);
+// Per matrix w[N,K] with steps sw[N]: codes[N,K] (integer-valued, storage type), what[N,K] =
+// round(s*q) (may be null), zcorr[N] = s[n] * sum_k q[n,k].  bits = 0: codes = what = round(w),
+// zcorr = 0.  All matrices of the list go into one launch (kMaxMatrixJobs per launch).
+constexpr int kMaxMatrixJobs = 24;
+struct WeightJob {
+  const float* w;
+  const float* sw;
+  void* codes;
+  void* what;
+  float* zcorr;
+  int N, K;
+};
+void weight_prepare(int dt, const WeightJob* jobs, int njobs, int bits, hipStream_t st);
 void convert_f32(int dt, const float* src, void* dst, int64_t n, hipStream_t st);
 
 // ---- elementwise / normalisation ------------------------------------------------
@@ -142,8 +151,14 @@ struct AdamArg {
 // one block per row n of w[N,K]: straight-through mask on dw_hat (in grads), row
 // reduction for the step gradient, AdamW on w[n,:] and on sw[n].  z_in/db (may be null):
 // offset of an asymmetric input quantizer and the bias gradient, dw_hat[n,:] += z * db[n].
-void adam_matrix(float* w, float* sw, float* g_w, float* g_sw, float* m_w, float* v_w, float* m_sw, float* v_sw, int N,
-                 int K, int bits, AdamArg a, int write_grads, const float* z_in, const float* db, hipStream_t st);
+// All matrices of the list go into one launch (kMaxMatrixJobs per launch).
+struct AdamJob {
+  float *w, *sw, *g_w, *g_sw, *m_w, *v_w, *m_sw, *v_sw;
+  const float* z_in;
+  const float* db;
+  int N, K;
+};
+void adam_matrix(const AdamJob* jobs, int njobs, int bits, AdamArg a, int write_grads, hipStream_t st);
 void adam_vector(float* p, const float* g, float* m, float* v, int64_t n, AdamArg a, int clamp, hipStream_t st);
 
 }  // namespace mrem
