@@ -30,7 +30,16 @@ __device__ __forceinline__ int key_of(int t, int i, int h) { return 32 * t + 8 *
 struct FwdScales {
   float qk, sp, sv, p_qp;
   int p_on;
+  float rsp;  // correctly rounded 1 / sp
 };
+// x / d from rd = fl(1 / d): t = fl(x * rd), then t + fl(x - d * t) * rd with fused multiply-adds.
+// The residual is exact and, rd being correctly rounded, the result is the correctly rounded
+// quotient (the residual-correction step of FMA division), so this matches an IEEE division while
+// one reciprocal serves a whole row (softmax sums) or tensor (step sizes).
+__device__ __forceinline__ float div_by(float x, float d, float rd) {
+  const float t = __fmul_rn(x, rd);
+  return __fmaf_rn(__fmaf_rn(-d, t, x), rd, t);
+}
 __device__ __forceinline__ FwdScales load_fwd_scales(const AttnQ& a) {
   FwdScales s;
   const float sq = a.q.on ? *a.q.s : 1.f, sk = a.k.on ? *a.k.s : 1.f;
@@ -39,6 +48,7 @@ __device__ __forceinline__ FwdScales load_fwd_scales(const AttnQ& a) {
   s.qk = sq * sk / sqrtf((float)kD);
   s.p_on = a.p.on;
   s.p_qp = a.p.qp;
+  s.rsp = __fdiv_rn(1.0f, s.sp);
   return s;
 }
 
@@ -136,7 +146,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_k(const bf16_t* __restrict_
     if (t < nt) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float e = sacc[t][r] == -INFINITY ? 0.f : expf(__fsub_rn(sacc[t][r], mx));
+        const float e = sacc[t][r] == -INFINITY ? 0.f : __expf(__fsub_rn(sacc[t][r], mx));
         sacc[t][r] = e;
         sum += e;
       }
@@ -156,6 +166,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_k(const bf16_t* __restrict_
     for (int r = 0; r < 16; ++r) oacc[et][r] = 0.f;
   const bf16_t* vrow0 = Vt + (lane & 31) * t_stride;
   const bf16_t* vrow1 = vrow0 + 32 * t_stride;
+  const float rsum = __fdiv_rn(1.0f, sum);
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     if (t < nt) {
@@ -164,8 +175,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_k(const bf16_t* __restrict_
         bf16x8_t pf;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          const float p = sacc[t][8 * s + i] / sum;
-          const float c = sc.p_on ? rintf(fminf(fmaxf(__fdiv_rn(p, sc.sp), 0.f), sc.p_qp)) : p;
+          const float p = div_by(sacc[t][8 * s + i], sum, rsum);
+          const float c = sc.p_on ? rintf(fminf(fmaxf(div_by(p, sc.sp, sc.rsp), 0.f), sc.p_qp)) : p;
           pf[i] = static_cast<bf16_t>(c);
         }
         oacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_t(vrow0, t, s, half), pf, oacc[0], 0, 0, 0);
@@ -175,7 +186,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_k(const bf16_t* __restrict_
   }
   if (q < S) {
     const float os = sc.sp * sc.sv;
-    const QuantParam qc5 = {aq.c.on ? *aq.c.s : 1.f, 0.f, aq.c.qn, aq.c.qp, aq.c.on};
+    QuantParam qc5 = {aq.c.on ? *aq.c.s : 1.f, 0.f, aq.c.qn, aq.c.qp, aq.c.on, 0.f};
+    qc5.rs = __fdiv_rn(1.0f, qc5.s);
     const size_t orow = ((size_t)b * S + q) * H + h * kD;
 #pragma unroll
     for (int et = 0; et < 2; ++et)
@@ -190,7 +202,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_k(const bf16_t* __restrict_
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const float r = round_to<bf16_t>(o[i]);
-            o[i] = qc5.on ? q_code(q_ratio(r, qc5), qc5) : r;
+            o[i] = qc5.on ? q_code(q_ratio_fma(r, qc5), qc5) : r;
           }
           store4(ctx_codes + orow + e, o[0], o[1], o[2], o[3]);
         }
@@ -244,7 +256,8 @@ __global__ __launch_bounds__(256) void attn_bwd_q_mfma_k(const bf16_t* __restric
     cf[kk] = ld_frag(dctx + ((size_t)b * S + qc) * H + h * kD + (kk * 2 + half) * 8);
   }
   const size_t stat_idx = ((size_t)b * nh + h) * S + qc;
-  const float mx = stat_m[stat_idx], inv_l = stat_l[stat_idx];
+  const float mx = stat_m[stat_idx], inv_l = stat_l[stat_idx];  // row maximum and row sum of the forward
+  const float rl = __fdiv_rn(1.0f, inv_l);
 
   float rowdot = 0.f, dsp = 0.f;
   f32x16_t dqacc[2];
@@ -275,11 +288,11 @@ __global__ __launch_bounds__(256) void attn_bwd_q_mfma_k(const bf16_t* __restric
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int j = key_of(t, r, half);
-        const float p = j < len ? expf(__fsub_rn(__fmul_rn(sacc[r], sc.qk), mx)) / inv_l : 0.f;  // same rounding steps as the forward
+        const float p = j < len ? div_by(__expf(__fsub_rn(__fmul_rn(sacc[r], sc.qk), mx)), inv_l, rl) : 0.f;  // same rounding steps as the forward
         const float dph = dacc[r] * sc.sv;
         float dp = dph, c = p;
         if (sc.p_on) {
-          const float v = __fdiv_rn(p, sc.sp);
+          const float v = div_by(p, sc.sp, sc.rsp);
           const bool in = v <= sc.p_qp;
           c = rintf(fminf(v, sc.p_qp));
           if (phase == 0) dsp += dph * (c - (in ? v : 0.f));
