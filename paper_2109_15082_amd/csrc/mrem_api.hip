@@ -140,7 +140,7 @@ Plan make_plan(const mrem_ctx* c, int B, int S) {
   // first-stage partial sums of one layer's backward pass (all of them stay until the single
   // second-stage launch at the end of the backward pass): two LayerNorms, two bias column sums,
   // the elementwise kernels (at most 2048 blocks, up to 3 values each) and the attention rows
-  size_t np = 2 * (size_t)ln_bwd_parts((int)T) * (3 * H + 1) + ((T + 31) / 32) * (F + 3 * H) + 8 * 2048 + (size_t)B * c->nh * S;
+  size_t np = 2 * (size_t)ln_bwd_parts((int)T) * (3 * H + 1) + (size_t)kColMaxParts * (F + 3 * H) + 8 * 2048 + (size_t)B * c->nh * S;
   np = (np + 63) & ~size_t(63);
   p.partials_per_layer = np;
   p.partials = b.take(np * 4 * c->L);
@@ -339,13 +339,6 @@ void dgrad(const Run& r, int l, int i, const void* dy, void* out) {
   gemm(c->dt, 0, 1, dy, c->wN[i], r.at(r.p.lw[l].what[i]), c->wK[i], out, c->wK[i], r.T, c->wK[i], c->wN[i], e, r.st);
 }
 
-// column sums of a [T, C] tensor into out[C] (bias gradients)
-void colsum(const Run& r, Reductions& red, const void* a, int C, float* out) {
-  float* parts = red.take((size_t)((r.T + 31) / 32) * C);
-  const int n = colsum_partials(r.c->dt, a, r.T, C, parts, r.st);
-  red.add(parts, n, C, 0, C, out);
-}
-
 void student_backward(const Run& r, const float* params, const void* x_q, const void* per_layer_fp, const void* per_layer_q,
                       float* grads, float* loss_out) {
   const mrem_ctx* c = r.c;
@@ -391,12 +384,14 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
     dgrad(r, l, 3, r.at(r.p.dr2), r.at(r.p.dgh));
     // GELU and its output quantizer
     {
+      // the kernel also leaves the column sums of du per row slab: the bias gradient of the first projection
       float* parts = red.take(2048);
-      const int n = gelu_quant_bwd(c->dt, r.at(r.p.dgh), r.at(w.u), r.at(r.p.du), (int64_t)T * F, make_q(c, params, l, 7), parts, r.st);
-      red.add(parts, n, 1, 0, 1, g + c->foff[MREM_F_S_A] + 7);
+      float* cols = red.take((size_t)kColMaxParts * F);
+      const ColGrid cg = gelu_quant_bwd(c->dt, r.at(r.p.dgh), r.at(w.u), r.at(r.p.du), T, F, make_q(c, params, l, 7), parts, cols, r.st);
+      red.add(parts, cg.gx * cg.gy, 1, 0, 1, g + c->foff[MREM_F_S_A] + 7);
+      red.add(cols, cg.gy, F, 0, F, g + c->foff[MREM_F_B_1]);
     }
     // first feed-forward projection
-    colsum(r, red, r.at(r.p.du), F, g + c->foff[MREM_F_B_1]);
     wgrad(r, params, grads, l, 2, r.at(r.p.du), r.at(w.x1codes));
     dgrad(r, l, 2, r.at(r.p.du), r.at(r.p.dx1h));
     // first LayerNorm: dy = dr2 (residual) + dx1h through the FFN-input quantizer
@@ -432,14 +427,17 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       red.add(parts, n, 1, 0, 1, g + c->foff[MREM_F_S_A] + 3);
     }
     {
+      // the kernel also leaves the column sums of dqkv per row slab: the bias gradient of the projection
       float* parts = red.take(2048 * 3);
-      const int n = qkv_quant_bwd(c->dt, r.at(r.p.dqkvh), r.at(w.qkv), r.at(r.p.dqkv), T, H, aq.q, aq.k, aq.v, parts, r.st);
+      float* cols = red.take((size_t)kColMaxParts * 3 * H);
+      const ColGrid cg = qkv_quant_bwd(c->dt, r.at(r.p.dqkvh), r.at(w.qkv), r.at(r.p.dqkv), T, H, aq.q, aq.k, aq.v, parts, cols, r.st);
+      const int n = cg.gx * cg.gy;
       red.add(parts, n, 3, 0, 1, g + c->foff[MREM_F_S_A] + 1);
       red.add(parts, n, 3, 1, 1, g + c->foff[MREM_F_S_A] + 2);
       red.add(parts, n, 3, 2, 1, g + c->foff[MREM_F_S_A] + 4);
+      red.add(cols, cg.gy, 3 * H, 0, 3 * H, g + c->foff[MREM_F_B_QKV]);
     }
     // query/key/value projection
-    colsum(r, red, r.at(r.p.dqkv), 3 * H, g + c->foff[MREM_F_B_QKV]);
     wgrad(r, params, grads, l, 0, r.at(r.p.dqkv), r.at(w.xcodes));
     dgrad(r, l, 0, r.at(r.p.dqkv), r.at(r.p.dxh));
     if (l == 0) {

@@ -1,7 +1,7 @@
 // Bandwidth-bound kernels of the MREM module step: quantizers (Section 3.1, Eq. 1,
 // with the straight-through backward of Section 3.1.1), residual + LayerNorm,
-// GELU, the per-layer squared-error term of Eq. 3, transposes for the weight
-// gradient products, calibration reductions and the AdamW update.
+// GELU, the per-layer squared-error term of Eq. 3, calibration reductions and the
+// AdamW update.
 #include "mrem_common.h"
 #include "mrem_kernels.h"
 
@@ -155,42 +155,65 @@ void qkv_quantize(int dt, const void* qkv, void* codes, int T_, int H, QArg q, Q
                                        H / 8, q, k, v));
 }
 
-// d_out = d_q * inside ; partial[block][sec] += d_q * (code - v * inside)
+// Column-walking backward kernels: a thread owns one 8-element column chunk and walks down its
+// share of the rows, kColRows rows in flight, so the column sums of what it writes (the bias
+// gradient of the projection in front) stay in its registers.  Grid y splits the rows into
+// at most kColMaxParts slabs; block (x, y) writes row y of colparts[gy][C] for its columns.
+constexpr int kColRows = 8;
+ColGrid col_grid(int T_, int C) {
+  ColGrid g;
+  g.gx = (C / 8 + kQkvThreads - 1) / kQkvThreads;
+  const int groups = (T_ + kColRows - 1) / kColRows;
+  int cap = 2048 / g.gx;  // the reductions downstream hold at most 2048 blocks
+  if (cap > kColMaxParts) cap = kColMaxParts;
+  if (cap < 1) cap = 1;
+  const int iters = (groups + cap - 1) / cap;  // every block walks the same number of row groups
+  g.gy = iters > 0 ? (groups + iters - 1) / iters : 1;
+  if (g.gy < 1) g.gy = 1;
+  return g;
+}
+
+// d_out = d_q * inside ; partial[block][sec] += d_q * (code - v * inside) ; colparts: column sums of d_out
 template <class T>
 __global__ __launch_bounds__(kQkvThreads) void qkv_quant_bwd_k(const T* __restrict__ dq, const T* __restrict__ a, T* __restrict__ dout,
-                                                                int T_, int H8, QArg q0, QArg q1, QArg q2, float* __restrict__ partials) {
+                                                                int T_, int H8, QArg q0, QArg q1, QArg q2, float* __restrict__ partials,
+                                                                float* __restrict__ colparts) {
   __shared__ float red[17];
   const int cc = blockIdx.x * kQkvThreads + threadIdx.x, row_chunks = 3 * H8;
   const bool live = cc < row_chunks;
   const int sec = live ? cc / H8 : 0;
   const QuantParam q = pick_q(sec, load_q(q0), load_q(q1), load_q(q2));
-  float acc = 0.f;
+  float acc = 0.f, col[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (live) {
-    for (int r0 = blockIdx.y * kQkvRows; r0 < T_; r0 += gridDim.y * kQkvRows) {
-      float g[kQkvRows][8], x[kQkvRows][8];
+    for (int r0 = blockIdx.y * kColRows; r0 < T_; r0 += gridDim.y * kColRows) {
+      Raw8<T> graw[kColRows], xraw[kColRows];
 #pragma unroll
-      for (int i = 0; i < kQkvRows; ++i) {
+      for (int i = 0; i < kColRows; ++i) {
         if (r0 + i < T_) {
           const size_t o = ((size_t)(r0 + i) * row_chunks + cc) * 8;
-          load8(dq + o, g[i]);
-          if (q.on) load8(a + o, x[i]);
+          graw[i].load(dq + o);
+          if (q.on) xraw[i].load(a + o);
         }
       }
 #pragma unroll
-      for (int i = 0; i < kQkvRows; ++i) {
+      for (int i = 0; i < kColRows; ++i) {
         if (r0 + i >= T_) break;
-        if (q.on) {
+        float g[8];
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const float v = q_ratio_t<T>(x[i][j], q);
+        for (int j = 0; j < 8; ++j) {
+          g[j] = graw[i].get(j);
+          if (q.on) {
+            const float v = q_ratio_t<T>(xraw[i].get(j), q);
             const bool in = q_inside(v, q);
-            acc += g[i][j] * (q_code(v, q) - (in ? v : 0.f));
-            g[i][j] = in ? g[i][j] : 0.f;
+            acc += g[j] * (q_code(v, q) - (in ? v : 0.f));
+            g[j] = in ? g[j] : 0.f;
           }
+          col[j] += round_to<T>(g[j]);
         }
-        if (dout) store8(dout + ((size_t)(r0 + i) * row_chunks + cc) * 8, g[i]);
+        if (dout) store8(dout + ((size_t)(r0 + i) * row_chunks + cc) * 8, g);
       }
     }
+    if (colparts) store8(colparts + ((size_t)blockIdx.y * row_chunks + cc) * 8, col);
   }
   const int block = blockIdx.y * gridDim.x + blockIdx.x;
   for (int s = 0; s < 3; ++s) {
@@ -198,12 +221,12 @@ __global__ __launch_bounds__(kQkvThreads) void qkv_quant_bwd_k(const T* __restri
     if (threadIdx.x == 0) partials[block * 3 + s] = t;
   }
 }
-int qkv_quant_bwd(int dt, const void* d_qkvh, const void* qkv, void* d_qkv, int T_, int H, QArg q, QArg k, QArg v,
-                  float* partials, hipStream_t st) {
-  const QkvGrid g = qkv_grid(T_, H);
+ColGrid qkv_quant_bwd(int dt, const void* d_qkvh, const void* qkv, void* d_qkv, int T_, int H, QArg q, QArg k, QArg v,
+                      float* partials, float* colparts, hipStream_t st) {
+  const ColGrid g = col_grid(T_, 3 * H);
   MREM_DISPATCH(dt, hipLaunchKernelGGL(qkv_quant_bwd_k<T>, dim3(g.gx, g.gy), dim3(kQkvThreads), 0, st, (const T*)d_qkvh, (const T*)qkv,
-                                       (T*)d_qkv, T_, H / 8, q, k, v, partials));
-  return g.gx * g.gy;
+                                       (T*)d_qkv, T_, H / 8, q, k, v, partials, colparts));
+  return g;
 }
 
 // generic single-quantizer backward (d_out may be null: reduction only)
@@ -262,36 +285,57 @@ void gelu_quantize(int dt, const void* u, void* codes, int64_t n, QArg q, hipStr
   MREM_DISPATCH(dt, hipLaunchKernelGGL(gelu_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)u, (T*)codes, n / 8, q));
 }
 
+// du = dgh * inside * gelu'(u) ; partials[block]: step-size gradient terms ; colparts: column sums of du
 template <class T>
-__global__ void gelu_quant_bwd_k(const T* __restrict__ dgh, const T* __restrict__ u, T* __restrict__ du, int64_t nchunks,
-                                 QArg qa, float* __restrict__ partials) {
+__global__ __launch_bounds__(kQkvThreads) void gelu_quant_bwd_k(const T* __restrict__ dgh, const T* __restrict__ u, T* __restrict__ du,
+                                                                 int T_, int C8, QArg qa, float* __restrict__ partials,
+                                                                 float* __restrict__ colparts) {
   __shared__ float red[17];
+  const int cc = blockIdx.x * kQkvThreads + threadIdx.x;
+  const bool live = cc < C8;
   const QuantParam q = load_q(qa);
-  float acc = 0.f;
-  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
-    float g[8], x[8];
-    load8(dgh + c * 8, g);
-    load8(u + c * 8, x);
+  float acc = 0.f, col[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (live) {
+    for (int r0 = blockIdx.y * kColRows; r0 < T_; r0 += gridDim.y * kColRows) {
+      Raw8<T> graw[kColRows], xraw[kColRows];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      float dg = g[j];
-      if (q.on) {
-        const float v = q_ratio_t<T>(gelu_t<T>(x[j]), q);
-        const bool in = q_inside(v, q);
-        acc += dg * (q_code(v, q) - (in ? v : 0.f));
-        dg = in ? dg : 0.f;
+      for (int i = 0; i < kColRows; ++i) {
+        if (r0 + i < T_) {
+          const size_t o = ((size_t)(r0 + i) * C8 + cc) * 8;
+          graw[i].load(dgh + o);
+          xraw[i].load(u + o);
+        }
       }
-      g[j] = dg * gelu_grad_t<T>(x[j]);
+#pragma unroll
+      for (int i = 0; i < kColRows; ++i) {
+        if (r0 + i >= T_) break;
+        float g[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float x = xraw[i].get(j);
+          float dg = graw[i].get(j);
+          if (q.on) {
+            const float v = q_ratio_t<T>(gelu_t<T>(x), q);
+            const bool in = q_inside(v, q);
+            acc += dg * (q_code(v, q) - (in ? v : 0.f));
+            dg = in ? dg : 0.f;
+          }
+          g[j] = dg * gelu_grad_t<T>(x);
+          col[j] += round_to<T>(g[j]);
+        }
+        store8(du + ((size_t)(r0 + i) * C8 + cc) * 8, g);
+      }
     }
-    store8(du + c * 8, g);
+    if (colparts) store8(colparts + ((size_t)blockIdx.y * C8 + cc) * 8, col);
   }
   const float t = block_sum(acc, red);
-  if (threadIdx.x == 0) partials[blockIdx.x] = t;
+  if (threadIdx.x == 0) partials[blockIdx.y * gridDim.x + blockIdx.x] = t;
 }
-int gelu_quant_bwd(int dt, const void* dgh, const void* u, void* du, int64_t n, QArg q, float* partials, hipStream_t st) {
-  const int g = ew_grid(n);
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(gelu_quant_bwd_k<T>, dim3(g), dim3(256), 0, st, (const T*)dgh, (const T*)u, (T*)du,
-                                       n / 8, q, partials));
+ColGrid gelu_quant_bwd(int dt, const void* dgh, const void* u, void* du, int T_, int C, QArg q, float* partials, float* colparts,
+                       hipStream_t st) {
+  const ColGrid g = col_grid(T_, C);
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(gelu_quant_bwd_k<T>, dim3(g.gx, g.gy), dim3(kQkvThreads), 0, st, (const T*)dgh, (const T*)u, (T*)du,
+                                       T_, C / 8, q, partials, colparts));
   return g;
 }
 
@@ -570,30 +614,6 @@ int mse_loss_grad(int dt, const void* fq, const void* ffp, void* grad, int64_t n
   MREM_DISPATCH(dt, hipLaunchKernelGGL(mse_k<T>, dim3(g), dim3(256), 0, st, (const T*)fq, (const T*)ffp, (T*)grad, n / 8, scale,
                                        partials));
   return g;
-}
-
-// ------------------------------------------------------------------------------
-// column sums of a [R, C] tensor (bias gradients): partials[R/32][C]
-// ------------------------------------------------------------------------------
-constexpr int kColsumRows = 32;
-template <class T>
-__global__ __launch_bounds__(256) void colsum_k(const T* __restrict__ a, int R, int C, float* __restrict__ partials) {
-  const int chunk = blockIdx.x * 256 + threadIdx.x;
-  if (chunk * 8 >= C) return;
-  const int r0 = blockIdx.y * kColsumRows;
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int r = r0; r < r0 + kColsumRows && r < R; ++r) {
-    float v[8];
-    load8(a + (size_t)r * C + chunk * 8, v);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] += v[j];
-  }
-  store8(partials + (size_t)blockIdx.y * C + chunk * 8, acc);
-}
-int colsum_partials(int dt, const void* a, int R, int C, float* partials, hipStream_t st) {
-  dim3 g((C / 8 + 255) / 256, (R + kColsumRows - 1) / kColsumRows);
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(colsum_k<T>, g, dim3(256), 0, st, (const T*)a, R, C, partials));
-  return (int)g.y;
 }
 
 // ------------------------------------------------------------------------------

@@ -69,8 +69,15 @@ void convert_f32(int dt, const float* src, void* dst, int64_t n, hipStream_t st)
 // ---- elementwise / normalisation ------------------------------------------------
 void act_quantize(int dt, const void* a, void* codes, int64_t n, QArg q, hipStream_t st);
 void gelu_quantize(int dt, const void* u, void* codes, int64_t n, QArg q, hipStream_t st);
-// du = dgh * inside(g) * gelu'(u); partials[grid] receive the step-size gradient terms
-int gelu_quant_bwd(int dt, const void* dgh, const void* u, void* du, int64_t n, QArg q, float* partials, hipStream_t st);
+// Grid of the column-walking backward kernels over a [T, C] tensor: gx column blocks, gy row
+// slabs (gy <= kColMaxParts, gx * gy <= 2048).
+constexpr int kColMaxParts = 512;
+struct ColGrid { int gx, gy; };
+ColGrid col_grid(int T_, int C);
+// du[T,C] = dgh * inside(g) * gelu'(u); partials[gx*gy]: step-size gradient terms;
+// colparts[gy][C] (may be null): column sums of du per row slab (bias gradient)
+ColGrid gelu_quant_bwd(int dt, const void* dgh, const void* u, void* du, int T_, int C, QArg q, float* partials, float* colparts,
+                       hipStream_t st);
 // d_out = d_q * inside(a) (d_out may be null); partials[grid]: step-size gradient terms
 int quant_bwd(int dt, const void* d_q, const void* a, void* d_out, int64_t n, QArg q, float* partials, hipStream_t st);
 // partial sums of d_q * (code - v*inside) only (layer-0 input quantizer)
@@ -89,9 +96,6 @@ int ln_bwd_parts(int T);
 // loss partials + gradient 2*(fq - ffp)*scale ; returns number of partials
 int mse_loss_grad(int dt, const void* fq, const void* ffp, void* grad, int64_t n, float scale, float* partials,
                   hipStream_t st);
-
-// partials[R/32][C]: column sums of 32-row slabs of a[R,C]; returns the number of slabs
-int colsum_partials(int dt, const void* a, int R, int C, float* partials, hipStream_t st);
 
 // out[c] = scale * sum_p partials[p*width + begin + c], c < len.  Jobs are collected on the
 // host while the first-stage kernels are enqueued and finished by reduce_jobs afterwards.
@@ -113,9 +117,10 @@ struct AttnQ {
 };
 // three column sections of qkv[T,3H] with their own quantizers -> integer codes
 void qkv_quantize(int dt, const void* qkv, void* codes, int T_, int H, QArg q, QArg k, QArg v, hipStream_t st);
-// d_qkv = d_qkvh * inside ; partials[grid][3]: step-size gradient terms of q, k, v
-int qkv_quant_bwd(int dt, const void* d_qkvh, const void* qkv, void* d_qkv, int T_, int H, QArg q, QArg k, QArg v, float* partials,
-                  hipStream_t st);
+// d_qkv = d_qkvh * inside ; partials[gx*gy][3]: step-size gradient terms of q, k, v;
+// colparts[gy][3H] (may be null): column sums of d_qkv per row slab (bias gradient)
+ColGrid qkv_quant_bwd(int dt, const void* d_qkvh, const void* qkv, void* d_qkv, int T_, int H, QArg q, QArg k, QArg v, float* partials,
+                      float* colparts, hipStream_t st);
 // codes [T,3H] (or raw values when the quantizers are off); ctx [T,H] stored context,
 // ctx_codes [T,H] its codes under quantizer c (null: skip); pmax_rows [B*nh*S] row
 // maxima of the probabilities (null: skip); seqlens may be null
