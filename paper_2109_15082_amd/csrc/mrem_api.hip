@@ -330,6 +330,7 @@ void wgrad(const Run& r, const float* params, float* grads, int l, int i, const 
   const QArg q = make_q(c, params, l, kInQuant[i]);
   if (q.on) e.alpha = q.s;  // the offset term z * db[n] of an asymmetric input quantizer is added by the update kernel
   e.out_f32 = 1;
+  e.c_zeroed = 1;  // the backward pass starts by zeroing the whole gradient buffer
   gemm(c->dt, 1, 1, dy, c->wN[i], codes_in, c->wK[i], g + c->foff[kWField[i]], c->wK[i], c->wN[i], c->wK[i], r.T, e, r.st);
 }
 // input-gradient product: d(in^) = dY * W^ with the dequantized weights [N_out, K_in]
@@ -347,6 +348,9 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
   const size_t slice = (size_t)T * H * es;
   const int64_t numel = (int64_t)T * H;
   Reductions red;
+  // One fill for everything that is added into (split weight-gradient products) or never written
+  // (the gradient slots of the fixed quantizer offsets).
+  fill_f32(grads, 0.f, mrem_param_count(c), r.st);
   for (int l = L - 1; l >= 0; --l) {
     const LayerWs& w = r.p.lw[l];
     const float* base = params + c->layer_stride * l;
@@ -446,7 +450,6 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       const int n = quant_bwd_reduce(c->dt, r.at(r.p.dxh), x, numel, make_q(c, params, 0, 0), parts, r.st);
       red.add(parts, n, 1, 0, 1, g + c->foff[MREM_F_S_A] + 0);
     }
-    fill_f32(g + c->foff[MREM_F_Z_A], 0.f, 8, r.st);
   }
   reduce_jobs(red.jobs.data(), (int)red.jobs.size(), r.st);
   loss_total(loss_out, L, r.st);

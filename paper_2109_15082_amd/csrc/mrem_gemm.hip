@@ -546,8 +546,8 @@ static void launch_mfma_modes(const void* A, int lda, const void* B, int ldb, vo
     // Few tiles and a long contraction (weight gradients of the square projections): two
     // k-slices.  Two atomic adds onto a zeroed fp32 value commute exactly, so the result
     // does not depend on which slice arrives first.
-    const int splits = (tiles <= 128 && K >= 2048 && (K / kBK) % 2 == 0 && !e.gelu) ? 2 : 1;
-    if (splits > 1) fill_f32((float*)C, 0.f, (int64_t)M * ldc, st);
+    const int splits = (tiles <= 256 && K >= 2048 && (K / kBK) % 2 == 0 && !e.gelu) ? 2 : 1;
+    if (splits > 1 && !e.c_zeroed) fill_f32((float*)C, 0.f, (int64_t)M * ldc, st);
     launch_mfma<128, 128, 2, 2, AT, BT, kRegBK, float>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
   } else {
     launch_mfma<128, 128, 2, 2, AT, BT, kRegBK, bf16_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);

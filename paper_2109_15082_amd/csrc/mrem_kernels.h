@@ -33,6 +33,7 @@ struct Epilogue {
   const float* bias = nullptr;
   int gelu = 0;
   int out_f32 = 0;
+  int c_zeroed = 0;  // the caller has already zeroed an fp32 C (a split contraction adds into it)
 };
 
 // C[M,N] = op(A) * op(B)^T.  a_t = 0: A is stored [M,K] (K contiguous); a_t = 1: A is stored
