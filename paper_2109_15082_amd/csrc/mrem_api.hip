@@ -96,6 +96,7 @@ struct Bump {
 
 struct LayerWs {
   size_t wcodes[4], what[4], zcorr[4];
+  size_t wcodes8[4], xcodes8, ctxcodes8, x1codes8, gcodes8;  // int8 copies of the codes the forward products read
   size_t xcodes, qkv, qkvcodes, ctx, ctxcodes, o, x1, x1codes, u, gcodes, y, mu1, rstd1, mu2, rstd2, stat_m, stat_l;
 };
 
@@ -108,6 +109,14 @@ struct Plan {
   size_t total;
 };
 
+// The forward products of the quantized module run on int8 codes (exact int32 accumulation) when
+// the storage type is bf16 and both bit widths are between 1 and 8; the token count must also
+// fit the tiles, which is decided per call.
+bool i8_config(const mrem_ctx* c) {
+  return c->dt == DT_BF16 && c->cfg.a_bits >= 1 && c->cfg.a_bits <= 8 && c->cfg.w_bits >= 1 && c->cfg.w_bits <= 8 && c->H % 128 == 0 &&
+         c->F % 128 == 0;
+}
+
 Plan make_plan(const mrem_ctx* c, int B, int S) {
   Plan p;
   Bump b;
@@ -119,7 +128,10 @@ Plan make_plan(const mrem_ctx* c, int B, int S) {
       w.wcodes[i] = b.take(n * es);
       w.what[i] = b.take(n * es);
       w.zcorr[i] = b.take((size_t)c->wN[i] * 4);
+      w.wcodes8[i] = b.take(i8_config(c) ? n : 0);
     }
+    w.xcodes8 = b.take(i8_config(c) ? T * H : 0); w.ctxcodes8 = b.take(i8_config(c) ? T * H : 0);
+    w.x1codes8 = b.take(i8_config(c) ? T * H : 0); w.gcodes8 = b.take(i8_config(c) ? T * F : 0);
     w.xcodes = b.take(T * H * es); w.qkv = b.take(T * 3 * H * es); w.qkvcodes = b.take(T * 3 * H * es);
     w.ctx = b.take(T * H * es); w.ctxcodes = b.take(T * H * es); w.o = b.take(T * H * es);
     w.x1 = b.take(T * H * es); w.x1codes = b.take(T * H * es); w.u = b.take(T * F * es); w.gcodes = b.take(T * F * es);
@@ -157,6 +169,8 @@ struct Run {
   int B, S, T;
   const int32_t* seqlens;
   template <class X = void> X* at(size_t off) const { return reinterpret_cast<X*>(ws + off); }
+  bool i8() const { return i8_config(c) && T % 128 == 0; }
+  int8_t* at8(size_t off) const { return i8() ? reinterpret_cast<int8_t*>(ws + off) : nullptr; }
 };
 
 // Second-stage reductions of a backward pass, collected while the first-stage kernels are enqueued.
@@ -198,7 +212,7 @@ const int kSField[4] = {MREM_F_SW_QKV, MREM_F_SW_O, MREM_F_SW_1, MREM_F_SW_2};
 const int kInQuant[4] = {0, 5, 6, 7};  // activation quantizer feeding each linear layer
 
 // quantized linear layer i of layer l: out = codes_in * wcodes^T with the steps in the epilogue
-void student_linear(const Run& r, const float* params, int l, int i, const void* in_codes, void* out) {
+void student_linear(const Run& r, const float* params, int l, int i, const void* in_codes, const int8_t* in_codes8, void* out) {
   const mrem_ctx* c = r.c;
   const float* base = params + c->layer_stride * l;
   Epilogue e;
@@ -207,6 +221,12 @@ void student_linear(const Run& r, const float* params, int l, int i, const void*
   if (c->cfg.w_bits > 0) e.col_scale = base + c->foff[kSField[i]];
   if (q.on && q.z) { e.beta = q.z; e.col_vec = r.at<float>(r.p.lw[l].zcorr[i]); }
   e.bias = base + c->foff[kBField[i]];
+  if (r.i8() && in_codes8) {
+    // unsigned codes (GELU output) are stored recentred by half their range; the epilogue adds that back
+    if (q.z) e.beta_alpha = 0.5f * (q.qp + 1.f);
+    gemm_i8(in_codes8, c->wK[i], r.at8(r.p.lw[l].wcodes8[i]), c->wK[i], out, c->wN[i], r.T, c->wN[i], c->wK[i], e, r.st);
+    return;
+  }
   gemm_nt(c->dt, in_codes, c->wK[i], r.at(r.p.lw[l].wcodes[i]), c->wK[i], out, c->wN[i], r.T, c->wN[i], c->wK[i], e, r.st);
 }
 
@@ -219,7 +239,9 @@ void prepare_weights(const Run& r, const float* params) {
     for (int i = 0; i < 4; ++i) {
       WeightJob j;
       j.w = base + c->foff[kWField[i]]; j.sw = base + c->foff[kSField[i]];
-      j.codes = r.at(r.p.lw[l].wcodes[i]); j.what = r.at(r.p.lw[l].what[i]); j.zcorr = r.at<float>(r.p.lw[l].zcorr[i]);
+      j.codes8 = r.at8(r.p.lw[l].wcodes8[i]);
+      j.codes = j.codes8 ? nullptr : r.at(r.p.lw[l].wcodes[i]);  // the forward reads one or the other
+      j.what = r.at(r.p.lw[l].what[i]); j.zcorr = r.at<float>(r.p.lw[l].zcorr[i]);
       j.N = c->wN[i]; j.K = c->wK[i];
       jobs.push_back(j);
     }
@@ -237,21 +259,27 @@ void student_forward(const Run& r, const float* params, const void* x_q, void* p
     const float* base = params + c->layer_stride * l;
     const void* x = l == 0 ? x_q : (const char*)per_layer_q + slice * (l - 1);
     void* f = (char*)per_layer_q + slice * l;
-    act_quantize(c->dt, x, r.at(w.xcodes), (int64_t)T * H, make_q(c, params, l, 0), r.st);
-    student_linear(r, params, l, 0, r.at(w.xcodes), r.at(w.qkv));
+    // every code tensor that feeds a linear layer is also written as int8 when the int8 products are in use
+    act_quantize(c->dt, x, r.at(w.xcodes), (int64_t)T * H, make_q(c, params, l, 0), r.st, r.at8(w.xcodes8));
+    student_linear(r, params, l, 0, r.at(w.xcodes), r.at8(w.xcodes8), r.at(w.qkv));
     const AttnQ aq = make_attn_q(c, params, l, true);
     qkv_quantize(c->dt, r.at(w.qkv), r.at(w.qkvcodes), T, H, aq.q, aq.k, aq.v, r.st);
-    if (attn_mfma_ok(c->dt, r.S, c->d))
+    if (attn_mfma_ok(c->dt, r.S, c->d)) {
       attn_fwd_mfma(r.at(w.qkvcodes), r.at(w.ctx), r.at(w.ctxcodes), aq, r.seqlens, r.B, r.S, c->nh, nullptr, r.at<float>(w.stat_m),
-                    r.at<float>(w.stat_l), r.st);
-    else
+                    r.at<float>(w.stat_l), r.st, r.at8(w.ctxcodes8));
+    } else {
       attn_fwd(c->dt, r.at(w.qkvcodes), r.at(w.ctx), r.at(w.ctxcodes), aq, r.seqlens, r.B, r.S, c->nh, c->d, nullptr, r.st);
-    student_linear(r, params, l, 1, r.at(w.ctxcodes), r.at(w.o));
+      if (r.i8()) codes_to_i8(c->dt, r.at(w.ctxcodes), r.at8(w.ctxcodes8), (int64_t)T * H, 0.f, r.st);
+    }
+    student_linear(r, params, l, 1, r.at(w.ctxcodes), r.at8(w.ctxcodes8), r.at(w.o));
     ln_fwd(c->dt, x, r.at(w.o), base + c->foff[MREM_F_LN1_G], base + c->foff[MREM_F_LN1_B], r.at(w.x1), r.at(w.x1codes),
-           make_q(c, params, l, 6), r.at<float>(w.mu1), r.at<float>(w.rstd1), T, H, c->cfg.ln_eps, r.st);
-    student_linear(r, params, l, 2, r.at(w.x1codes), r.at(w.u));
-    gelu_quantize(c->dt, r.at(w.u), r.at(w.gcodes), (int64_t)T * F, make_q(c, params, l, 7), r.st);
-    student_linear(r, params, l, 3, r.at(w.gcodes), r.at(w.y));
+           make_q(c, params, l, 6), r.at<float>(w.mu1), r.at<float>(w.rstd1), T, H, c->cfg.ln_eps, r.st, r.at8(w.x1codes8));
+    student_linear(r, params, l, 2, r.at(w.x1codes), r.at8(w.x1codes8), r.at(w.u));
+    {
+      const QArg qg = make_q(c, params, l, 7);
+      gelu_quantize(c->dt, r.at(w.u), r.at(w.gcodes), (int64_t)T * F, qg, r.st, r.at8(w.gcodes8), 0.5f * (qg.qp + 1.f));
+    }
+    student_linear(r, params, l, 3, r.at(w.gcodes), r.at8(w.gcodes8), r.at(w.y));
     ln_fwd(c->dt, r.at(w.x1), r.at(w.y), base + c->foff[MREM_F_LN2_G], base + c->foff[MREM_F_LN2_B], f, nullptr, QArg(),
            r.at<float>(w.mu2), r.at<float>(w.rstd2), T, H, c->cfg.ln_eps, r.st);
   }

@@ -97,7 +97,7 @@ template <int NT>
 __global__ __launch_bounds__(256) void attn_fwd_mfma_k(const bf16_t* __restrict__ codes, bf16_t* __restrict__ ctx,
                                                        bf16_t* __restrict__ ctx_codes, AttnQ aq, const int32_t* __restrict__ seqlens,
                                                        int S, int H, int nt, float* __restrict__ pmax_rows, float* __restrict__ stat_m,
-                                                       float* __restrict__ stat_l) {
+                                                       float* __restrict__ stat_l, int8_t* __restrict__ ctx_codes8) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   const int s_pad = 32 * nt, t_stride = s_pad + 8;
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem_raw);  // [s_pad][72]
@@ -205,6 +205,11 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_k(const bf16_t* __restrict_
             o[i] = qc5.on ? q_code(q_ratio_fma(r, qc5), qc5) : r;
           }
           store4(ctx_codes + orow + e, o[0], o[1], o[2], o[3]);
+          if (ctx_codes8) {
+            const unsigned pk = ((unsigned)(int)o[0] & 0xffu) | (((unsigned)(int)o[1] & 0xffu) << 8) | (((unsigned)(int)o[2] & 0xffu) << 16) |
+                                (((unsigned)(int)o[3] & 0xffu) << 24);
+            *reinterpret_cast<unsigned*>(ctx_codes8 + orow + e) = pk;
+          }
         }
       }
   }
@@ -407,7 +412,7 @@ bool attn_mfma_ok(int dt, int S, int d) { return dt == DT_BF16 && d == kD && S >
 
 template <int NT>
 static void fwd_launch(const void* codes, void* ctx, void* ctx_codes, const AttnQ& aq, const int32_t* seqlens, int B, int S, int nh,
-                       float* pmax_rows, float* stat_m, float* stat_l, hipStream_t st) {
+                       float* pmax_rows, float* stat_m, float* stat_l, hipStream_t st, int8_t* ctx_codes8) {
   const int nt = (S + 31) / 32, s_pad = 32 * nt;
   const size_t lds = ((size_t)s_pad * kRowStride + (size_t)kD * (s_pad + 8)) * sizeof(bf16_t);
   static size_t configured = 0;
@@ -417,12 +422,12 @@ static void fwd_launch(const void* codes, void* ctx, void* ctx_codes, const Attn
   }
   dim3 g((S + 127) / 128, nh, B);
   hipLaunchKernelGGL(attn_fwd_mfma_k<NT>, g, dim3(256), lds, st, (const bf16_t*)codes, (bf16_t*)ctx, (bf16_t*)ctx_codes, aq, seqlens, S,
-                     nh * kD, nt, pmax_rows, stat_m, stat_l);
+                     nh * kD, nt, pmax_rows, stat_m, stat_l, ctx_codes8);
 }
 void attn_fwd_mfma(const void* codes, void* ctx, void* ctx_codes, const AttnQ& aq, const int32_t* seqlens, int B, int S, int nh,
-                   float* pmax_rows, float* stat_m, float* stat_l, hipStream_t st) {
-  if (S <= 128) fwd_launch<4>(codes, ctx, ctx_codes, aq, seqlens, B, S, nh, pmax_rows, stat_m, stat_l, st);
-  else fwd_launch<12>(codes, ctx, ctx_codes, aq, seqlens, B, S, nh, pmax_rows, stat_m, stat_l, st);
+                   float* pmax_rows, float* stat_m, float* stat_l, hipStream_t st, int8_t* ctx_codes8) {
+  if (S <= 128) fwd_launch<4>(codes, ctx, ctx_codes, aq, seqlens, B, S, nh, pmax_rows, stat_m, stat_l, st, ctx_codes8);
+  else fwd_launch<12>(codes, ctx, ctx_codes, aq, seqlens, B, S, nh, pmax_rows, stat_m, stat_l, st, ctx_codes8);
 }
 
 // returns the number of partial sums written to ds_parts

@@ -42,6 +42,7 @@ __device__ __forceinline__ void store8(bf16_t* p, const float* v) {
 
 // eight stored values kept as loaded (4 registers for bf16, 8 for fp32) until they are needed
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2e_t __attribute__((ext_vector_type(2)));
 typedef float f32x4v_t __attribute__((ext_vector_type(4)));
 template <class T>
 struct Raw8;
@@ -63,6 +64,18 @@ struct Raw8<float> {
   }
   __device__ __forceinline__ float get(int j) const { return j < 4 ? a[j] : b[j - 4]; }
 };
+
+// eight integer-valued codes (minus shift) as int8, one 8-byte store
+__device__ __forceinline__ void store8_i8(int8_t* p, const float* v, float shift) {
+  unsigned lo = 0u, hi = 0u;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    lo |= ((unsigned)(int)(v[j] - shift) & 0xffu) << (8 * j);
+    hi |= ((unsigned)(int)(v[4 + j] - shift) & 0xffu) << (8 * j);
+  }
+  u32x2e_t r = {lo, hi};
+  *reinterpret_cast<u32x2e_t*>(p) = r;
+}
 
 __device__ __forceinline__ QuantParam load_q(const QArg& a) {
   QuantParam q;
@@ -92,7 +105,7 @@ static inline int ew_grid(int64_t n) {
 // activation quantizer forward: integer-valued codes in the storage type
 // ------------------------------------------------------------------------------
 template <class T>
-__global__ void act_quantize_k(const T* __restrict__ a, T* __restrict__ codes, int64_t nchunks, QArg qa) {
+__global__ void act_quantize_k(const T* __restrict__ a, T* __restrict__ codes, int64_t nchunks, QArg qa, int8_t* __restrict__ codes8) {
   const QuantParam q = load_q(qa);
   for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
     float v[8];
@@ -102,10 +115,22 @@ __global__ void act_quantize_k(const T* __restrict__ a, T* __restrict__ codes, i
       for (int j = 0; j < 8; ++j) v[j] = q_code(q_ratio_t<T>(v[j], q), q);
     }
     store8(codes + c * 8, v);
+    if (codes8) store8_i8(codes8 + c * 8, v, 0.f);
   }
 }
-void act_quantize(int dt, const void* a, void* codes, int64_t n, QArg q, hipStream_t st) {
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(act_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)a, (T*)codes, n / 8, q));
+void act_quantize(int dt, const void* a, void* codes, int64_t n, QArg q, hipStream_t st, int8_t* codes8) {
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(act_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)a, (T*)codes, n / 8, q, codes8));
+}
+template <class T>
+__global__ void codes_to_i8_k(const T* __restrict__ codes, int8_t* __restrict__ codes8, int64_t nchunks, float shift) {
+  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
+    float v[8];
+    load8(codes + c * 8, v);
+    store8_i8(codes8 + c * 8, v, shift);
+  }
+}
+void codes_to_i8(int dt, const void* codes, int8_t* codes8, int64_t n, float shift, hipStream_t st) {
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(codes_to_i8_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)codes, codes8, n / 8, shift));
 }
 
 // Three column sections of qkv[T,3H] with their own quantizers.  A thread owns one 8-element
@@ -268,7 +293,8 @@ int quant_bwd_reduce(int dt, const void* d_q, const void* a, int64_t n, QArg q, 
 // GELU + quantizer of its output (unsigned grid with offset)
 // ------------------------------------------------------------------------------
 template <class T>
-__global__ void gelu_quantize_k(const T* __restrict__ u, T* __restrict__ codes, int64_t nchunks, QArg qa) {
+__global__ void gelu_quantize_k(const T* __restrict__ u, T* __restrict__ codes, int64_t nchunks, QArg qa, int8_t* __restrict__ codes8,
+                                float shift8) {
   const QuantParam q = load_q(qa);
   for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
     float v[8];
@@ -279,10 +305,12 @@ __global__ void gelu_quantize_k(const T* __restrict__ u, T* __restrict__ codes, 
       v[j] = q.on ? q_code(q_ratio_t<T>(g, q), q) : g;
     }
     store8(codes + c * 8, v);
+    if (codes8) store8_i8(codes8 + c * 8, v, shift8);
   }
 }
-void gelu_quantize(int dt, const void* u, void* codes, int64_t n, QArg q, hipStream_t st) {
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(gelu_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)u, (T*)codes, n / 8, q));
+void gelu_quantize(int dt, const void* u, void* codes, int64_t n, QArg q, hipStream_t st, int8_t* codes8, float shift8) {
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(gelu_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)u, (T*)codes, n / 8, q, codes8,
+                                       shift8));
 }
 
 // du = dgh * inside * gelu'(u) ; partials[block]: step-size gradient terms ; colparts: column sums of du
@@ -347,7 +375,8 @@ constexpr int kLnMaxChunks = 4;  // hidden <= 64 lanes * 8 * 4 = 2048
 template <class T>
 __global__ void ln_fwd_k(const T* __restrict__ x, const T* __restrict__ r, const float* __restrict__ gamma,
                          const float* __restrict__ beta, T* __restrict__ y, T* __restrict__ ycodes, QArg qa,
-                         float* __restrict__ mu_out, float* __restrict__ rstd_out, int T_, int H, float eps) {
+                         float* __restrict__ mu_out, float* __restrict__ rstd_out, int T_, int H, float eps,
+                         int8_t* __restrict__ ycodes8) {
   const QuantParam q = load_q(qa);
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
@@ -396,14 +425,15 @@ __global__ void ln_fwd_k(const T* __restrict__ x, const T* __restrict__ r, const
           o[j] = q.on ? q_code(q_ratio_t<T>(s, q), q) : s;
         }
         store8(ycodes + (size_t)row * H + c * 8, o);
+        if (ycodes8) store8_i8(ycodes8 + (size_t)row * H + c * 8, o, 0.f);
       }
     }
   }
 }
 void ln_fwd(int dt, const void* x, const void* r, const float* gamma, const float* beta, void* y, void* ycodes, QArg q,
-            float* mu, float* rstd, int T_, int H, float eps, hipStream_t st) {
+            float* mu, float* rstd, int T_, int H, float eps, hipStream_t st, int8_t* ycodes8) {
   MREM_DISPATCH(dt, hipLaunchKernelGGL(ln_fwd_k<T>, dim3((T_ + 3) / 4), dim3(256), 0, st, (const T*)x, (const T*)r, gamma, beta,
-                                       (T*)y, (T*)ycodes, q, mu, rstd, T_, H, eps));
+                                       (T*)y, (T*)ycodes, q, mu, rstd, T_, H, eps, ycodes8));
 }
 
 constexpr int kLnBwdWaves = 8;       // wavefronts per block
@@ -793,7 +823,8 @@ __global__ __launch_bounds__(128) void weight_codes_k(WeightJobTable tab, float 
       c[j] = x[j];
       if (on) { c[j] = rintf(fminf(fmaxf(__fdiv_rn(x[j], s), -qp), qp)); acc += c[j]; x[j] = s * c[j]; }
     }
-    store8(codes + row + k, c);
+    if (codes) store8(codes + row + k, c);
+    if (jb.codes8) store8_i8(jb.codes8 + row + k, c, 0.f);
     if (what) store8(what + row + k, x);
   }
   acc = block_sum(acc, red);

@@ -99,7 +99,7 @@ __global__ void gemm_nt_simt_k(const TA* __restrict__ A, int lda, const TA* __re
   }
   EpiVals ev;
   ev.alpha = e.alpha ? *e.alpha : 1.f;
-  ev.beta = e.beta ? *e.beta : 0.f;
+  ev.beta = (e.beta ? *e.beta : 0.f) + e.beta_alpha * ev.alpha;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -125,6 +125,8 @@ __global__ void gemm_nt_simt_k(const TA* __restrict__ A, int lda, const TA* __re
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+typedef int i32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kBK = 64;
 constexpr int kRegBK = 64;  // k-step of the register-staged kernel
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16
 
   // epilogue: out = acc * (alpha * col_scale[n]) + beta * (col_vec[n] + row_vec[m]) + bias[n]
   const float alpha = e.alpha ? *e.alpha : 1.f;
-  const float beta = e.beta ? *e.beta : 0.f;
+  const float beta = (e.beta ? *e.beta : 0.f) + e.beta_alpha * alpha;
   const bool split = gridDim.y > 1, lead = blockIdx.y == 0;  // the additive terms go in once, with slice 0
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
@@ -328,12 +330,34 @@ __device__ __forceinline__ void wait_vmcnt_le(int n) {
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, class TO>
-__global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + kProducers)) void gemm_nt_pc_k(const bf16_t* __restrict__ A, int lda,
-                                                                                       const bf16_t* __restrict__ B, int ldb,
+// TE: element type of A and B, bf16_t (values or integer codes, fp32 accumulation) or int8_t
+// (integer codes, exact int32 accumulation with the 32x32x32 int8 instruction).  A stage row is
+// 128 bytes either way: 64 bf16 or 128 int8 values of k.
+template <class TE>
+struct PcElem;
+template <>
+struct PcElem<bf16_t> {
+  typedef bf16x8_t frag_t;
+  typedef f32x16_t acc_t;
+  static __device__ __forceinline__ acc_t mfma(frag_t a, frag_t b, acc_t c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+};
+template <>
+struct PcElem<int8_t> {
+  typedef i32x4_t frag_t;
+  typedef i32x16_t acc_t;
+  static __device__ __forceinline__ acc_t mfma(frag_t a, frag_t b, acc_t c) { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, class TO, class TE>
+__global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + kProducers)) void gemm_nt_pc_k(const TE* __restrict__ A, int lda,
+                                                                                       const TE* __restrict__ B, int ldb,
                                                                                        TO* __restrict__ C, int ldc, int M, int N, int K,
                                                                                        Epilogue e, int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  constexpr int CE = 16 / (int)sizeof(TE);    // elements per 16-byte chunk
+  constexpr int SK = 128 / (int)sizeof(TE);   // k values per stage
+  typedef typename PcElem<TE>::frag_t frag_t;
+  typedef typename PcElem<TE>::acc_t acc_t;
   constexpr int NCONS = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int MT = WM / 32, NT = WN / 32;
@@ -356,7 +380,7 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + kProducers)) void gemm_nt
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // gridDim.y > 1: split-K, each y-slice accumulates its share of the k-steps into fp32 C with atomic adds
-  const int KT = K / kBK / (int)gridDim.y;
+  const int KT = K / SK / (int)gridDim.y;
   const int kt0 = (int)blockIdx.y * KT;
 
   if (wave >= NCONS) {
@@ -368,17 +392,17 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + kProducers)) void gemm_nt
     const int pw = __builtin_amdgcn_readfirstlane(wave) - NCONS;
     const int sub_row = lane >> 3, slot = lane & 7;
     const int c_even = slot ^ (sub_row >> 1), c_odd = slot ^ (4 + (sub_row >> 1));
-    const size_t a_lane_even = (size_t)sub_row * lda + c_even * 8, a_lane_odd = (size_t)sub_row * lda + c_odd * 8;
-    const size_t b_lane_even = (size_t)sub_row * ldb + c_even * 8, b_lane_odd = (size_t)sub_row * ldb + c_odd * 8;
-    const bf16_t* Ablk = A + (size_t)m0 * lda;
-    const bf16_t* Bblk = B + (size_t)n0 * ldb;
+    const size_t a_lane_even = (size_t)sub_row * lda + c_even * CE, a_lane_odd = (size_t)sub_row * lda + c_odd * CE;
+    const size_t b_lane_even = (size_t)sub_row * ldb + c_even * CE, b_lane_odd = (size_t)sub_row * ldb + c_odd * CE;
+    const TE* Ablk = A + (size_t)m0 * lda;
+    const TE* Bblk = B + (size_t)n0 * ldb;
 #define MREM_ISSUE_STAGE(kt_)                                                                                      \
     {                                                                                                              \
       unsigned char* stage_ = smem_raw + ((kt_) % STAGES) * STAGE_BYTES;                                           \
-      const int k0_ = (kt0 + (kt_)) * kBK;                                                                               \
+      const int k0_ = (kt0 + (kt_)) * SK;                                                                                \
       _Pragma("unroll") for (int i = 0; i < PER_PROD; ++i) {                                                       \
         const int gi = pw * PER_PROD + i;                                                                          \
-        const bf16_t* src;                                                                                         \
+        const TE* src;                                                                                             \
         if (gi < BM / 8) src = Ablk + (size_t)(8 * gi) * lda + k0_ + ((gi & 1) ? a_lane_odd : a_lane_even);        \
         else src = Bblk + (size_t)(8 * (gi - BM / 8)) * ldb + k0_ + ((gi & 1) ? b_lane_odd : b_lane_even);         \
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,                       \
@@ -404,13 +428,13 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + kProducers)) void gemm_nt
 
   // ---------------- consumers ----------------
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  f32x16_t acc[MT][NT];
+  acc_t acc[MT][NT];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int j = 0; j < NT; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
   const int frag_row = lane & 31, half = lane >> 5;
   // byte offsets of this lane's fragment rows inside a stage, and its swizzle term per MFMA tile
   int a_off[MT], b_off[NT], a_sw[MT], b_sw[NT];
@@ -429,20 +453,20 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + kProducers)) void gemm_nt
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();  // stage 0 has landed
   asm volatile("" ::: "memory");
-  bf16x8_t af[2][MT], bfr[2][NT];
+  frag_t af[2][MT], bfr[2][NT];
 #define MREM_READ_FRAGS(buf, stage_ptr, kk_)                                                                       \
   {                                                                                                                \
     const int c_ = 2 * (kk_) + half;                                                                               \
     _Pragma("unroll") for (int i = 0; i < MT; ++i)                                                                 \
-        af[buf][i] = *reinterpret_cast<const bf16x8_t*>((stage_ptr) + a_off[i] + ((c_ ^ a_sw[i]) << 4));           \
+        af[buf][i] = *reinterpret_cast<const frag_t*>((stage_ptr) + a_off[i] + ((c_ ^ a_sw[i]) << 4));           \
     _Pragma("unroll") for (int j = 0; j < NT; ++j)                                                                 \
-        bfr[buf][j] = *reinterpret_cast<const bf16x8_t*>((stage_ptr) + b_off[j] + ((c_ ^ b_sw[j]) << 4));          \
+        bfr[buf][j] = *reinterpret_cast<const frag_t*>((stage_ptr) + b_off[j] + ((c_ ^ b_sw[j]) << 4));          \
   }
 #define MREM_MFMAS(buf)                                                                                            \
   {                                                                                                                \
     _Pragma("unroll") for (int i = 0; i < MT; ++i)                                                                 \
         _Pragma("unroll") for (int j = 0; j < NT; ++j)                                                             \
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);      \
+            acc[i][j] = PcElem<TE>::mfma(af[buf][i], bfr[buf][j], acc[i][j]);             \
   }
   MREM_READ_FRAGS(0, smem_raw, 0)
   for (int kt = 0; kt < KT; ++kt) {
@@ -464,7 +488,7 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + kProducers)) void gemm_nt
 #undef MREM_MFMAS
 
   const float alpha = e.alpha ? *e.alpha : 1.f;
-  const float beta = e.beta ? *e.beta : 0.f;
+  const float beta = (e.beta ? *e.beta : 0.f) + e.beta_alpha * alpha;
   const bool split = gridDim.y > 1, lead = blockIdx.y == 0;  // the additive terms go in once, with slice 0
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
@@ -478,7 +502,7 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + kProducers)) void gemm_nt
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = mb + 8 * (r >> 2) + (r & 3);
-        float v = acc[i][j][r] * cs + cb;
+        float v = (float)acc[i][j][r] * cs + cb;
         if (e.beta && e.row_vec && lead) v += beta * e.row_vec[m];
         if constexpr (sizeof(TO) == 4) {
           if (split) {
@@ -493,19 +517,19 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + kProducers)) void gemm_nt
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, class TO>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, class TO, class TE = bf16_t>
 static void launch_pc(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
                       hipStream_t st, int k_splits = 1) {
   constexpr size_t lds = (size_t)STAGES * (BM + BN) * 128;
   static bool configured = false;
   if (!configured) {
-    hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_pc_k<BM, BN, WAVES_M, WAVES_N, STAGES, TO>),
+    hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_pc_k<BM, BN, WAVES_M, WAVES_N, STAGES, TO, TE>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     configured = true;
   }
   const int tiles_m = M / BM, tiles_n = N / BN;
-  hipLaunchKernelGGL((gemm_nt_pc_k<BM, BN, WAVES_M, WAVES_N, STAGES, TO>), dim3(tiles_m * tiles_n, k_splits),
-                     dim3(64 * (WAVES_M * WAVES_N + kProducers)), lds, st, (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (TO*)C, ldc, M, N, K,
+  hipLaunchKernelGGL((gemm_nt_pc_k<BM, BN, WAVES_M, WAVES_N, STAGES, TO, TE>), dim3(tiles_m * tiles_n, k_splits),
+                     dim3(64 * (WAVES_M * WAVES_N + kProducers)), lds, st, (const TE*)A, lda, (const TE*)B, ldb, (TO*)C, ldc, M, N, K,
                      e, tiles_m, tiles_n);
 }
 
@@ -529,6 +553,33 @@ void gemm(int dt, int a_t, int b_t, const void* A, int lda, const void* B, int l
   hipEventCreate(&r.e1);
   hipEventRecord(r.e0, st);
   gemm_launch(dt, a_t, b_t, A, lda, B, ldb, C, ldc, M, N, K, e, st);
+  hipEventRecord(r.e1, st);
+  g_prof.push_back(r);
+}
+
+bool gemm_i8_ok(const void* A, int lda, const void* B, int ldb, int M, int N, int K) {
+  return M % 128 == 0 && N % 128 == 0 && K % 128 == 0 && lda % 16 == 0 && ldb % 16 == 0 &&
+         (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (reinterpret_cast<uintptr_t>(B) & 15) == 0;
+}
+// Measured on MI355X: three stages with one block per compute unit for one-tile-per-CU shapes;
+// two stages (64 KiB, two co-resident blocks) when a compute unit works through several tiles.
+static void gemm_i8_launch(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
+                           hipStream_t st) {
+  const int tiles = (M / 128) * (N / 128);
+  if (tiles <= 256) launch_pc<128, 128, 2, 2, 3, bf16_t, int8_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+  else launch_pc<128, 128, 2, 2, 2, bf16_t, int8_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+}
+void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e, hipStream_t st) {
+  if (!g_prof_on) {
+    gemm_i8_launch(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+    return;
+  }
+  GemmRecord r;
+  r.flops = 2.0 * (double)M * (double)N * (double)K;
+  hipEventCreate(&r.e0);
+  hipEventCreate(&r.e1);
+  hipEventRecord(r.e0, st);
+  gemm_i8_launch(A, lda, B, ldb, C, ldc, M, N, K, e, st);
   hipEventRecord(r.e1, st);
   g_prof.push_back(r);
 }

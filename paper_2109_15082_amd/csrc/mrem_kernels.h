@@ -21,8 +21,9 @@ struct QArg {
   int on = 0;
 };
 
-// out[m,n] = acc * (alpha * col_scale[n]) + beta * (col_vec[n] + row_vec[m]) + bias[n]
-// alpha/beta are device scalars (null: alpha = 1, beta = 0); vectors may be null.
+// out[m,n] = acc * (alpha * col_scale[n]) + (beta + beta_alpha * alpha) * (col_vec[n] + row_vec[m]) + bias[n]
+// alpha/beta are device scalars (null: alpha = 1, beta = 0); vectors may be null.  beta_alpha
+// undoes a constant subtracted from the codes of A (unsigned codes stored as int8).
 // gelu: out = round(gelu(round(out))) in the storage type.  out_f32: C is fp32.
 struct Epilogue {
   const float* alpha = nullptr;
@@ -34,12 +35,17 @@ struct Epilogue {
   int gelu = 0;
   int out_f32 = 0;
   int c_zeroed = 0;  // the caller has already zeroed an fp32 C (a split contraction adds into it)
+  float beta_alpha = 0.f;
 };
 
 // C[M,N] = op(A) * op(B)^T.  a_t = 0: A is stored [M,K] (K contiguous); a_t = 1: A is stored
 // [K,M] (the contraction index is the slow one).  Same for B with N.  lda/ldb: row pitch.
 void gemm(int dt, int a_t, int b_t, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
           const Epilogue& e, hipStream_t st);
+// C[M,N] (bf16) = A[M,K] * B[N,K]^T on int8 codes with exact int32 accumulation; needs
+// gemm_i8_ok(...).  Same epilogue.
+bool gemm_i8_ok(const void* A, int lda, const void* B, int ldb, int M, int N, int K);
+void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e, hipStream_t st);
 // C[M,N] = A[M,K] * B[N,K]^T  (both operands contiguous along K)
 void gemm_nt(int dt, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
              const Epilogue& e, hipStream_t st);
@@ -59,17 +65,22 @@ constexpr int kMaxMatrixJobs = 24;
 struct WeightJob {
   const float* w;
   const float* sw;
-  void* codes;
+  void* codes;     // may be null when only the int8 codes are wanted
   void* what;
   float* zcorr;
+  int8_t* codes8;  // may be null
   int N, K;
 };
 void weight_prepare(int dt, const WeightJob* jobs, int njobs, int bits, hipStream_t st);
 void convert_f32(int dt, const float* src, void* dst, int64_t n, hipStream_t st);
 
 // ---- elementwise / normalisation ------------------------------------------------
-void act_quantize(int dt, const void* a, void* codes, int64_t n, QArg q, hipStream_t st);
-void gelu_quantize(int dt, const void* u, void* codes, int64_t n, QArg q, hipStream_t st);
+// codes8 (may be null): the same codes as int8, for the int8 products of the forward pass
+void act_quantize(int dt, const void* a, void* codes, int64_t n, QArg q, hipStream_t st, int8_t* codes8 = nullptr);
+// codes8 (may be null): codes - shift8 as int8 (the unsigned grid of the GELU output, recentred)
+void gelu_quantize(int dt, const void* u, void* codes, int64_t n, QArg q, hipStream_t st, int8_t* codes8 = nullptr, float shift8 = 0.f);
+// bf16/fp32 integer codes -> int8 (codes - shift); for producers without an int8 output of their own
+void codes_to_i8(int dt, const void* codes, int8_t* codes8, int64_t n, float shift, hipStream_t st);
 // Grid of the column-walking backward kernels over a [T, C] tensor: gx column blocks, gy row
 // slabs (gy <= kColMaxParts, gx * gy <= 2048).
 constexpr int kColMaxParts = 512;
@@ -86,7 +97,7 @@ int quant_bwd_reduce(int dt, const void* d_q, const void* a, int64_t n, QArg q, 
 
 // y = LN(x + r) * gamma + beta ; optional codes of y ; mean/rstd saved
 void ln_fwd(int dt, const void* x, const void* r, const float* gamma, const float* beta, void* y, void* ycodes, QArg q,
-            float* mu, float* rstd, int T, int H, float eps, hipStream_t st);
+            float* mu, float* rstd, int T, int H, float eps, hipStream_t st, int8_t* ycodes8 = nullptr);
 // dy = d_a + d_b + d_q * inside(a_q)   (any of the three may be null)
 // dr = LN backward of dy through LN(x + r); partials[nparts][3H+1]: dgamma, dbeta, colsum(dr), ds
 int ln_bwd(int dt, const void* d_a, const void* d_b, const void* d_q, const void* a_q, QArg q, const void* x,
@@ -139,7 +150,7 @@ void attn_bwd(int dt, const void* codes, const void* dctx, void* d_qkvh, const A
 // up to 32) and returns the number of partial sums written to ds_parts.
 bool attn_mfma_ok(int dt, int S, int d);
 void attn_fwd_mfma(const void* codes, void* ctx, void* ctx_codes, const AttnQ& aq, const int32_t* seqlens, int B, int S, int nh,
-                   float* pmax_rows, float* stat_m, float* stat_l, hipStream_t st);
+                   float* pmax_rows, float* stat_m, float* stat_l, hipStream_t st, int8_t* ctx_codes8 = nullptr);
 int attn_bwd_mfma(const void* codes, const void* dctx, void* d_qkvh, const AttnQ& aq, const int32_t* seqlens, int B, int S, int nh,
                   const float* stat_m, const float* stat_l, void* pt_scratch, void* dat_scratch, float* ds_parts, hipStream_t st);
 
