@@ -5,6 +5,8 @@
 #include "mrem_common.h"
 #include "mrem_kernels.h"
 
+#include <type_traits>
+
 #include <vector>
 
 namespace mrem {
@@ -172,7 +174,10 @@ struct OperandTile {
   }
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, int BK, class TO>
+// I8: the operands are int8 codes seen as pairs (the caller passes K, lda and ldb in units of two
+// bytes): data movement and fragment addresses are those of the bf16 case, the product runs on
+// the 32x32x32 int8 instruction with exact int32 accumulation.  Not for transposed operands.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, int BK, class TO, bool I8 = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B,
                                                                       int ldb, TO* __restrict__ C, int ldc, int M, int N, int K, Epilogue e,
                                                                       int tiles_m, int tiles_n) {
@@ -203,13 +208,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
-  f32x16_t acc[MT][NT];
+  static_assert(!I8 || (!AT && !BT), "int8 operands are read along k only");
+  typedef typename std::conditional<I8, i32x16_t, f32x16_t>::type acc_t;
+  acc_t acc[MT][NT];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int j = 0; j < NT; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
   // gridDim.y > 1: split-K, each y-slice accumulates its share of the k-steps into fp32 C with atomic adds
   const int KT = K / BK / (int)gridDim.y;
@@ -251,7 +258,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16
 #pragma unroll
       for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NT; ++j) {
+          if constexpr (I8) {
+            union { bf16x8_t h; i32x4_t w; } ua, ub;
+            ua.h = af[i];
+            ub.h = bfr[j];
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ua.w, ub.w, acc[i][j], 0, 0, 0);
+          } else {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          }
+        }
     }
     if (kt + 1 < KT) MREM_STORE_LDS(cur ^ 1)
     __syncthreads();
@@ -275,7 +291,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = mb + 8 * (r >> 2) + (r & 3);
-        float v = acc[i][j][r] * cs + cb;
+        float v = (float)acc[i][j][r] * cs + cb;
         if (e.beta && e.row_vec && lead) v += beta * e.row_vec[m];
         if constexpr (sizeof(TO) == 4) {
           if (split) {
@@ -290,19 +306,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, int BK, class TO>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, int BK, class TO, bool I8 = false>
 static void launch_mfma(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
                         hipStream_t st, int k_splits = 1) {
   constexpr int NTHREADS = 64 * WAVES_M * WAVES_N;
   constexpr size_t lds = 2 * (size_t)(OperandTile<AT, BM, NTHREADS, BK>::ELEMS + OperandTile<BT, BN, NTHREADS, BK>::ELEMS) * sizeof(bf16_t);
   static bool configured = false;
   if (!configured) {
-    hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, BK, TO>),
+    hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, BK, TO, I8>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     configured = true;
   }
   const int tiles_m = M / BM, tiles_n = N / BN;
-  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, BK, TO>), dim3(tiles_m * tiles_n, k_splits), dim3(NTHREADS), lds, st,
+  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, BK, TO, I8>), dim3(tiles_m * tiles_n, k_splits), dim3(NTHREADS), lds, st,
                      (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (TO*)C, ldc, M, N, K, e, tiles_m, tiles_n);
 }
 
@@ -561,13 +577,13 @@ bool gemm_i8_ok(const void* A, int lda, const void* B, int ldb, int M, int N, in
   return M % 128 == 0 && N % 128 == 0 && K % 128 == 0 && lda % 16 == 0 && ldb % 16 == 0 &&
          (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (reinterpret_cast<uintptr_t>(B) & 15) == 0;
 }
-// Measured on MI355X: three stages with one block per compute unit for one-tile-per-CU shapes;
-// two stages (64 KiB, two co-resident blocks) when a compute unit works through several tiles.
+// Measured on MI355X: the producer/consumer kernel for one-tile-per-CU shapes, two co-resident
+// blocks of the register-staged kernel when a compute unit works through several tiles.
 static void gemm_i8_launch(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
                            hipStream_t st) {
   const int tiles = (M / 128) * (N / 128);
   if (tiles <= 256) launch_pc<128, 128, 2, 2, 3, bf16_t, int8_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
-  else launch_pc<128, 128, 2, 2, 2, bf16_t, int8_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+  else launch_mfma<128, 128, 2, 2, false, false, kRegBK, bf16_t, true>(A, lda / 2, B, ldb / 2, C, ldc, M, N, K / 2, e, st);
 }
 void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e, hipStream_t st) {
   if (!g_prof_on) {
