@@ -121,7 +121,9 @@ def main():
     dt = time.perf_counter() - t0
     # pass 2, the same K steps again with a HIP event pair around every matrix-product launch (on the
     # stream the products run on).  Kept out of pass 1 because each recorded event stalls the queue for
-    # about 5 us, which with 96 products a step would add about a millisecond to every step.
+    # about 5 us, which with 96 products a step would add about a millisecond to every step.  In this
+    # pass the library also keeps the teacher's forward pass on the caller's stream (in pass 1 it runs on
+    # a side stream next to the quantized forward pass), so that every product is timed alone.
     B.mrem_profile_gemm_begin()
     t1 = time.perf_counter()
     for _ in range(args.steps):

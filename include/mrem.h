@@ -14,7 +14,11 @@
  *    library never allocates, frees or retains device memory.  "host" pointers are
  *    ordinary host memory.
  *  - All work is enqueued on the caller's hipStream_t (passed as void*, NULL = the
- *    default stream).  Calls return without synchronising.
+ *    default stream) or ordered with it: mrem_module_step runs the full-precision
+ *    forward pass on a side stream that the context owns (default priority, created
+ *    on the first step), forked from the caller's stream by an event at the start of
+ *    the call and joined to it before the loss; to the caller the call behaves like
+ *    work on its own stream.  Calls return without synchronising.
  *  - Arguments are validated on the host before anything is enqueued; a call that
  *    returns an error has had no effect on device memory.
  *  - Return value: MREM_OK or a negative mrem_status.  mrem_last_error() gives a
@@ -186,6 +190,7 @@ mrem_status mrem_module_forward(mrem_ctx* ctx, const float* params, const float*
  *   per_layer_fp, per_layer_q  device act_dtype [n_layers, batch, seq, hidden] (out, required)
  *   grads_out                device fp32 [mrem_param_count] or NULL (out): the gradients
  *                            that were applied (Z_A slots are written as 0)
+ * A context must be used from the device that was current at its first step.
  */
 mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* adam_m, float* adam_v, int64_t step_index,
                              float lr, const float* teacher, const void* teacher_cache, const void* x_fp,

@@ -22,6 +22,11 @@ struct mrem_ctx {
   int64_t tc_off[4], tc_layer_stride;  // teacher cache, in elements
   int wN[4], wK[4];                    // the four linear layers [N,K]
   std::string err;
+  // side stream for the teacher's forward pass of a step (created on the first step, on the
+  // device that is current then; default priority) and the two events of its fork and join
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  int side_device = -1;
 };
 
 static mrem_status fail(const mrem_ctx* ctx, mrem_status st, const std::string& msg) {
@@ -65,7 +70,16 @@ extern "C" mrem_status mrem_create(const mrem_config* cfg, mrem_ctx** out) {
   return MREM_OK;
 }
 
-extern "C" void mrem_destroy(mrem_ctx* ctx) { delete ctx; }
+extern "C" void mrem_destroy(mrem_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->side) {
+    (void)hipStreamSynchronize(ctx->side);
+    (void)hipEventDestroy(ctx->ev_fork);
+    (void)hipEventDestroy(ctx->ev_join);
+    (void)hipStreamDestroy(ctx->side);
+  }
+  delete ctx;
+}
 extern "C" int64_t mrem_param_count(const mrem_ctx* ctx) { return ctx ? ctx->layer_stride * ctx->L : -1; }
 extern "C" int64_t mrem_teacher_count(const mrem_ctx* ctx) { return mrem_param_count(ctx); }
 extern "C" int64_t mrem_param_offset(const mrem_ctx* ctx, int32_t layer, int32_t field) {
@@ -666,9 +680,33 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
   if (step_index < 1) return fail(ctx, MREM_EINVAL, "mrem_module_step: step_index is 1-based");
   Run r{ctx, plan, (char*)workspace, (hipStream_t)hip_stream, batch, seq, batch * seq, seqlens};
   float* grads = grads_out ? grads_out : r.at<float>(r.p.grads);
-  teacher_forward(r, teacher, teacher_cache, x_fp, per_layer_fp, nullptr);
+  // The teacher's forward pass shares nothing with the quantized forward pass (its own scratch, its
+  // own outputs), so it runs on a side stream, forked from the caller's stream and joined before
+  // the loss: kernels of the two passes fill each other's tails.
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return fail(ctx, MREM_EHIP, "mrem_module_step: no current device");
+  if (!ctx->side) {
+    if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess)
+      return fail(ctx, MREM_EHIP, "mrem_module_step: cannot create the side stream");
+    ctx->side_device = dev;
+  }
+  if (dev != ctx->side_device) return fail(ctx, MREM_EINVAL, "mrem_module_step: the context was first used on another device");
+  const bool fork = !gemm_profile_active();  // per-launch timing wants every product alone on the device
+  if (fork) {
+    Run rt = r;
+    rt.st = ctx->side;
+    (void)hipEventRecord(ctx->ev_fork, r.st);
+    (void)hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
+    teacher_forward(rt, teacher, teacher_cache, x_fp, per_layer_fp, nullptr);
+    (void)hipEventRecord(ctx->ev_join, ctx->side);
+  } else {
+    teacher_forward(r, teacher, teacher_cache, x_fp, per_layer_fp, nullptr);
+  }
   prepare_weights(r, params);
   student_forward(r, params, x_q, per_layer_q);
+  if (fork) (void)hipStreamWaitEvent(r.st, ctx->ev_join, 0);
   student_backward(r, params, x_q, per_layer_fp, per_layer_q, grads, loss_out);
   apply_update(r, params, grads, adam_m, adam_v, step_index, lr, grads_out != nullptr);
   return finish(ctx, "mrem_module_step");

@@ -21,6 +21,7 @@ bool g_prof_on = false;
 std::vector<GemmRecord> g_prof;
 }  // namespace
 
+bool gemm_profile_active() { return g_prof_on; }
 void gemm_profile_begin() {
   for (auto& r : g_prof) { hipEventDestroy(r.e0); hipEventDestroy(r.e1); }
   g_prof.clear();

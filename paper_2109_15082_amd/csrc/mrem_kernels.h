@@ -52,6 +52,7 @@ void gemm_nt(int dt, const void* A, int lda, const void* B, int ldb, void* C, in
 
 // Timing of every gemm_nt launch with a pair of HIP events on its stream.
 void gemm_profile_begin();
+bool gemm_profile_active();
 int gemm_profile_end(double* ms, double* flops, int64_t* launches);
 
 // ---- weights ------------------------------------------------------------------
