@@ -274,7 +274,8 @@ void student_forward(const Run& r, const float* params, const void* x_q, void* p
     const void* x = l == 0 ? x_q : (const char*)per_layer_q + slice * (l - 1);
     void* f = (char*)per_layer_q + slice * l;
     // every code tensor that feeds a linear layer is also written as int8 when the int8 products are in use
-    act_quantize(c->dt, x, r.at(w.xcodes), (int64_t)T * H, make_q(c, params, l, 0), r.st, r.at8(w.xcodes8));
+    // (the input codes of layers 1.. come from the second LayerNorm of the layer before)
+    if (l == 0) act_quantize(c->dt, x, r.at(w.xcodes), (int64_t)T * H, make_q(c, params, l, 0), r.st, r.at8(w.xcodes8));
     student_linear(r, params, l, 0, r.at(w.xcodes), r.at8(w.xcodes8), r.at(w.qkv));
     const AttnQ aq = make_attn_q(c, params, l, true);
     qkv_quantize(c->dt, r.at(w.qkv), r.at(w.qkvcodes), T, H, aq.q, aq.k, aq.v, r.st);
@@ -294,8 +295,15 @@ void student_forward(const Run& r, const float* params, const void* x_q, void* p
       gelu_quantize(c->dt, r.at(w.u), r.at(w.gcodes), (int64_t)T * F, qg, r.st, r.at8(w.gcodes8), 0.5f * (qg.qp + 1.f));
     }
     student_linear(r, params, l, 3, r.at(w.gcodes), r.at8(w.gcodes8), r.at(w.y));
-    ln_fwd(c->dt, r.at(w.x1), r.at(w.y), base + c->foff[MREM_F_LN2_G], base + c->foff[MREM_F_LN2_B], f, nullptr, QArg(),
-           r.at<float>(w.mu2), r.at<float>(w.rstd2), T, H, c->cfg.ln_eps, r.st);
+    if (l + 1 < c->L) {
+      // the layer output and, in the same pass, its codes under the next layer's input quantizer
+      const LayerWs& wn = r.p.lw[l + 1];
+      ln_fwd(c->dt, r.at(w.x1), r.at(w.y), base + c->foff[MREM_F_LN2_G], base + c->foff[MREM_F_LN2_B], f, r.at(wn.xcodes),
+             make_q(c, params, l + 1, 0), r.at<float>(w.mu2), r.at<float>(w.rstd2), T, H, c->cfg.ln_eps, r.st, r.at8(wn.xcodes8));
+    } else {
+      ln_fwd(c->dt, r.at(w.x1), r.at(w.y), base + c->foff[MREM_F_LN2_G], base + c->foff[MREM_F_LN2_B], f, nullptr, QArg(),
+             r.at<float>(w.mu2), r.at<float>(w.rstd2), T, H, c->cfg.ln_eps, r.st);
+    }
   }
 }
 
@@ -525,16 +533,13 @@ void apply_update(const Run& r, float* params, float* grads, float* m, float* v,
     }
   }
   adam_matrix(jobs.data(), (int)jobs.size(), c->cfg.w_bits, a, write_grads, r.st);
+  std::vector<VecJob> vjobs;
   for (int l = 0; l < c->L; ++l) {
     const int64_t o = c->layer_stride * l;
-    const int64_t ob = o + c->foff[MREM_F_B_QKV];
-    const int64_t nb = c->foff[MREM_F_SW_QKV] - c->foff[MREM_F_B_QKV];
-    adam_vector(params + ob, grads + ob, m + ob, v + ob, nb, nodecay, 0, r.st);
-    if (c->cfg.a_bits > 0) {
-      const int64_t oa = o + c->foff[MREM_F_S_A];
-      adam_vector(params + oa, grads + oa, m + oa, v + oa, 8, nodecay, 1, r.st);
-    }
+    vjobs.push_back(VecJob{o + c->foff[MREM_F_B_QKV], c->foff[MREM_F_SW_QKV] - c->foff[MREM_F_B_QKV], 0});
+    if (c->cfg.a_bits > 0) vjobs.push_back(VecJob{o + c->foff[MREM_F_S_A], 8, 1});
   }
+  adam_vector(params, grads, m, v, vjobs.data(), (int)vjobs.size(), nodecay, r.st);
 }
 
 mrem_status check_common(const mrem_ctx* ctx, int32_t batch, int32_t seq, const void* workspace, size_t workspace_bytes, const char* who,

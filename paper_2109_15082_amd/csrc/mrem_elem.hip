@@ -996,22 +996,32 @@ void adam_matrix(const AdamJob* jobs, int njobs, int bits, AdamArg a, int write_
   }
 }
 
+struct VecJobTable {
+  VecJob job[kMaxVecJobs];
+};
 __global__ void adam_vector_k(float* __restrict__ p, const float* __restrict__ g, float* __restrict__ m, float* __restrict__ v,
-                              int64_t n, AdamArg a, int clamp) {
-  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+                              VecJobTable tab, AdamArg a) {
+  const VecJob jb = tab.job[blockIdx.y];
+  for (int64_t k = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; k < jb.n; k += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t i = jb.off + k;
     float mm = m[i], vv = v[i];
     float np_ = adam_one(p[i], g[i], mm, vv, a);
-    if (clamp) np_ = fmaxf(np_, a.floor);
+    if (jb.clamp) np_ = fmaxf(np_, a.floor);
     p[i] = np_;
     m[i] = mm;
     v[i] = vv;
   }
 }
-void adam_vector(float* p, const float* g, float* m, float* v, int64_t n, AdamArg a, int clamp, hipStream_t st) {
-  int g_ = (int)((n + 255) / 256);
-  if (g_ > 4096) g_ = 4096;
-  if (g_ < 1) g_ = 1;
-  hipLaunchKernelGGL(adam_vector_k, dim3(g_), dim3(256), 0, st, p, g, m, v, n, a, clamp);
+void adam_vector(float* p, const float* g, float* m, float* v, const VecJob* jobs, int njobs, AdamArg a, hipStream_t st) {
+  for (int j0 = 0; j0 < njobs; j0 += kMaxVecJobs) {
+    VecJobTable tab;
+    const int nj = njobs - j0 < kMaxVecJobs ? njobs - j0 : kMaxVecJobs;
+    int64_t longest = 1;
+    for (int j = 0; j < nj; ++j) { tab.job[j] = jobs[j0 + j]; if (jobs[j0 + j].n > longest) longest = jobs[j0 + j].n; }
+    int gx = (int)((longest + 255) / 256);
+    if (gx > 1024) gx = 1024;
+    hipLaunchKernelGGL(adam_vector_k, dim3(gx, nj), dim3(256), 0, st, p, g, m, v, tab, a);
+  }
 }
 
 }  // namespace mrem

@@ -177,6 +177,15 @@ struct AdamJob {
   int N, K;
 };
 void adam_matrix(const AdamJob* jobs, int njobs, int bits, AdamArg a, int write_grads, hipStream_t st);
-void adam_vector(float* p, const float* g, float* m, float* v, int64_t n, AdamArg a, int clamp, hipStream_t st);
+// AdamW without decay on segments [off, off + n) of the parameter vector (all vectors share one
+// layout); clamp != 0 applies the lower bound a.floor afterwards (step sizes).  One launch per
+// kMaxVecJobs segments.
+constexpr int kMaxVecJobs = 64;
+struct VecJob {
+  int64_t off;
+  int64_t n;
+  int clamp;
+};
+void adam_vector(float* p, const float* g, float* m, float* v, const VecJob* jobs, int njobs, AdamArg a, hipStream_t st);
 
 }  // namespace mrem
