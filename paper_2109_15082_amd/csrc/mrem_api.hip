@@ -119,7 +119,7 @@ struct Plan {
   // teacher scratch
   size_t t_qkv, t_ctx, t_o, t_x1, t_g, t_y, t_mu, t_rstd;
   // backward scratch
-  size_t lg, dr2, dr1, dxh, dx1h, dch, dc, dgh, du, dqkvh, dqkv, s_da, s_ph, partials, partials_per_layer, grads, pmax;
+  size_t dr2, dr1, dxh, dx1h, dch, dc, dgh, du, dqkvh, dqkv, s_da, s_ph, partials, partials_per_layer, grads, pmax;
   size_t total;
 };
 
@@ -155,7 +155,7 @@ Plan make_plan(const mrem_ctx* c, int B, int S) {
   }
   p.t_qkv = b.take(T * 3 * H * es); p.t_ctx = b.take(T * H * es); p.t_o = b.take(T * H * es); p.t_x1 = b.take(T * H * es);
   p.t_g = b.take(T * F * es); p.t_y = b.take(T * H * es); p.t_mu = b.take(T * 4); p.t_rstd = b.take(T * 4);
-  p.lg = b.take(T * H * es); p.dr2 = b.take(T * H * es); p.dr1 = b.take(T * H * es); p.dxh = b.take(T * H * es);
+  p.dr2 = b.take(T * H * es); p.dr1 = b.take(T * H * es); p.dxh = b.take(T * H * es);
   p.dx1h = b.take(T * H * es); p.dch = b.take(T * H * es); p.dc = b.take(T * H * es);
   p.dgh = b.take(T * F * es); p.du = b.take(T * F * es); p.dqkvh = b.take(T * 3 * H * es); p.dqkv = b.take(T * 3 * H * es);
   const size_t widest = (3 * H > F ? 3 * H : F);
@@ -166,7 +166,7 @@ Plan make_plan(const mrem_ctx* c, int B, int S) {
   // first-stage partial sums of one layer's backward pass (all of them stay until the single
   // second-stage launch at the end of the backward pass): two LayerNorms, two bias column sums,
   // the elementwise kernels (at most 2048 blocks, up to 3 values each) and the attention rows
-  size_t np = 2 * (size_t)ln_bwd_parts((int)T) * (3 * H + 1) + (size_t)kColMaxParts * (F + 3 * H) + 8 * 2048 + (size_t)B * c->nh * S;
+  size_t np = 2 * (size_t)ln_bwd_parts((int)T) * (3 * H + 2) + (size_t)kColMaxParts * (F + 3 * H) + 8 * 2048 + (size_t)B * c->nh * S;
   np = (np + 63) & ~size_t(63);
   p.partials_per_layer = np;
   p.partials = b.take(np * 4 * c->L);
@@ -410,28 +410,23 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
     const void* ffp = (const char*)per_layer_fp + slice * l;
     const bool in_loss = (c->cfg.loss_layer_mask >> l) & 1u;
     red.next = r.at<float>(r.p.partials) + r.p.partials_per_layer * l;
-    // Eq. 3 term of this layer and its gradient
-    if (in_loss) {
-      const float scale = c->cfg.loss_mean ? 1.0f / (float)numel : 1.0f;
-      float* parts = red.take(2048);
-      const int n = mse_loss_grad(c->dt, fq, ffp, r.at(r.p.lg), numel, scale, parts, r.st);
-      red.add(parts, n, 1, 0, 1, loss_out + 1 + l, scale);
-    } else {
-      fill_f32(loss_out + 1 + l, 0.f, 1, r.st);
-    }
-    // second LayerNorm: dy = [dr1 + dxh*mask of the layer above] + loss gradient
+    // second LayerNorm: dy = [dr1 + dxh*mask of the layer above] + gradient of this layer's Eq. 3 term,
+    // which the same kernel forms from the two layer outputs (it also returns the squared-error sum)
     {
       const bool top = (l == L - 1);
       const QArg q_above = top ? QArg() : make_q(c, params, l + 1, 0);
-      float* parts = red.take((size_t)ln_bwd_parts(T) * (3 * H + 1));
-      const int n = ln_bwd(c->dt, top ? nullptr : r.at(r.p.dr1), in_loss ? r.at(r.p.lg) : nullptr, top ? nullptr : r.at(r.p.dxh), fq,
-                           q_above, r.at(w.x1), r.at(w.y), r.at<float>(w.mu2), r.at<float>(w.rstd2), base + c->foff[MREM_F_LN2_G],
-                           r.at(r.p.dr2), parts, T, H, r.st);
-      const int wd = 3 * H + 1;
+      const float scale = c->cfg.loss_mean ? 1.0f / (float)numel : 1.0f;
+      const int wd = 3 * H + 2;
+      float* parts = red.take((size_t)ln_bwd_parts(T) * wd);
+      const int n = ln_bwd(c->dt, top ? nullptr : r.at(r.p.dr1), nullptr, top ? nullptr : r.at(r.p.dxh), fq, q_above, r.at(w.x1), r.at(w.y),
+                           r.at<float>(w.mu2), r.at<float>(w.rstd2), base + c->foff[MREM_F_LN2_G], r.at(r.p.dr2), parts, T, H, r.st,
+                           in_loss ? ffp : nullptr, scale);
       red.add(parts, n, wd, 0, H, g + c->foff[MREM_F_LN2_G]);
       red.add(parts, n, wd, H, H, g + c->foff[MREM_F_LN2_B]);
       red.add(parts, n, wd, 2 * H, H, g + c->foff[MREM_F_B_2]);
       if (!top) red.add(parts, n, wd, 3 * H, 1, grads + c->layer_stride * (l + 1) + c->foff[MREM_F_S_A] + 0);
+      // a layer outside the loss mask contributes an exact zero (its partial sums are zero)
+      red.add(parts, n, wd, 3 * H + 1, 1, loss_out + 1 + l, in_loss ? scale : 0.f);
     }
     // second feed-forward projection
     wgrad(r, params, grads, l, 3, r.at(r.p.dr2), r.at(w.gcodes));
@@ -450,10 +445,10 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
     dgrad(r, l, 2, r.at(r.p.du), r.at(r.p.dx1h));
     // first LayerNorm: dy = dr2 (residual) + dx1h through the FFN-input quantizer
     {
-      float* parts = red.take((size_t)ln_bwd_parts(T) * (3 * H + 1));
+      float* parts = red.take((size_t)ln_bwd_parts(T) * (3 * H + 2));
       const int n = ln_bwd(c->dt, r.at(r.p.dr2), nullptr, r.at(r.p.dx1h), r.at(w.x1), make_q(c, params, l, 6), x, r.at(w.o),
                            r.at<float>(w.mu1), r.at<float>(w.rstd1), base + c->foff[MREM_F_LN1_G], r.at(r.p.dr1), parts, T, H, r.st);
-      const int wd = 3 * H + 1;
+      const int wd = 3 * H + 2;
       red.add(parts, n, wd, 0, H, g + c->foff[MREM_F_LN1_G]);
       red.add(parts, n, wd, H, H, g + c->foff[MREM_F_LN1_B]);
       red.add(parts, n, wd, 2 * H, H, g + c->foff[MREM_F_B_O]);

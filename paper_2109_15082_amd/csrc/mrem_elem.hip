@@ -1,7 +1,7 @@
 // Bandwidth-bound kernels of the MREM module step: quantizers (Section 3.1, Eq. 1,
 // with the straight-through backward of Section 3.1.1), residual + LayerNorm,
-// GELU, the per-layer squared-error term of Eq. 3, calibration reductions and the
-// AdamW update.
+// GELU, the per-layer squared-error term of Eq. 3 (inside the backward kernel of the
+// second LayerNorm), calibration reductions and the AdamW update.
 #include "mrem_common.h"
 #include "mrem_kernels.h"
 
@@ -451,8 +451,8 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict
                                                              const T* __restrict__ a_q, QArg qa, const T* __restrict__ x, const T* __restrict__ r,
                                                              const float* __restrict__ mu, const float* __restrict__ rstd_in,
                                                              const float* __restrict__ gamma, T* __restrict__ dr, float* __restrict__ partials,
-                                                             int T_, int H) {
-  extern __shared__ float red[];  // [kLnBwdWaves/2][3*H] + kLnBwdWaves
+                                                             int T_, int H, const T* __restrict__ loss_ref, float loss_scale) {
+  extern __shared__ float red[];  // [kLnBwdWaves/2][3*H] + 2 * kLnBwdWaves
   constexpr int HALF = kLnBwdWaves / 2;
   const QuantParam q = load_q(qa);
   const int lane = threadIdx.x & 63, wave = threadIdx.x / 64;
@@ -464,7 +464,7 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict
     for (int j = 0; j < 8; ++j) acc_g[i][j] = acc_b[i][j] = acc_d[i][j] = gam[i][j] = 0.f;
     if (lane + 64 * i < nch) load8(gamma + (lane + 64 * i) * 8, gam[i]);
   }
-  float ds_acc = 0.f;
+  float ds_acc = 0.f, loss_acc = 0.f;
 
   constexpr int INF = NCH * sizeof(T) <= 4 ? 2 : 1;  // rows in flight: two when their loaded values fit the registers
   const int row_base = blockIdx.x * kLnBwdRows + wave * kLnBwdRowsPerWave;
@@ -485,11 +485,10 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict
         if (live && c < nch) {
           const size_t off = (size_t)row * H + c * 8;
           if (d_a) t_a[k][i].load(d_a + off);
-          if (d_b) t_b[k][i].load(d_b + off);
-          if (d_q) {
-            t_q[k][i].load(d_q + off);
-            if (q.on) t_v[k][i].load(a_q + off);
-          }
+          if (loss_ref) t_b[k][i].load(loss_ref + off);
+          else if (d_b) t_b[k][i].load(d_b + off);
+          if (d_q) t_q[k][i].load(d_q + off);
+          if ((d_q && q.on) || loss_ref) t_v[k][i].load(a_q + off);
           t_x[k][i].load(x + off);
           t_r[k][i].load(r + off);
         }
@@ -508,7 +507,14 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict
           for (int j = 0; j < 8; ++j) {
             float d = 0.f;
             if (d_a) d += t_a[k][i].get(j);
-            if (d_b) d += t_b[k][i].get(j);
+            if (loss_ref) {
+              // Eq. 3 term of this layer: a_q holds the quantized module's output, loss_ref the full-precision one
+              const float diff = t_v[k][i].get(j) - t_b[k][i].get(j);
+              loss_acc += diff * diff;
+              d += 2.0f * diff * loss_scale;
+            } else if (d_b) {
+              d += t_b[k][i].get(j);
+            }
             if (d_q) {
               float t = t_q[k][i].get(j);
               if (q.on) {
@@ -549,9 +555,10 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict
   // the wavefronts meet in LDS: the upper half adds onto the lower half, whose sum in wavefront
   // order is the block's partial row
   ds_acc = wave_sum(ds_acc);
+  loss_acc = wave_sum(loss_acc);
   float* mine = red + (size_t)(wave % HALF) * 3 * H;
   float* dsv = red + (size_t)HALF * 3 * H;
-  if (lane == 0) dsv[wave] = ds_acc;
+  if (lane == 0) { dsv[wave] = ds_acc; dsv[kLnBwdWaves + wave] = loss_acc; }
   if (wave >= HALF) {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
@@ -586,7 +593,7 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict
     }
   }
   __syncthreads();
-  const int width = 3 * H + 1;
+  const int width = 3 * H + 2;
   float* out = partials + (size_t)blockIdx.x * width;
   for (int c = threadIdx.x; c < 3 * H; c += blockDim.x) {
     float t = red[c];
@@ -595,54 +602,27 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict
     out[c] = t;
   }
   if (threadIdx.x == 0) {
-    float t = 0.f;
-    for (int w = 0; w < kLnBwdWaves; ++w) t += dsv[w];
+    float t = 0.f, tl = 0.f;
+    for (int w = 0; w < kLnBwdWaves; ++w) { t += dsv[w]; tl += dsv[kLnBwdWaves + w]; }
     out[3 * H] = t;
+    out[3 * H + 1] = tl;
   }
 }
 int ln_bwd(int dt, const void* d_a, const void* d_b, const void* d_q, const void* a_q, QArg q, const void* x, const void* r,
-           const float* mu, const float* rstd, const float* gamma, void* dr, float* partials, int T_, int H, hipStream_t st) {
+           const float* mu, const float* rstd, const float* gamma, void* dr, float* partials, int T_, int H, hipStream_t st,
+           const void* loss_ref, float loss_scale) {
   const int g = ln_bwd_parts(T_);
-  const size_t lds = ((size_t)(kLnBwdWaves / 2) * 3 * H + kLnBwdWaves) * sizeof(float);
+  const size_t lds = ((size_t)(kLnBwdWaves / 2) * 3 * H + 2 * kLnBwdWaves) * sizeof(float);
 #define MREM_LN_BWD(NCH)                                                                                                        \
   MREM_DISPATCH(dt, if (lds > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ln_bwd_k<T, NCH>),                   \
                                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);            \
                     hipLaunchKernelGGL((ln_bwd_k<T, NCH>), dim3(g), dim3(64 * kLnBwdWaves), lds, st, (const T*)d_a, (const T*)d_b, \
-                                       (const T*)d_q, (const T*)a_q, q, (const T*)x, (const T*)r, mu, rstd, gamma, (T*)dr, partials, T_, H))
+                                       (const T*)d_q, (const T*)a_q, q, (const T*)x, (const T*)r, mu, rstd, gamma, (T*)dr, partials, T_, H, \
+                                       (const T*)loss_ref, loss_scale))
   if (H <= 512) MREM_LN_BWD(1);
   else if (H <= 1024) MREM_LN_BWD(2);
   else MREM_LN_BWD(4);
 #undef MREM_LN_BWD
-  return g;
-}
-
-// ------------------------------------------------------------------------------
-// squared-error term of Eq. 3 for one layer and its gradient
-// ------------------------------------------------------------------------------
-template <class T>
-__global__ void mse_k(const T* __restrict__ fq, const T* __restrict__ ffp, T* __restrict__ grad, int64_t nchunks, float scale,
-                      float* __restrict__ partials) {
-  __shared__ float red[17];
-  float acc = 0.f;
-  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
-    float a[8], b[8];
-    load8(fq + c * 8, a);
-    load8(ffp + c * 8, b);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const float d = a[j] - b[j];
-      acc += d * d;
-      a[j] = 2.0f * d * scale;
-    }
-    store8(grad + c * 8, a);
-  }
-  const float t = block_sum(acc, red);
-  if (threadIdx.x == 0) partials[blockIdx.x] = t;
-}
-int mse_loss_grad(int dt, const void* fq, const void* ffp, void* grad, int64_t n, float scale, float* partials, hipStream_t st) {
-  const int g = ew_grid(n);
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(mse_k<T>, dim3(g), dim3(256), 0, st, (const T*)fq, (const T*)ffp, (T*)grad, n / 8, scale,
-                                       partials));
   return g;
 }
 
