@@ -1,0 +1,150 @@
+"""Module schedules around the MREM step: sequential training of the modules (Section 4.1) and
+parallel training with input queues (Section 4.2, Algorithm 1) on one GPU.
+
+Host-side orchestration only: every tensor operation is a call into the C library
+(`mrem_module_step`, `mrem_module_forward`, `mrem_mix_inputs`) or a plain device-to-device copy
+into a queue slot.  In the parallel schedule each module has its own HIP stream (default
+priority), context, parameters and workspace, so the kernels of different modules overlap on the
+device the way they would on separate devices; a step ends with an event barrier between the
+streams, which is the one message per step that neighbouring devices would exchange.
+
+Queue layout: for the outputs of module n a ring of t0 + 1 slots of [batch, seq, hidden] for the
+full-precision half and the same for the quantized half, plus the sequence lengths of each slot.
+t0 slots are readable (the most recent t0 steps, first in first out); the extra slot is the one
+being written during a step, so a module that samples the oldest entry never reads a slot while
+its predecessor overwrites it.  Which entry a module samples is an argument (`slots[t][n]`, an
+age: 0 = newest), drawn by the caller.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+
+def linear_decay_lr(lr0: float, t: int, total: int) -> float:
+    """Section 5.1.2: linearly decayed rate, t = 0 .. total-1."""
+    return lr0 * (1.0 - t / float(total))
+
+
+def teacher_forcing_lambda(t: int, tf_steps: int) -> float:
+    """Section 4.2.1: lambda_t = max(1 - t/T0, 0); 0 when teacher forcing is off."""
+    return max(1.0 - t / float(tf_steps), 0.0) if tf_steps > 0 else 0.0
+
+
+class _Queue:
+    def __init__(self, depth: int, batch: int, seq: int, hidden: int, dtype, with_lengths: bool):
+        self.depth = depth                      # readable entries
+        self.fp = torch.empty((depth + 1, batch, seq, hidden), dtype=dtype, device="cuda")
+        self.q = torch.empty_like(self.fp)
+        self.lengths = torch.empty((depth + 1, batch), dtype=torch.int32, device="cuda") if with_lengths else None
+        self.pushed = 0                         # entries published so far
+
+    def write_slot(self) -> int:
+        return self.pushed % (self.depth + 1)
+
+    def slot_of_age(self, age: int) -> int:
+        if not 0 <= age < min(self.pushed, self.depth):
+            raise ValueError(f"queue holds {min(self.pushed, self.depth)} entries, age {age} asked")
+        return (self.pushed - 1 - age) % (self.depth + 1)
+
+
+class ModulePipeline:
+    """N consecutive modules (binding.MremModule, already loaded, initialised and calibrated)."""
+
+    def __init__(self, modules: Sequence[B.MremModule], batch: int, seq: int, with_lengths: bool = False):
+        self.modules = list(modules)
+        self.batch, self.seq = batch, seq
+        self.with_lengths = with_lengths
+        m0 = self.modules[0]
+        self.hidden, self.dtype = m0.hidden, m0.tdtype
+        self.outs = [m.new_outputs(batch, seq) for m in self.modules]
+        self.mixed = [torch.empty((batch, seq, self.hidden), dtype=self.dtype, device="cuda") for _ in self.modules]
+        self.streams = [torch.cuda.Stream() for _ in self.modules]
+
+    # -- one module, one step, on the current stream ---------------------------------------
+    def _step(self, n: int, x_fp, x_q, lengths, lr: float, lam: float, queue: Optional[_Queue], loss_row):
+        mod = self.modules[n]
+        x_in = x_q
+        if n > 0 and lam > 0.0:
+            B.mrem_mix_inputs(mod.ctx, x_fp, x_q, lam, self.mixed[n], x_fp.numel())
+            x_in = self.mixed[n]
+        out_fp, out_q = self.outs[n]
+        mod.step(x_fp, x_in, lr, lengths, out_fp, out_q)
+        loss_row[n].copy_(mod.loss[0], non_blocking=True)
+        if queue is not None:
+            w = queue.write_slot()
+            queue.fp[w].copy_(out_fp[-1], non_blocking=True)
+            queue.q[w].copy_(out_q[-1], non_blocking=True)
+            if queue.lengths is not None:
+                queue.lengths[w].copy_(lengths, non_blocking=True)
+
+    def run_parallel(self, data: Sequence[torch.Tensor], lengths: Sequence[Optional[torch.Tensor]], slots, t0: int, total_steps: int,
+                     lr0: float, tf_steps: int, concurrent: bool = True) -> torch.Tensor:
+        """Algorithm 1.  data[t]: [batch, seq, hidden] device tensor entering the first module at step t;
+        slots[t][n]: age of the entry module n reads at step t >= t0.  Returns losses [total_steps, N] (host)."""
+        N = len(self.modules)
+        queues = [_Queue(t0, self.batch, self.seq, self.hidden, self.dtype, self.with_lengths) for _ in range(N)]
+        losses = torch.zeros((total_steps, N), dtype=torch.float32, device="cuda")
+        main = torch.cuda.current_stream()
+        for t in range(total_steps):
+            lr = linear_decay_lr(lr0, t, total_steps)
+            lam = teacher_forcing_lambda(t, tf_steps)
+            if t < t0:
+                # fill phase: one after another on the caller's stream
+                x_fp = x_q = data[t]
+                sl = lengths[t]
+                for n in range(N):
+                    self._step(n, x_fp, x_q, sl, lr, lam, queues[n], losses[t])
+                    w = queues[n].write_slot()
+                    queues[n].pushed += 1
+                    x_fp, x_q = queues[n].fp[w], queues[n].q[w]
+                continue
+            # every module reads the queues as they were after step t-1
+            start = torch.cuda.Event()
+            start.record(main)
+            done = []
+            for n in range(N):
+                if n == 0:
+                    x_fp = x_q = data[t]
+                    sl = lengths[t]
+                else:
+                    src = queues[n - 1]
+                    k = src.slot_of_age(int(slots[t][n]))
+                    x_fp, x_q = src.fp[k], src.q[k]
+                    sl = src.lengths[k] if src.lengths is not None else None
+                stream = self.streams[n] if concurrent else main
+                with torch.cuda.stream(stream):
+                    stream.wait_event(start)
+                    self._step(n, x_fp, x_q, sl, lr, lam, queues[n], losses[t])
+                    ev = torch.cuda.Event()
+                    ev.record(stream)
+                    done.append(ev)
+            for ev in done:            # the barrier that ends the step
+                main.wait_event(ev)
+            for qn in queues:          # publish: first in, first out
+                qn.pushed += 1
+        torch.cuda.synchronize()
+        return losses.cpu()
+
+    def run_sequential(self, data: Sequence[torch.Tensor], lengths: Sequence[Optional[torch.Tensor]], steps_per_module: int, lr0: float):
+        """Section 4.1: module n is trained on the outputs of the finished modules 1..n-1.  Returns
+        (losses [N, steps_per_module] on the host, final full-precision chain outputs, final quantized chain outputs)."""
+        N = len(self.modules)
+        losses = torch.zeros((N, steps_per_module), dtype=torch.float32, device="cuda")
+        fp_in = list(data)
+        q_in = list(data)
+        for n, mod in enumerate(self.modules):
+            for t in range(steps_per_module):
+                k = t % len(data)
+                self._step(n, fp_in[k], q_in[k], lengths[k], linear_decay_lr(lr0, t, steps_per_module), 0.0, None, losses[:, t])
+            nxt_fp, nxt_q = [], []
+            for k in range(len(data)):
+                o_fp, o_q = mod.forward(fp_in[k], q_in[k], lengths[k])
+                nxt_fp.append(o_fp[-1].clone())
+                nxt_q.append(o_q[-1].clone())
+            fp_in, q_in = nxt_fp, nxt_q
+        torch.cuda.synchronize()
+        return losses.cpu(), fp_in, q_in

@@ -106,3 +106,35 @@ def make_case_with_margin(wl: synth.Workload, min_margin: float, max_tries: int 
         if forward_margin(case) >= min_margin:
             return case
     raise RuntimeError(f"no seed with margin {min_margin} in {max_tries} tries")
+
+
+# ---------------------------------------------------------------------------------
+# several consecutive modules (schedules of Section 4.1 / 4.2)
+# ---------------------------------------------------------------------------------
+
+def make_chain(wl: synth.Workload, n_modules: int, n_batches: int, **cfg_kw):
+    """n_modules seeded modules (module n: weight seed 1234 + n) and n_batches input batches
+    (input seed 5678 + t).  Every module's clip ranges are calibrated by the oracle on the
+    full-precision chain's activations of batch 0, as a calibration pass through the modules
+    in order would do.  Returns (cases, batches [n_batches][B,S,H] fp32, seqlens list)."""
+    cases, batches, lens = [], [], []
+    for t in range(n_batches):
+        _, x, sl = synth.make_workload_inputs(wl, 1234, 5678 + t, 0.05)
+        batches.append(x)
+        lens.append(sl)
+    x_cal = batches[0].reshape(-1, wl.hidden).astype(np.float64)
+    for n in range(n_modules):
+        case = make_case(wl, weight_seed=1234 + n, **cfg_kw)
+        cal = O.calibrate(x_cal, case.teacher, case.cfg, wl.batch, wl.seq, lens[0])
+        for lp, (s, z) in zip(case.student, cal):
+            lp["s_a"], lp["z_a"] = s.copy(), z.copy()
+        f_fp, _ = O.module_forward(x_cal, case.teacher, case.cfg, wl.batch, wl.seq, lens[0], quant=False)
+        x_cal = f_fp[-1]
+        cases.append(case)
+    return cases, batches, lens
+
+
+def draw_slots(total_steps: int, n_modules: int, t0: int, seed: int = 4321):
+    """slots[t][n]: age (0 = newest) of the queue entry module n reads at step t."""
+    rng = np.random.default_rng(seed)
+    return rng.integers(0, t0, size=(total_steps, n_modules)).tolist()

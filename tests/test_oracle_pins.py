@@ -600,3 +600,98 @@ def test_loss_ordering_and_descent():
     for k in O.TRAINABLE_FIELDS:
         assert not np.array_equal(student[0][k], before[k]), k       # weights and every step size moved
     assert all(np.all(lp[k] > 0) for lp in student for k in O.STEP_NAMES + ("s_a",))
+
+
+# ---------------------------------------------------------------------------------
+# schedules around the step (Section 4.1, Section 4.2 / Algorithm 1): the pipeline oracle
+# ---------------------------------------------------------------------------------
+import helpers as Hh  # noqa: E402  (tests/ is on sys.path through conftest)
+
+def _chain_states(cases):
+    from oracle import mrem_pipeline as P
+    import copy
+    states = []
+    for c in cases:
+        m, v = Hh.fresh_moments(c.student)
+        states.append(P.ModuleState(copy.deepcopy(c.teacher), copy.deepcopy(c.student), m, v, c.cfg))
+    return states
+
+
+PIPE_WL = synth.Workload("pipe_tiny", 1, 32, 2, 64, 8, 2, act_dtype="f32")
+
+
+def test_pipeline_single_module_is_repeated_steps():
+    """One module: Algorithm 1 degenerates to Algorithm 2 applied to the data stream."""
+    import copy
+    from oracle import mrem_pipeline as P
+    cases, batches, lens = Hh.make_chain(PIPE_WL, 1, 4)
+    data = [b.reshape(-1, PIPE_WL.hidden).astype(np.float64) for b in batches]
+    tr = P.run_parallel(_chain_states(cases), data, lens, Hh.draw_slots(4, 1, 2), 2, 4, 1e-3, 2, PIPE_WL.batch, PIPE_WL.seq)
+    c = cases[0]
+    student = copy.deepcopy(c.student)
+    m, v = Hh.fresh_moments(student)
+    for t in range(4):
+        res = O.module_step(data[t], data[t], c.teacher, student, m, v, t + 1, O.linear_decay_lr(1e-3, t, 4), c.cfg,
+                            PIPE_WL.batch, PIPE_WL.seq, lens[t])
+        assert tr.loss[t][0] == res.loss
+        assert tr.read_age[t] == [-1]
+
+
+def test_pipeline_queue_semantics_by_hand():
+    """Two modules, queue depth 2, 5 steps, written out by hand: fill phase chained within the
+    step; afterwards module 2 reads the entry of the stated age from the queue as it stood after
+    the previous step, mixes its two halves with lambda_t (Eq. 4) and the queue drops its oldest entry."""
+    import copy
+    from oracle import mrem_pipeline as P
+    T, t0, tf = 5, 2, 4
+    cases, batches, lens = Hh.make_chain(PIPE_WL, 2, T)
+    data = [b.reshape(-1, PIPE_WL.hidden).astype(np.float64) for b in batches]
+    slots = [[0, 0], [0, 0], [0, 1], [0, 0], [0, 1]]
+    tr = P.run_parallel(_chain_states(cases), data, lens, slots, t0, T, 1e-3, tf, PIPE_WL.batch, PIPE_WL.seq)
+    st = [copy.deepcopy(c.student) for c in cases]
+    mv = [Hh.fresh_moments(s) for s in st]
+    B_, S_ = PIPE_WL.batch, PIPE_WL.seq
+    history = []   # outputs of module 1 per step: (f, f^)
+    for t in range(T):
+        lr = 1e-3 * (1 - t / T)
+        lam = max(1 - t / tf, 0.0)
+        r1 = O.module_step(data[t], data[t], cases[0].teacher, st[0], mv[0][0], mv[0][1], t + 1, lr, cases[0].cfg, B_, S_, lens[t])
+        if t < t0:
+            src = (r1.f_fp[-1], r1.f_q[-1])          # just produced
+        else:
+            src = history[t - 1 - slots[t][1]]      # age 0 = step t-1, age 1 = step t-2
+        x_in = lam * src[0] + (1 - lam) * src[1]
+        r2 = O.module_step(src[0], x_in, cases[1].teacher, st[1], mv[1][0], mv[1][1], t + 1, lr, cases[1].cfg, B_, S_, lens[t])
+        history.append((r1.f_fp[-1], r1.f_q[-1]))
+        assert tr.loss[t][0] == r1.loss
+        np.testing.assert_allclose(tr.loss[t][1], r2.loss, rtol=1e-12)
+    # teacher forcing matters: with lambda = 0 throughout, module 2 sees other inputs and other losses
+    tr0 = P.run_parallel(_chain_states(cases), data, lens, slots, t0, T, 1e-3, 0, B_, S_)
+    assert tr0.loss[0][0] == tr.loss[0][0]
+    assert tr0.loss[0][1] != tr.loss[0][1]
+
+
+def test_pipeline_sequential_feeds_finished_chains():
+    """Section 4.1: the second module is trained on the outputs of the finished first module
+    (teacher chain into the teacher, quantized chain into the quantized copy)."""
+    import copy
+    from oracle import mrem_pipeline as P
+    cases, batches, lens = Hh.make_chain(PIPE_WL, 2, 2)
+    data = [b.reshape(-1, PIPE_WL.hidden).astype(np.float64) for b in batches]
+    states = _chain_states(cases)
+    tr = P.run_sequential(states, data, lens, 3, 1e-3, PIPE_WL.batch, PIPE_WL.seq)
+    B_, S_ = PIPE_WL.batch, PIPE_WL.seq
+    # module 1 alone
+    st = copy.deepcopy(cases[0].student)
+    m, v = Hh.fresh_moments(st)
+    for t in range(3):
+        res = O.module_step(data[t % 2], data[t % 2], cases[0].teacher, st, m, v, t + 1, 1e-3 * (1 - t / 3), cases[0].cfg, B_, S_, lens[t % 2])
+        assert tr.loss[0][t] == res.loss
+    f_fp, _ = O.module_forward(data[0], cases[0].teacher, cases[0].cfg, B_, S_, lens[0], quant=False)
+    f_q, _ = O.module_forward(data[0], st, cases[0].cfg, B_, S_, lens[0], quant=True)
+    st2 = copy.deepcopy(cases[1].student)
+    m2, v2 = Hh.fresh_moments(st2)
+    res = O.module_step(f_fp[-1], f_q[-1], cases[1].teacher, st2, m2, v2, 1, 1e-3, cases[1].cfg, B_, S_, lens[0])
+    assert tr.loss[1][0] == res.loss
+    # the quantized chain differs from the full-precision chain
+    assert not np.array_equal(f_fp[-1], f_q[-1])
