@@ -18,6 +18,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+MFMA_INT8_PEAK_TOPS = 5000.0
 # HBM bytes per matrix-product launch (read + written), from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE), each scaled by what the counter reads for a 256 MiB device copy; summary with the commands in
 # profiles/module_step_bert_large_6l_hbm_traffic.md.  Only for the workload it was measured on.
@@ -131,7 +132,7 @@ def main():
         t += 1
     torch.cuda.synchronize()
     dt_events = time.perf_counter() - t1
-    gemm_ms, gemm_flops, gemm_launches = B.mrem_profile_gemm_end()
+    (gemm_ms, gemm_flops, gemm_launches), (i8_ms, i8_ops, i8_launches) = B.mrem_profile_gemm_end()
     losses = mod.loss.cpu().numpy()
     assert np.isfinite(losses).all(), losses
 
@@ -139,6 +140,8 @@ def main():
     tokens_per_s = wl.tokens * args.steps / dt
     flops_total, flops_linear = step_flops(wl)
     achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    i8_achieved = i8_ops / (i8_ms * 1e-3) / 1e12 if i8_ms > 0 else 0.0
+    all_ms, all_flops, all_launches = gemm_ms + i8_ms, gemm_flops + i8_ops, gemm_launches + i8_launches
     result = {
         "metric": "module fwd+bwd tokens/s at BERT-large W4A8",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -147,13 +150,21 @@ def main():
         "config": {"workload": wl.name, "n_layers": wl.n_layers, "hidden": wl.hidden, "n_heads": wl.n_heads, "ffn": wl.ffn,
                    "seq_len": wl.seq, "batch": wl.batch, "w_bits": wl.w_bits, "a_bits": wl.a_bits,
                    "tokens_per_step": wl.tokens, "step_tflop": flops_total / 1e12, "loss_last_step": float(losses[0])},
-        "roofline": {"bound": "mfma", "kernel": "gemm_nt (all matrix products of the linear layers)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_k / gemm_nt_pc_k on bf16 operands (teacher forward, input and weight gradients)",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(wl.name),
                      "traffic_unit": "bytes/launch",
                      "launches_per_step": gemm_launches / args.steps,
                      "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
                      "gemm_ms_per_step": gemm_ms / args.steps,
+                     # the products of the quantized forward pass run on int8 codes and are priced against the int8 peak
+                     "int8_products": {"achieved": i8_achieved, "peak": MFMA_INT8_PEAK_TOPS, "unit": "TOP/s",
+                                       "frac": i8_achieved / MFMA_INT8_PEAK_TOPS, "launches_per_step": i8_launches / args.steps,
+                                       "ms_per_step": i8_ms / args.steps},
+                     # every product of the step against the bf16 peak
+                     "all_products": {"achieved": all_flops / (all_ms * 1e-3) / 1e12 if all_ms > 0 else 0.0, "peak": MFMA_BF16_PEAK_TFLOPS,
+                                      "unit": "TFLOP/s", "frac": (all_flops / (all_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS) if all_ms > 0 else 0.0,
+                                      "launches_per_step": all_launches / args.steps, "ms_per_step": all_ms / args.steps},
                      "measured_on": "a second pass of the same K steps with an event pair around every product launch",
                      "ms_per_step_with_events": dt_events * 1e3 / args.steps,
                      "flops_per_launch": gemm_flops / max(gemm_launches, 1)},

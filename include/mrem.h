@@ -208,12 +208,15 @@ mrem_status mrem_mix_inputs(mrem_ctx* ctx, const void* x_fp, const void* x_q, fl
 /*
  * Measurement aid (not part of the method): between mrem_profile_gemm_begin() and
  * mrem_profile_gemm_end() every matrix-product kernel launch of this process is
- * bracketed by a pair of HIP events on its stream.  _end waits for them and returns
- * the summed kernel time in milliseconds (host double), the summed 2*M*N*K of those
- * launches and their number.  Not thread-safe; events are host-side objects.
+ * bracketed by a pair of HIP events on its stream, and mrem_module_step keeps the
+ * full-precision forward pass on the caller's stream so that every product runs
+ * alone.  _end waits for the events and returns, for products on bf16 operands in
+ * element [0] and for products on int8 operands in element [1] of each host array:
+ * the summed kernel time in milliseconds, the summed 2*M*N*K of those launches and
+ * their number.  Not thread-safe; events are host-side objects.
  */
 void mrem_profile_gemm_begin(void);
-mrem_status mrem_profile_gemm_end(double* ms /*host*/, double* flops /*host*/, int64_t* launches /*host*/);
+mrem_status mrem_profile_gemm_end(double ms[2] /*host*/, double flops[2] /*host*/, int64_t launches[2] /*host*/);
 
 #ifdef __cplusplus
 }

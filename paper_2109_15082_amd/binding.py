@@ -197,10 +197,10 @@ def mrem_profile_gemm_begin() -> None:
 
 
 def mrem_profile_gemm_end():
-    """(milliseconds, flops, launches) of the matrix-product kernels since _begin."""
-    ms, fl, n = C.c_double(), C.c_double(), _i64()
-    _check(_lib.mrem_profile_gemm_end(C.byref(ms), C.byref(fl), C.byref(n)))
-    return ms.value, fl.value, n.value
+    """((ms, flops, launches) of the products on bf16 operands, the same for int8 operands) since _begin."""
+    ms, fl, n = (C.c_double * 2)(), (C.c_double * 2)(), (_i64 * 2)()
+    _check(_lib.mrem_profile_gemm_end(ms, fl, n))
+    return (ms[0], fl[0], n[0]), (ms[1], fl[1], n[1])
 
 
 # ------------------------------------------------------------------------------

@@ -16,6 +16,7 @@ namespace {
 struct GemmRecord {
   hipEvent_t e0, e1;
   double flops;
+  int cls = 0;  // 0: bf16 (or fp32) operands, 1: int8 operands
 };
 bool g_prof_on = false;
 std::vector<GemmRecord> g_prof;
@@ -27,21 +28,20 @@ void gemm_profile_begin() {
   g_prof.clear();
   g_prof_on = true;
 }
-int gemm_profile_end(double* ms, double* flops, int64_t* launches) {
+int gemm_profile_end(double ms[2], double flops[2], int64_t launches[2]) {
   g_prof_on = false;
-  double t = 0.0, f = 0.0;
+  ms[0] = ms[1] = flops[0] = flops[1] = 0.0;
+  launches[0] = launches[1] = 0;
   int rc = 0;
   for (auto& r : g_prof) {
     float e = 0.f;
     if (hipEventSynchronize(r.e1) != hipSuccess || hipEventElapsedTime(&e, r.e0, r.e1) != hipSuccess) rc = -1;
-    t += e;
-    f += r.flops;
+    ms[r.cls] += e;
+    flops[r.cls] += r.flops;
+    launches[r.cls] += 1;
     hipEventDestroy(r.e0);
     hipEventDestroy(r.e1);
   }
-  *ms = t;
-  *flops = f;
-  *launches = (int64_t)g_prof.size();
   g_prof.clear();
   return rc;
 }
@@ -598,6 +598,7 @@ void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, i
   hipEventRecord(r.e0, st);
   gemm_i8_launch(A, lda, B, ldb, C, ldc, M, N, K, e, st);
   hipEventRecord(r.e1, st);
+  r.cls = 1;
   g_prof.push_back(r);
 }
 

@@ -53,7 +53,7 @@ void gemm_nt(int dt, const void* A, int lda, const void* B, int ldb, void* C, in
 // Timing of every gemm_nt launch with a pair of HIP events on its stream.
 void gemm_profile_begin();
 bool gemm_profile_active();
-int gemm_profile_end(double* ms, double* flops, int64_t* launches);
+int gemm_profile_end(double ms[2], double flops[2], int64_t launches[2]);  // [0] bf16 operands, [1] int8 operands
 
 // ---- weights ------------------------------------------------------------------
 void weight_quantize_i8(const float* w, float* scale, int8_t* codes, int64_t N, int64_t K, int bits, int init_scale,
