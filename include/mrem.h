@@ -72,6 +72,9 @@ typedef struct {
   float ln_eps;      /* LayerNorm epsilon (BERT: 1e-12) */
   float beta1, beta2, adam_eps, weight_decay; /* AdamW; decay applies to the four linear weights only */
   float step_floor;  /* step sizes are kept >= this after every update */
+  int32_t per_channel; /* 1: one weight step per output channel; 0: one per weight matrix (Section 3.1's
+                          default granularity): the step fields keep their [out_features] layout, all entries
+                          of a matrix hold the same value and receive the same gradient (the sum over rows) */
 } mrem_config;
 
 /* Fields of one layer inside the flat fp32 parameter vector, in storage order;

@@ -101,6 +101,8 @@ class Config:
     adam_eps: float = 1e-8
     weight_decay: float = 0.01  # on the four linear weights only
     step_floor: float = 1e-8
+    per_channel: bool = True   # False: one step per weight matrix (Section 3.1's default granularity),
+                               # kept as a vector of equal entries whose gradient is the sum over rows
 
     @property
     def head_dim(self) -> int:
@@ -210,10 +212,13 @@ def decision_margin(v, qn: int, qp: int, nonnegative: bool = False) -> float:
     return float(min(tie.min(), edge.min()))
 
 
-def weight_step_init(w, bits: int) -> np.ndarray:
-    """Per-output-channel initial step max_k |w[n,k]| / Qp, one fp32 division."""
+def weight_step_init(w, bits: int, per_channel: bool = True) -> np.ndarray:
+    """Initial step max |w| / Qp, one fp32 division: per output channel (row), or over the
+    whole matrix (then every entry of the returned vector holds that one value)."""
     _, qp = sym_range(bits)
     a = np.abs(np.asarray(w, dtype=np.float32)).max(axis=1).astype(np.float64)
+    if not per_channel:
+        a = np.full_like(a, a.max())
     return (a / float(qp)).astype(np.float32).astype(np.float64)
 
 
@@ -332,6 +337,7 @@ class _AQ:
 class _WQ:
     def __init__(self, cfg: Config, w, s_w, enabled: bool):
         self.enabled = enabled and cfg.w_bits > 0
+        self.per_channel = cfg.per_channel
         self.w = w
         if self.enabled:
             self.codes, self.w_hat, self.v, self.inside = quantize_weight(w, s_w, cfg.w_bits)
@@ -341,7 +347,11 @@ class _WQ:
     def bwd(self, d_what):
         if not self.enabled:
             return d_what, np.zeros(self.w.shape[0])
-        return fake_quant_backward(d_what, self.codes, self.v, self.inside, reduce_axes=1)
+        dw, ds = fake_quant_backward(d_what, self.codes, self.v, self.inside, reduce_axes=1)
+        if not self.per_channel:
+            # one step for the whole matrix: its derivative is the sum over the rows
+            ds = np.full_like(ds, ds.sum())
+        return dw, ds
 
 
 def layer_forward(x, lp, cfg: Config, batch: int, seq: int, seqlens=None, quant: bool = True):

@@ -38,7 +38,7 @@ class mrem_config(C.Structure):
                 ("max_seq", C.c_int32), ("max_batch", C.c_int32), ("w_bits", C.c_int32), ("a_bits", C.c_int32),
                 ("act_dtype", C.c_int32), ("loss_layer_mask", C.c_uint32), ("loss_mean", C.c_int32),
                 ("ln_eps", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("adam_eps", C.c_float),
-                ("weight_decay", C.c_float), ("step_floor", C.c_float)]
+                ("weight_decay", C.c_float), ("step_floor", C.c_float), ("per_channel", C.c_int32)]
 
 
 _vp, _i32, _i64, _f32, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
@@ -117,7 +117,7 @@ def mrem_last_error(ctx=None) -> str:
 def mrem_create(**kw) -> int:
     """Returns an opaque context handle.  Keyword arguments are the fields of mrem_config."""
     cfg = mrem_config(loss_layer_mask=0xFFFFFFFF, loss_mean=1, ln_eps=1e-12, beta1=0.9, beta2=0.999, adam_eps=1e-8,
-                      weight_decay=0.01, step_floor=1e-8, w_bits=4, a_bits=8, act_dtype=MREM_BF16)
+                      weight_decay=0.01, step_floor=1e-8, w_bits=4, a_bits=8, act_dtype=MREM_BF16, per_channel=1)
     for k, v in kw.items():
         if not hasattr(cfg, k):
             raise TypeError(f"unknown mrem_config field {k}")

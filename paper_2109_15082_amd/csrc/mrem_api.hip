@@ -53,6 +53,7 @@ extern "C" mrem_status mrem_create(const mrem_config* cfg, mrem_ctx** out) {
   if (!(c.w_bits == 0 || (c.w_bits >= 2 && c.w_bits <= 8))) return fail(nullptr, MREM_EINVAL, "w_bits must be 0 or 2..8");
   if (!(c.a_bits == 0 || (c.a_bits >= 2 && c.a_bits <= 8))) return fail(nullptr, MREM_EINVAL, "a_bits must be 0 or 2..8");
   if (c.act_dtype != MREM_BF16 && c.act_dtype != MREM_FP32) return fail(nullptr, MREM_EINVAL, "act_dtype must be MREM_BF16 or MREM_FP32");
+  if (c.per_channel != 0 && c.per_channel != 1) return fail(nullptr, MREM_EINVAL, "per_channel must be 0 or 1");
   mrem_ctx* x = new mrem_ctx();
   x->cfg = c;
   x->dt = c.act_dtype == MREM_BF16 ? DT_BF16 : DT_F32;
@@ -527,7 +528,7 @@ void apply_update(const Run& r, float* params, float* grads, float* m, float* v,
       jobs.push_back(j);
     }
   }
-  adam_matrix(jobs.data(), (int)jobs.size(), c->cfg.w_bits, a, write_grads, r.st);
+  adam_matrix(jobs.data(), (int)jobs.size(), c->cfg.w_bits, a, write_grads, c->cfg.per_channel ? 0 : 1, r.st);
   std::vector<VecJob> vjobs;
   for (int l = 0; l < c->L; ++l) {
     const int64_t o = c->layer_stride * l;
@@ -583,9 +584,13 @@ extern "C" mrem_status mrem_module_init_steps(mrem_ctx* ctx, float* params, void
   REQUIRE_PTR(params, "mrem_module_init_steps");
   if (ctx->cfg.w_bits == 0) return fail(ctx, MREM_EINVAL, "mrem_module_init_steps: weight quantizers are off (w_bits = 0)");
   for (int l = 0; l < ctx->L; ++l)
-    for (int i = 0; i < 4; ++i)
-      weight_step_init(params + ctx->layer_stride * l + ctx->foff[kWField[i]], params + ctx->layer_stride * l + ctx->foff[kSField[i]],
-                       ctx->wN[i], ctx->wK[i], ctx->cfg.w_bits, (hipStream_t)hip_stream);
+    for (int i = 0; i < 4; ++i) {
+      float* sw = params + ctx->layer_stride * l + ctx->foff[kSField[i]];
+      weight_step_init(params + ctx->layer_stride * l + ctx->foff[kWField[i]], sw, ctx->wN[i], ctx->wK[i], ctx->cfg.w_bits,
+                       (hipStream_t)hip_stream);
+      // one step per matrix: max|W| / Qp is the largest of the rows' quotients (the division is monotone)
+      if (!ctx->cfg.per_channel) tie_steps_max(sw, ctx->wN[i], (hipStream_t)hip_stream);
+    }
   return finish(ctx, "mrem_module_init_steps");
 }
 

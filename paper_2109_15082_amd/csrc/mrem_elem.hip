@@ -775,6 +775,15 @@ void weight_step_init(const float* w, float* scale, int64_t N, int64_t K, int bi
   hipLaunchKernelGGL(weight_step_init_k, dim3((unsigned)N), dim3(256), 0, st, w, scale, K, qp);
 }
 
+__global__ void tie_steps_max_k(float* __restrict__ scale, int64_t N) {
+  __shared__ float red[17];
+  float m = 0.f;
+  for (int64_t i = threadIdx.x; i < N; i += blockDim.x) m = fmaxf(m, scale[i]);
+  m = block_max(m, red);
+  for (int64_t i = threadIdx.x; i < N; i += blockDim.x) scale[i] = m;
+}
+void tie_steps_max(float* scale, int64_t N, hipStream_t st) { hipLaunchKernelGGL(tie_steps_max_k, dim3(1), dim3(256), 0, st, scale, N); }
+
 // codes (integer-valued, storage type), dequantized weights s*code (same layout), and
 // zcorr[n] = s[n] * sum_k code; one block per output channel, all matrices of a table in one launch
 struct WeightJobTable {
@@ -902,7 +911,7 @@ struct AdamJobTable {
   int first_row[kMaxMatrixJobs + 1];
   int njobs;
 };
-__global__ __launch_bounds__(256) void adam_matrix_k(AdamJobTable tab, float qp, int on, AdamArg a, int write_grads) {
+__global__ __launch_bounds__(256) void adam_matrix_k(AdamJobTable tab, float qp, int on, AdamArg a, int write_grads, int tied) {
   __shared__ float red[17];
   int ji = 0;
   while (ji + 1 < tab.njobs && (int)blockIdx.x >= tab.first_row[ji + 1]) ++ji;
@@ -948,7 +957,9 @@ __global__ __launch_bounds__(256) void adam_matrix_k(AdamJobTable tab, float qp,
   }
   if (on) {
     acc = block_sum(acc, red);
-    if (threadIdx.x == 0) {
+    if (threadIdx.x == 0 && tied) {
+      jb.g_sw[n] = acc;  // summed over the rows and applied by adam_tied_steps_k
+    } else if (threadIdx.x == 0) {
       if (write_grads) jb.g_sw[n] = acc;
       AdamArg as = a;
       as.wd = 0.f;
@@ -962,7 +973,26 @@ __global__ __launch_bounds__(256) void adam_matrix_k(AdamJobTable tab, float qp,
     jb.g_sw[n] = 0.f;
   }
 }
-void adam_matrix(const AdamJob* jobs, int njobs, int bits, AdamArg a, int write_grads, hipStream_t st) {
+// one block per matrix: fixed-order sum of the rows' step gradients, AdamW on the one step, broadcast
+__global__ __launch_bounds__(256) void adam_tied_steps_k(AdamJobTable tab, AdamArg a) {
+  __shared__ float red[17];
+  const AdamJob& jb = tab.job[blockIdx.x];
+  float t = 0.f;
+  for (int i = threadIdx.x; i < jb.N; i += blockDim.x) t += jb.g_sw[i];
+  const float g = block_sum(t, red);
+  AdamArg as = a;
+  as.wd = 0.f;
+  float m = jb.m_sw[0], vv = jb.v_sw[0];
+  const float ns = fmaxf(adam_one(jb.sw[0], g, m, vv, as), a.floor);
+  __syncthreads();  // every thread has read entry 0 before anyone overwrites it
+  for (int i = threadIdx.x; i < jb.N; i += blockDim.x) {
+    jb.sw[i] = ns;
+    jb.m_sw[i] = m;
+    jb.v_sw[i] = vv;
+    jb.g_sw[i] = g;
+  }
+}
+void adam_matrix(const AdamJob* jobs, int njobs, int bits, AdamArg a, int write_grads, int tied, hipStream_t st) {
   const int on = bits > 0;
   const float qp = on ? (float)((1 << (bits - 1)) - 1) : 0.f;
   for (int j0 = 0; j0 < njobs; j0 += kMaxMatrixJobs) {
@@ -972,7 +1002,8 @@ void adam_matrix(const AdamJob* jobs, int njobs, int bits, AdamArg a, int write_
     for (int j = 0; j < tab.njobs; ++j) { tab.job[j] = jobs[j0 + j]; tab.first_row[j] = rows; rows += jobs[j0 + j].N; }
     tab.first_row[tab.njobs] = rows;
     if (rows == 0) continue;
-    hipLaunchKernelGGL(adam_matrix_k, dim3(rows), dim3(256), 0, st, tab, qp, on, a, write_grads);
+    hipLaunchKernelGGL(adam_matrix_k, dim3(rows), dim3(256), 0, st, tab, qp, on, a, write_grads, (on && tied) ? 1 : 0);
+    if (on && tied) hipLaunchKernelGGL(adam_tied_steps_k, dim3(tab.njobs), dim3(256), 0, st, tab, a);
   }
 }
 

@@ -59,6 +59,8 @@ int gemm_profile_end(double ms[2], double flops[2], int64_t launches[2]);  // [0
 void weight_quantize_i8(const float* w, float* scale, int8_t* codes, int64_t N, int64_t K, int bits, int init_scale,
                         hipStream_t st);
 void weight_step_init(const float* w, float* scale, int64_t N, int64_t K, int bits, hipStream_t st);
+// scale[0..N) := max_n scale[n]  (one step for the whole matrix, kept as N equal entries)
+void tie_steps_max(float* scale, int64_t N, hipStream_t st);
 // Per matrix w[N,K] with steps sw[N]: codes[N,K] (integer-valued, storage type), what[N,K] =
 // round(s*q) (may be null), zcorr[N] = s[n] * sum_k q[n,k].  bits = 0: codes = what = round(w),
 // zcorr = 0.  All matrices of the list go into one launch (kMaxMatrixJobs per launch).
@@ -175,7 +177,10 @@ struct AdamJob {
   const float* db;
   int N, K;
 };
-void adam_matrix(const AdamJob* jobs, int njobs, int bits, AdamArg a, int write_grads, hipStream_t st);
+// tied != 0 (one step per matrix): the row kernels only leave their step gradients in g_sw; a second
+// launch sums them per matrix in a fixed order, updates the one step and writes it, its moments and its
+// gradient to all N entries.
+void adam_matrix(const AdamJob* jobs, int njobs, int bits, AdamArg a, int write_grads, int tied, hipStream_t st);
 // AdamW without decay on segments [off, off + n) of the parameter vector (all vectors share one
 // layout); clamp != 0 applies the lower bound a.floor afterwards (step sizes).  One launch per
 // kMaxVecJobs segments.

@@ -45,7 +45,7 @@ def make_case(wl: synth.Workload, weight_seed=1234, input_seed=5678, jitter=0.05
             lp[n] = synth.round_to_dtype(lp[n].astype(np.float32), wl.act_dtype).astype(np.float64)
     for lp in student:
         for n in MATRICES:
-            lp["s" + n] = O.weight_step_init(lp[n], wl.w_bits) if wl.w_bits else np.ones(lp[n].shape[0])
+            lp["s" + n] = O.weight_step_init(lp[n], wl.w_bits, cfg.per_channel) if wl.w_bits else np.ones(lp[n].shape[0])
         lp["s_a"], lp["z_a"] = np.ones(8), np.zeros(8)
     if wl.a_bits:
         xc = x if calib_seed is None else synth.make_hidden_states(wl.batch, wl.seq, wl.hidden, calib_seed, wl.act_dtype,
@@ -66,7 +66,7 @@ def device_module(case: Case, **cfg_kw):
     mod = B.MremModule(wl.n_layers, wl.hidden, wl.n_heads, wl.ffn, wl.batch, wl.seq, act_dtype=wl.act_dtype,
                        w_bits=wl.w_bits, a_bits=wl.a_bits, loss_layer_mask=mask, loss_mean=int(c.loss_mean),
                        ln_eps=c.ln_eps, beta1=c.beta1, beta2=c.beta2, adam_eps=c.adam_eps, weight_decay=c.weight_decay,
-                       step_floor=c.step_floor, **cfg_kw)
+                       step_floor=c.step_floor, per_channel=int(c.per_channel), **cfg_kw)
     # the teacher vector holds the unrounded fp32 weights; the library rounds the matrices to the
     # activation type itself when it prepares its operand cache
     mod.load(case.student, case.layers_f32)

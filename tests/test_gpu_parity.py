@@ -184,6 +184,32 @@ def test_step_matches_oracle_bf16(B, name):
     _compare_step(B, CASES_BF16[name])
 
 
+def test_per_tensor_weight_steps_fp32(B):
+    """One step per weight matrix (Section 3.1's default granularity): whole step against the oracle;
+    the step fields stay tied and carry the summed gradient."""
+    wl = CASES_F32["two_layer_f32"]
+    case = Hh.make_case_with_margin(wl, MARGIN, per_channel=False)
+    _compare_step(B, wl, case=case)
+
+
+def test_per_tensor_weight_steps_bf16_and_initial_steps(B):
+    torch = _torch()
+    wl = CASES_BF16["aligned_bf16"]
+    _compare_step(B, wl, case=Hh.make_case(wl, per_channel=False))
+    # mrem_module_init_steps under per_channel = 0: max|W| / Qp of the whole matrix in every entry, bit for bit
+    case = Hh.make_case(wl, per_channel=False)
+    mod = Hh.device_module(case)
+    mod.init_steps()
+    torch.cuda.synchronize()
+    pp = B.unpack_params(mod.ctx, mod.params, wl.n_layers)
+    for l in range(wl.n_layers):
+        for n in Hh.MATRICES:
+            want = O.weight_step_init(case.layers_f32[l][n], wl.w_bits, per_channel=False).astype(np.float32)
+            assert np.array_equal(pp[l]["s" + n], want)
+            assert np.all(want == want[0])
+    mod.close()
+
+
 def test_step_fp32_several_tiles_no_margin(B):
     _compare_step(B, MID_F32, tol=1e-2)
 

@@ -695,3 +695,47 @@ def test_pipeline_sequential_feeds_finished_chains():
     assert tr.loss[1][0] == res.loss
     # the quantized chain differs from the full-precision chain
     assert not np.array_equal(f_fp[-1], f_q[-1])
+
+
+# ---------------------------------------------------------------------------------
+# one step per weight matrix (Section 3.1's default granularity)
+# ---------------------------------------------------------------------------------
+
+def test_per_tensor_weight_steps_vs_autograd_of_a_scalar_step():
+    """per_channel=False: the initial step is max|W|/Qp over the whole matrix, the vector of
+    steps stays tied through AdamW updates, and the step gradient the oracle returns (one value,
+    repeated) equals torch's autograd derivative of the surrogate with a scalar step."""
+    cfg = tiny_cfg(n_layers=1)
+    cfg = O.Config(**{**cfg.__dict__, "per_channel": False})
+    batch, seq = 2, 6
+    teacher, student, x = tiny_student(cfg, batch=batch, seq=seq)
+    lp = student[0]
+    for n in O.WEIGHT_NAMES:
+        s0 = O.weight_step_init(lp[n], cfg.w_bits, per_channel=False)
+        assert np.all(s0 == s0[0])
+        assert s0[0] == np.float64(np.float32(np.float32(np.abs(lp[n]).max()) / np.float32(O.sym_range(cfg.w_bits)[1])))
+        lp["s" + n] = np.float64(np.float32(s0 * 0.9))       # off the clip bound (see the per-channel test)
+    res = O.module_grads(x, x, teacher, student, cfg, batch, seq, None)
+    # torch: scalar steps, expanded to rows inside the surrogate
+    tl = {k: torch.tensor(v, requires_grad=(k != "z_a")) for k, v in lp.items()}
+    scal = {n: torch.tensor(float(lp[n][0]), dtype=torch.float64, requires_grad=True) for n in O.STEP_NAMES}
+    tl_s = dict(tl)
+    for n in O.STEP_NAMES:
+        tl_s[n] = scal[n].expand(lp[n].shape[0])
+    h = _torch_student_layer(torch.tensor(x), tl_s, cfg, batch, seq, None)
+    loss = ((h - torch.tensor(res.f_fp[0])) ** 2).mean()
+    loss.backward()
+    for n in O.STEP_NAMES:
+        got = res.grads[0][n]
+        assert np.all(got == got[0])
+        assert abs(got[0] - scal[n].grad.item()) <= 2e-6 * abs(scal[n].grad.item()), (n, got[0], scal[n].grad.item())
+    # the per-channel gradients of the same point sum to it
+    cfg_pc = O.Config(**{**cfg.__dict__, "per_channel": True})
+    res_pc = O.module_grads(x, x, teacher, student, cfg_pc, batch, seq, None)
+    for n in O.STEP_NAMES:
+        np.testing.assert_allclose(res.grads[0][n][0], res_pc.grads[0][n].sum(), rtol=1e-12)
+    # tied through an update
+    m, v = ([{k: np.zeros_like(a) for k, a in lp.items()}], [{k: np.zeros_like(a) for k, a in lp.items()}])
+    O.module_step(x, x, teacher, student, m, v, 1, 1e-3, cfg, batch, seq, None)
+    for n in O.STEP_NAMES:
+        assert np.all(student[0][n] == student[0][n][0])
