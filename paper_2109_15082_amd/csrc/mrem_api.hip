@@ -159,7 +159,6 @@ Plan make_plan(const mrem_ctx* c, int B, int S) {
   p.dr2 = b.take(T * H * es); p.dr1 = b.take(T * H * es); p.dxh = b.take(T * H * es);
   p.dx1h = b.take(T * H * es); p.dch = b.take(T * H * es); p.dc = b.take(T * H * es);
   p.dgh = b.take(T * F * es); p.du = b.take(T * F * es); p.dqkvh = b.take(T * 3 * H * es); p.dqkv = b.take(T * 3 * H * es);
-  const size_t widest = (3 * H > F ? 3 * H : F);
   const size_t s_pad = ((size_t)S + 31) / 32 * 32;
   const size_t pp = (size_t)B * c->nh * s_pad * s_pad;
   p.s_da = b.take(pp * 4); p.s_ph = b.take(pp * 4);

@@ -417,7 +417,7 @@ static void fwd_launch(const void* codes, void* ctx, void* ctx_codes, const Attn
   const size_t lds = ((size_t)s_pad * kRowStride + (size_t)kD * (s_pad + 8)) * sizeof(bf16_t);
   static size_t configured = 0;
   if (lds > configured) {
-    hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_mfma_k<NT>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_mfma_k<NT>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     configured = lds;
   }
   dim3 g((S + 127) / 128, nh, B);
@@ -437,7 +437,7 @@ int attn_bwd_mfma(const void* codes, const void* dctx, void* d_qkvh, const AttnQ
   const size_t lds = ((size_t)2 * s_pad * kRowStride + (size_t)kD * (s_pad + 8)) * sizeof(bf16_t);
   static size_t configured = 0;
   if (lds > configured) {
-    hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_q_mfma_k<4>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_q_mfma_k<4>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     configured = lds;
   }
   dim3 gq((s_pad + 127) / 128, nh, B);

@@ -101,25 +101,6 @@ __device__ __forceinline__ float block_max(float v, float* scratch) {
   return scratch[16];
 }
 
-// Cross-block reduction without atomics on the data: every block stores its
-// partial(s), then calls this.  It returns true (uniformly) in the block that
-// arrives last; that block then sums the partials in index order, which makes the
-// result independent of scheduling.  The counter must be 0 on entry of the grid
-// and is reset by the last block.
-__device__ __forceinline__ bool last_block_arrives(unsigned* counter, unsigned nblocks) {
-  __shared__ int is_last_;
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    unsigned t = atomicAdd(counter, 1u);
-    is_last_ = (t == nblocks - 1u);
-    if (is_last_) *counter = 0u;
-  }
-  __syncthreads();
-  if (is_last_) __threadfence();
-  return is_last_ != 0;
-}
-
 __device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f)); }
 __device__ __forceinline__ float gelu_grad_f(float u) {
   return 0.5f * (1.0f + erff(u * 0.70710678118654752440f)) + u * __expf(-0.5f * u * u) * 0.39894228040143267794f;

@@ -12,6 +12,8 @@
 namespace mrem {
 
 // ---- optional timing of every product launch with HIP events (measurement aid) ----
+// Return codes of event and attribute calls are not looked at here: the runtime keeps the last
+// error, and every entry point of the library ends by reading it (hipGetLastError).
 namespace {
 struct GemmRecord {
   hipEvent_t e0, e1;
@@ -24,7 +26,7 @@ std::vector<GemmRecord> g_prof;
 
 bool gemm_profile_active() { return g_prof_on; }
 void gemm_profile_begin() {
-  for (auto& r : g_prof) { hipEventDestroy(r.e0); hipEventDestroy(r.e1); }
+  for (auto& r : g_prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
   g_prof.clear();
   g_prof_on = true;
 }
@@ -39,8 +41,8 @@ int gemm_profile_end(double ms[2], double flops[2], int64_t launches[2]) {
     ms[r.cls] += e;
     flops[r.cls] += r.flops;
     launches[r.cls] += 1;
-    hipEventDestroy(r.e0);
-    hipEventDestroy(r.e1);
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
   }
   g_prof.clear();
   return rc;
@@ -133,7 +135,6 @@ typedef int i32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kBK = 64;
 constexpr int kRegBK = 64;  // k-step of the register-staged kernel
-constexpr int kLdsStride = kBK + 8;  // elements per LDS row (144 bytes)
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
@@ -314,7 +315,7 @@ static void launch_mfma(const void* A, int lda, const void* B, int ldb, void* C,
   constexpr size_t lds = 2 * (size_t)(OperandTile<AT, BM, NTHREADS, BK>::ELEMS + OperandTile<BT, BN, NTHREADS, BK>::ELEMS) * sizeof(bf16_t);
   static bool configured = false;
   if (!configured) {
-    hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, BK, TO, I8>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, BK, TO, I8>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     configured = true;
   }
@@ -540,7 +541,7 @@ static void launch_pc(const void* A, int lda, const void* B, int ldb, void* C, i
   constexpr size_t lds = (size_t)STAGES * (BM + BN) * 128;
   static bool configured = false;
   if (!configured) {
-    hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_pc_k<BM, BN, WAVES_M, WAVES_N, STAGES, TO, TE>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_pc_k<BM, BN, WAVES_M, WAVES_N, STAGES, TO, TE>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     configured = true;
   }
@@ -566,11 +567,11 @@ void gemm(int dt, int a_t, int b_t, const void* A, int lda, const void* B, int l
   }
   GemmRecord r;
   r.flops = 2.0 * (double)M * (double)N * (double)K;
-  hipEventCreate(&r.e0);
-  hipEventCreate(&r.e1);
-  hipEventRecord(r.e0, st);
+  (void)hipEventCreate(&r.e0);
+  (void)hipEventCreate(&r.e1);
+  (void)hipEventRecord(r.e0, st);
   gemm_launch(dt, a_t, b_t, A, lda, B, ldb, C, ldc, M, N, K, e, st);
-  hipEventRecord(r.e1, st);
+  (void)hipEventRecord(r.e1, st);
   g_prof.push_back(r);
 }
 
@@ -593,11 +594,11 @@ void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, i
   }
   GemmRecord r;
   r.flops = 2.0 * (double)M * (double)N * (double)K;
-  hipEventCreate(&r.e0);
-  hipEventCreate(&r.e1);
-  hipEventRecord(r.e0, st);
+  (void)hipEventCreate(&r.e0);
+  (void)hipEventCreate(&r.e1);
+  (void)hipEventRecord(r.e0, st);
   gemm_i8_launch(A, lda, B, ldb, C, ldc, M, N, K, e, st);
-  hipEventRecord(r.e1, st);
+  (void)hipEventRecord(r.e1, st);
   r.cls = 1;
   g_prof.push_back(r);
 }
