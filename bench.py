@@ -5,7 +5,9 @@
 
 A step = teacher forward + quantized forward + Eq. 3 loss + straight-through
 backward + AdamW update of weights and step sizes, on one synthetic batch that is
-already resident in HBM.  Prints ONE JSON line (see README / DESIGN for fields).
+already resident in HBM.  Prints ONE JSON line: tokens/s of the step (value), the time per step, the
+roofline of the matrix products (bf16 and int8 launches timed with HIP events in a second pass) and
+the oracle's rate on the host cores (cpu_baseline).
 """
 import argparse
 import json
