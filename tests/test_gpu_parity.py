@@ -122,9 +122,11 @@ CASES_BF16 = {
 MID_F32 = W("mid_f32", 2, 128, 2, 512, 80, 3, act_dtype="f32", seqlen_lo=40, seqlen_hi=80)
 
 
-def _compare_step(B, wl, lr=1e-3, case=None, tol=None, **cfg_kw):
+def _compare_step(B, wl, lr=1e-3, case=None, tol=None, tol_for=None, **cfg_kw):
+    """tol_for: {quantity name: tolerance} for the quantities judged on another scale than tol."""
     torch = _torch()
     tol = tol or TOL[wl.act_dtype]
+    tol_for = tol_for or {}
     case = case or Hh.make_case(wl, **cfg_kw)
     mod = Hh.device_module(case)
     x, sl = Hh.device_inputs(case)
@@ -164,7 +166,7 @@ def _compare_step(B, wl, lr=1e-3, case=None, tol=None, **cfg_kw):
         assert np.array_equal(pp[l]["z_a"], case.student[l]["z_a"].astype(np.float32))
         # first moment after one step is (1-beta1)*g: ties the update to the exported gradient
         np.testing.assert_allclose(mm[l]["w_1"], (1 - case.cfg.beta1) * gg[l]["w_1"], rtol=1e-5, atol=1e-30)
-    bad = [(n, e) for n, e in report if not e <= tol]
+    bad = [(n, e) for n, e in report if not e <= tol_for.get(n, tol)]
     assert not bad, f"{wl.name}: beyond {tol}: {bad}"
     mod.close()
     return dict(report)
@@ -351,6 +353,19 @@ def test_full_size_bert_base_module_step(B):
     """The BERT-base-shaped 3-layer module (seq 128, batch 32, bf16): one whole step
     against the oracle -- every output, loss and gradient."""
     _compare_step(B, synth.WORKLOADS["bert_base_3l"], lr=1e-4)
+
+
+def test_full_size_bert_large_module_step(B):
+    """The bench workload itself (6 layers, H1024, F4096, seq 128, batch 32, 1% outlier channels,
+    W4A8, bf16): one whole step against the oracle at full size -- every layer output of both
+    modules, the loss, every gradient and every updated parameter within 2e-2.  The one exception
+    is stated in the next test's text: the quantized module's outputs of layers 3..5, where one
+    bf16 rounding upstream that goes the other way flips a code worth half a standard deviation
+    and such differences grow through the chained quantized layers (measured 2.2e-2, 3.1e-2,
+    3.9e-2); they are held to 1e-1 here and checked layer by layer from the oracle's inputs below.
+    The oracle takes about 20 s for this step on the machine's host cores."""
+    wl = synth.WORKLOADS["bert_large_6l"]
+    _compare_step(B, wl, lr=1e-4, tol_for={"f_q[3]": 1e-1, "f_q[4]": 1e-1, "f_q[5]": 1e-1})
 
 
 def _full_size_forward_on_sampled_sequences(B, wl, pick, chained_tol):
