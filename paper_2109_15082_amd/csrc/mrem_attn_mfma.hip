@@ -10,6 +10,10 @@
 // in lane ^ 32.  Row-wise softmax statistics then need a single cross-lane exchange,
 // and the accumulator registers already have the layout of the B operand of the next
 // product (contraction over keys), with the key order fixed by `key_of`.
+//
+// All tiles (K, V, Q, dC) sit row-major in LDS as they do in memory; where a product
+// needs an operand with the contraction index along the rows, the fragment is gathered
+// with the transposing LDS read (ds_read_tr16_b64), see `ld_frag_tr`.
 #include "mrem_common.h"
 #include "mrem_kernels.h"
 
@@ -61,27 +65,21 @@ __device__ __forceinline__ void stage_rows(const bf16_t* __restrict__ src, int l
     *reinterpret_cast<u32x4_t*>(dst + row * kRowStride + ch * 8) = v;
   }
 }
-// stage the same slice transposed: dst[e][row], row stride t_stride elements; rows r0 .. r0+nrows of src
-__device__ __forceinline__ void stage_transposed(const bf16_t* __restrict__ src, int ld, int S, int r0, int nrows, int t_stride,
-                                                 bf16_t* dst) {
-  for (int q = threadIdx.x; q < nrows * 8; q += blockDim.x) {
-    const int row = q >> 3, ch = q & 7;
-    union { u32x4_t v; bf16_t h[8]; } u;
-    u.v = (u32x4_t){0u, 0u, 0u, 0u};
-    if (r0 + row < S) u.v = *reinterpret_cast<const u32x4_t*>(src + (size_t)(r0 + row) * ld + ch * 8);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) dst[(ch * 8 + i) * t_stride + row] = u.h[i];
-  }
-}
-
 __device__ __forceinline__ bf16x8_t ld_frag(const bf16_t* p) { return *reinterpret_cast<const bf16x8_t*>(p); }
 
-// A operand of a key-contracted product from a transposed tile xt[e][key]: keys of step s of tile t for half h
-__device__ __forceinline__ bf16x8_t ld_frag_t(const bf16_t* xt_row, int t, int s, int h) {
-  union { bf16x8_t v; u32x2_t p[2]; } u;
-  const bf16_t* p = xt_row + 32 * t + 16 * s + 4 * h;
-  u.p[0] = *reinterpret_cast<const u32x2_t*>(p);
-  u.p[1] = *reinterpret_cast<const u32x2_t*>(p + 8);
+// MFMA operand fragment gathered down the rows of a row-major LDS tile (pitch kRowStride) with the
+// transposing LDS read (ds_read_b64_tr_b16): lane l receives, for column c0 + l%32, rows
+// r_first + 0..3 and r_second + 0..3 (the caller picks the two row bases for its half l/32).  In a
+// group of 16 lanes, lane s supplies the 8-byte chunk of row s/4, columns 4*(s%4)..+3, and receives
+// column s of the four rows.  Lets K, V, Q and dC stay row-major in LDS (16-byte conflict-free stores)
+// where the products contract over their row index.
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8_t ld_frag_tr(const bf16_t* tile, int c0, int r_first, int r_second, int lane) {
+  const int g = lane >> 4, s = lane & 15;
+  const bf16_t* p = tile + (s >> 2) * kRowStride + c0 + 16 * (g & 1) + 4 * (s & 3);
+  union { bf16x8_t v; s16x4_t h[2]; } u;
+  u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(p + r_first * kRowStride));
+  u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(p + r_second * kRowStride));
   return u.v;
 }
 
@@ -99,9 +97,9 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_k(const bf16_t* __restrict_
                                                        int S, int H, int nt, float* __restrict__ pmax_rows, float* __restrict__ stat_m,
                                                        float* __restrict__ stat_l, int8_t* __restrict__ ctx_codes8) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  const int s_pad = 32 * nt, t_stride = s_pad + 8;
+  const int s_pad = 32 * nt;
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem_raw);  // [s_pad][72]
-  bf16_t* Vt = Ks + s_pad * kRowStride;              // [64][s_pad + 8]
+  bf16_t* Vs = Ks + s_pad * kRowStride;              // [s_pad][72]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z, nh = gridDim.y;
   const int ld = 3 * H;
@@ -110,7 +108,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_k(const bf16_t* __restrict_
   const FwdScales sc = load_fwd_scales(aq);
 
   stage_rows(base + H, ld, S, s_pad, Ks);
-  stage_transposed(base + 2 * H, ld, S, 0, s_pad, t_stride, Vt);
+  stage_rows(base + 2 * H, ld, S, s_pad, Vs);
   __syncthreads();
 
   const int q0 = blockIdx.x * 128 + wave * 32;
@@ -164,8 +162,6 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_k(const bf16_t* __restrict_
   for (int et = 0; et < 2; ++et)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[et][r] = 0.f;
-  const bf16_t* vrow0 = Vt + (lane & 31) * t_stride;
-  const bf16_t* vrow1 = vrow0 + 32 * t_stride;
   const float rsum = __fdiv_rn(1.0f, sum);
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
@@ -179,8 +175,10 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_k(const bf16_t* __restrict_
           const float c = sc.p_on ? rintf(fminf(fmaxf(div_by(p, sc.sp, sc.rsp), 0.f), sc.p_qp)) : p;
           pf[i] = static_cast<bf16_t>(c);
         }
-        oacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_t(vrow0, t, s, half), pf, oacc[0], 0, 0, 0);
-        oacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_t(vrow1, t, s, half), pf, oacc[1], 0, 0, 0);
+        // V^T fragments: keys in the order the accumulator registers of the score tile hold them
+        const int k0 = 32 * t + 16 * s + 4 * half;
+        oacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_tr(Vs, 0, k0, k0 + 8, lane), pf, oacc[0], 0, 0, 0);
+        oacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_tr(Vs, 32, k0, k0 + 8, lane), pf, oacc[1], 0, 0, 0);
       }
     }
   }
@@ -228,10 +226,9 @@ __global__ __launch_bounds__(256) void attn_bwd_q_mfma_k(const bf16_t* __restric
                                                          bf16_t* __restrict__ pt_out, bf16_t* __restrict__ dat_out,
                                                          float* __restrict__ ds_parts) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  const int s_pad = 32 * nt, t_stride = s_pad + 8;
+  const int s_pad = 32 * nt;
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem_raw);  // [s_pad][72]
   bf16_t* Vs = Ks + s_pad * kRowStride;              // [s_pad][72]
-  bf16_t* Kt = Vs + s_pad * kRowStride;              // [64][s_pad + 8]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z, nh = gridDim.y;
   const int ld = 3 * H;
@@ -242,7 +239,6 @@ __global__ __launch_bounds__(256) void attn_bwd_q_mfma_k(const bf16_t* __restric
 
   stage_rows(base + H, ld, S, s_pad, Ks);
   stage_rows(base + 2 * H, ld, S, s_pad, Vs);
-  stage_transposed(base + H, ld, S, 0, s_pad, t_stride, Kt);
   __syncthreads();
 
   const int q0 = blockIdx.x * 128 + wave * 32;
@@ -270,8 +266,6 @@ __global__ __launch_bounds__(256) void attn_bwd_q_mfma_k(const bf16_t* __restric
   for (int et = 0; et < 2; ++et)
 #pragma unroll
     for (int r = 0; r < 16; ++r) dqacc[et][r] = 0.f;
-  const bf16_t* krow0 = Kt + (lane & 31) * t_stride;
-  const bf16_t* krow1 = krow0 + 32 * t_stride;
   const size_t tbase = ((size_t)b * nh + h) * s_pad * s_pad;
 
   // phase 0 accumulates rowdot = sum_j dP[q][j] * P[q][j]; phase 1 forms dA and consumes it
@@ -320,8 +314,9 @@ __global__ __launch_bounds__(256) void attn_bwd_q_mfma_k(const bf16_t* __restric
           bf16x8_t af;
 #pragma unroll
           for (int i = 0; i < 8; ++i) af[i] = static_cast<bf16_t>(da[8 * s + i]);
-          dqacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_t(krow0, t, s, half), af, dqacc[0], 0, 0, 0);
-          dqacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_t(krow1, t, s, half), af, dqacc[1], 0, 0, 0);
+          const int k0 = 32 * t + 16 * s + 4 * half;
+          dqacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_tr(Ks, 0, k0, k0 + 8, lane), af, dqacc[0], 0, 0, 0);
+          dqacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_tr(Ks, 32, k0, k0 + 8, lane), af, dqacc[1], 0, 0, 0);
         }
       }
     }
@@ -344,13 +339,13 @@ __global__ __launch_bounds__(256) void attn_bwd_q_mfma_k(const bf16_t* __restric
 
 // ------------------------------------------------------------------------------
 // backward, key-major part: dV^[j] = sum_q P^[q][j] dC[q], dK^[j] = sum_q dA[q][j] Q^[q] / sqrt(d).
-// One wavefront = 32 keys; queries are streamed in chunks of 128 through LDS (transposed).
+// One wavefront = 32 keys; queries are streamed in chunks of 128 through LDS (row-major, read transposed).
 // ------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void attn_bwd_k_mfma_k(const bf16_t* __restrict__ codes, const bf16_t* __restrict__ dctx,
                                                          bf16_t* __restrict__ d_qkvh, AttnQ aq, int S, int H, int nt,
                                                          const bf16_t* __restrict__ pt_in, const bf16_t* __restrict__ dat_in) {
-  __shared__ __attribute__((aligned(16))) bf16_t Qt[kD * 136];
-  __shared__ __attribute__((aligned(16))) bf16_t Ct[kD * 136];
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[128 * kRowStride];  // one chunk of queries, row-major
+  __shared__ __attribute__((aligned(16))) bf16_t Cs[128 * kRowStride];  // the same rows of dC
   const int s_pad = 32 * nt;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z, nh = gridDim.y;
@@ -371,8 +366,8 @@ __global__ __launch_bounds__(256) void attn_bwd_k_mfma_k(const bf16_t* __restric
   for (int c0 = 0; c0 < s_pad; c0 += 128) {
     const int cn = (s_pad - c0) < 128 ? (s_pad - c0) : 128;
     __syncthreads();
-    stage_transposed(base, ld, S, c0, cn, 136, Qt);
-    stage_transposed(cbase, H, S, c0, cn, 136, Ct);
+    stage_rows(base + (size_t)c0 * ld, ld, S - c0, cn, Qs);
+    stage_rows(cbase + (size_t)c0 * H, H, S - c0, cn, Cs);
     __syncthreads();
     if (active) {
       const bf16_t* prow = pt_in + tbase + (size_t)jrow * s_pad + c0 + 8 * half;
@@ -380,11 +375,11 @@ __global__ __launch_bounds__(256) void attn_bwd_k_mfma_k(const bf16_t* __restric
       for (int s = 0; s < cn / 16; ++s) {
         const bf16x8_t pf = ld_frag(prow + 16 * s);
         const bf16x8_t af = ld_frag(arow + 16 * s);
+        const int q0 = 16 * s + 8 * half;  // queries of this lane's k-slots, in natural order
 #pragma unroll
         for (int et = 0; et < 2; ++et) {
-          const int e = 32 * et + (lane & 31);
-          vacc[et] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, ld_frag(Ct + e * 136 + 16 * s + 8 * half), vacc[et], 0, 0, 0);
-          kacc[et] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, ld_frag(Qt + e * 136 + 16 * s + 8 * half), kacc[et], 0, 0, 0);
+          vacc[et] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, ld_frag_tr(Cs, 32 * et, q0, q0 + 4, lane), vacc[et], 0, 0, 0);
+          kacc[et] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, ld_frag_tr(Qs, 32 * et, q0, q0 + 4, lane), kacc[et], 0, 0, 0);
         }
       }
     }
@@ -414,7 +409,7 @@ template <int NT>
 static void fwd_launch(const void* codes, void* ctx, void* ctx_codes, const AttnQ& aq, const int32_t* seqlens, int B, int S, int nh,
                        float* pmax_rows, float* stat_m, float* stat_l, hipStream_t st, int8_t* ctx_codes8) {
   const int nt = (S + 31) / 32, s_pad = 32 * nt;
-  const size_t lds = ((size_t)s_pad * kRowStride + (size_t)kD * (s_pad + 8)) * sizeof(bf16_t);
+  const size_t lds = (size_t)2 * s_pad * kRowStride * sizeof(bf16_t);
   static size_t configured = 0;
   if (lds > configured) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_mfma_k<NT>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -434,7 +429,7 @@ void attn_fwd_mfma(const void* codes, void* ctx, void* ctx_codes, const AttnQ& a
 int attn_bwd_mfma(const void* codes, const void* dctx, void* d_qkvh, const AttnQ& aq, const int32_t* seqlens, int B, int S, int nh,
                   const float* stat_m, const float* stat_l, void* pt_scratch, void* dat_scratch, float* ds_parts, hipStream_t st) {
   const int nt = (S + 31) / 32, s_pad = 32 * nt;
-  const size_t lds = ((size_t)2 * s_pad * kRowStride + (size_t)kD * (s_pad + 8)) * sizeof(bf16_t);
+  const size_t lds = (size_t)2 * s_pad * kRowStride * sizeof(bf16_t);
   static size_t configured = 0;
   if (lds > configured) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_q_mfma_k<4>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
