@@ -15,10 +15,12 @@
  *    ordinary host memory.
  *  - All work is enqueued on the caller's hipStream_t (passed as void*, NULL = the
  *    default stream) or ordered with it: mrem_module_step runs the full-precision
- *    forward pass on a side stream that the context owns (default priority, created
- *    on the first step), forked from the caller's stream by an event at the start of
- *    the call and joined to it before the loss; to the caller the call behaves like
- *    work on its own stream.  Calls return without synchronising.
+ *    forward pass, and the update of each layer's weight matrices once that layer's
+ *    gradients are complete, on a side stream that the context owns (default
+ *    priority, created on the first step), forked from the caller's stream by
+ *    events and joined to it before the loss and before the call's last kernels; to
+ *    the caller the call behaves like work on its own stream.  Calls return without
+ *    synchronising.
  *  - Arguments are validated on the host before anything is enqueued; a call that
  *    returns an error has had no effect on device memory.
  *  - Return value: MREM_OK or a negative mrem_status.  mrem_last_error() gives a

@@ -26,6 +26,7 @@ struct mrem_ctx {
   // device that is current then; default priority) and the two events of its fork and join
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  std::vector<hipEvent_t> ev_layer;  // "the backward pass of layer l is enqueued", one per layer
   int side_device = -1;
 };
 
@@ -77,6 +78,7 @@ extern "C" void mrem_destroy(mrem_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->side);
     (void)hipEventDestroy(ctx->ev_fork);
     (void)hipEventDestroy(ctx->ev_join);
+    for (hipEvent_t e : ctx->ev_layer) (void)hipEventDestroy(e);
     (void)hipStreamDestroy(ctx->side);
   }
   delete ctx;
@@ -390,8 +392,22 @@ void dgrad(const Run& r, int l, int i, const void* dy, void* out) {
   gemm(c->dt, 0, 1, dy, c->wN[i], r.at(r.p.lw[l].what[i]), c->wK[i], out, c->wK[i], r.T, c->wK[i], c->wN[i], e, r.st);
 }
 
+// What the backward pass needs to update the weight matrices of a layer as soon as that layer's
+// gradients are complete (Algorithm 2, last line), on `side` if there is one.
+struct Update {
+  float* params;
+  float* m;
+  float* v;
+  AdamArg a;
+  int write_grads;
+  hipStream_t side;            // nullptr: everything on the caller's stream
+  const hipEvent_t* ev_layer;  // one per layer when side != nullptr
+  hipEvent_t ev_join;
+};
+void update_matrices(const Run& r, const Update& u, float* grads, int l, hipStream_t st);
+
 void student_backward(const Run& r, const float* params, const void* x_q, const void* per_layer_fp, const void* per_layer_q,
-                      float* grads, float* loss_out) {
+                      float* grads, float* loss_out, const Update& up) {
   const mrem_ctx* c = r.c;
   const size_t es = dt_size(c->dt);
   const int H = c->H, F = c->F, T = r.T, L = c->L;
@@ -402,6 +418,7 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
   // (the gradient slots of the fixed quantizer offsets).
   fill_f32(grads, 0.f, mrem_param_count(c), r.st);
   for (int l = L - 1; l >= 0; --l) {
+    const size_t first_job = red.jobs.size();
     const LayerWs& w = r.p.lw[l];
     const float* base = params + c->layer_stride * l;
     float* g = grads + c->layer_stride * l;
@@ -495,46 +512,65 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       const int n = quant_bwd_reduce(c->dt, r.at(r.p.dxh), x, numel, make_q(c, params, 0, 0), parts, r.st);
       red.add(parts, n, 1, 0, 1, g + c->foff[MREM_F_S_A] + 0);
     }
+    // This layer's gradients are complete and nothing below reads its matrices or their steps
+    // again (the input gradients used the dequantized copies): its second-stage reductions and
+    // the update of its four matrices, which is bound by memory traffic, run beside the
+    // matrix products of the layers below.
+    hipStream_t us = r.st;
+    if (up.side) {
+      us = up.side;
+      (void)hipEventRecord(up.ev_layer[l], r.st);
+      (void)hipStreamWaitEvent(us, up.ev_layer[l], 0);
+    }
+    reduce_jobs(red.jobs.data() + first_job, (int)(red.jobs.size() - first_job), us);
+    update_matrices(r, up, grads, l, us);
   }
-  reduce_jobs(red.jobs.data(), (int)red.jobs.size(), r.st);
+  if (up.side) {
+    (void)hipEventRecord(up.ev_join, up.side);
+    (void)hipStreamWaitEvent(r.st, up.ev_join, 0);
+  }
   loss_total(loss_out, L, r.st);
 }
 
-void apply_update(const Run& r, float* params, float* grads, float* m, float* v, int64_t step, float lr, int write_grads) {
-  const mrem_ctx* c = r.c;
+AdamArg adam_arg(const mrem_ctx* c, int64_t step, float lr) {
   AdamArg a;
   a.lr = lr; a.beta1 = c->cfg.beta1; a.beta2 = c->cfg.beta2; a.eps = c->cfg.adam_eps; a.wd = c->cfg.weight_decay;
   a.bc1 = (float)(1.0 - std::pow((double)c->cfg.beta1, (double)step));
   a.bc2 = (float)(1.0 - std::pow((double)c->cfg.beta2, (double)step));
   a.floor = c->cfg.step_floor;
-  AdamArg nodecay = a;
-  nodecay.wd = 0.f;
-  // the matrices first (they read the bias gradient and the activation offset of their layer), then the vectors
-  std::vector<AdamJob> jobs;
-  jobs.reserve((size_t)c->L * 4);
-  for (int l = 0; l < c->L; ++l) {
-    const int64_t o = c->layer_stride * l;
-    for (int i = 0; i < 4; ++i) {
-      const int64_t ow = o + c->foff[kWField[i]], os = o + c->foff[kSField[i]];
-      // the second feed-forward projection reads the GELU output through an asymmetric quantizer with offset z
-      const bool zterm = (i == 3 && c->cfg.a_bits > 0);
-      AdamJob j;
-      j.w = params + ow; j.sw = params + os; j.g_w = grads + ow; j.g_sw = grads + os;
-      j.m_w = m + ow; j.v_w = v + ow; j.m_sw = m + os; j.v_sw = v + os;
-      j.z_in = zterm ? params + o + c->foff[MREM_F_Z_A] + 7 : nullptr;
-      j.db = zterm ? grads + o + c->foff[MREM_F_B_2] : nullptr;
-      j.N = c->wN[i]; j.K = c->wK[i];
-      jobs.push_back(j);
-    }
+  return a;
+}
+// AdamW on the four weight matrices of layer l and their steps (they read the bias gradient and the
+// activation offset of their layer, so the layer's reductions come first on the same stream)
+void update_matrices(const Run& r, const Update& u, float* grads, int l, hipStream_t st) {
+  const mrem_ctx* c = r.c;
+  AdamJob jobs[4];
+  const int64_t o = c->layer_stride * l;
+  for (int i = 0; i < 4; ++i) {
+    const int64_t ow = o + c->foff[kWField[i]], os = o + c->foff[kSField[i]];
+    // the second feed-forward projection reads the GELU output through an asymmetric quantizer with offset z
+    const bool zterm = (i == 3 && c->cfg.a_bits > 0);
+    AdamJob& j = jobs[i];
+    j.w = u.params + ow; j.sw = u.params + os; j.g_w = grads + ow; j.g_sw = grads + os;
+    j.m_w = u.m + ow; j.v_w = u.v + ow; j.m_sw = u.m + os; j.v_sw = u.v + os;
+    j.z_in = zterm ? u.params + o + c->foff[MREM_F_Z_A] + 7 : nullptr;
+    j.db = zterm ? grads + o + c->foff[MREM_F_B_2] : nullptr;
+    j.N = c->wN[i]; j.K = c->wK[i];
   }
-  adam_matrix(jobs.data(), (int)jobs.size(), c->cfg.w_bits, a, write_grads, c->cfg.per_channel ? 0 : 1, r.st);
+  adam_matrix(jobs, 4, c->cfg.w_bits, u.a, u.write_grads, c->cfg.per_channel ? 0 : 1, st);
+}
+// AdamW (no decay) on everything that is not a matrix: biases, LayerNorm parameters, activation steps
+void update_vectors(const Run& r, const Update& u, float* grads) {
+  const mrem_ctx* c = r.c;
+  AdamArg nodecay = u.a;
+  nodecay.wd = 0.f;
   std::vector<VecJob> vjobs;
   for (int l = 0; l < c->L; ++l) {
     const int64_t o = c->layer_stride * l;
     vjobs.push_back(VecJob{o + c->foff[MREM_F_B_QKV], c->foff[MREM_F_SW_QKV] - c->foff[MREM_F_B_QKV], 0});
     if (c->cfg.a_bits > 0) vjobs.push_back(VecJob{o + c->foff[MREM_F_S_A], 8, 1});
   }
-  adam_vector(params, grads, m, v, vjobs.data(), (int)vjobs.size(), nodecay, r.st);
+  adam_vector(u.params, grads, u.m, u.v, vjobs.data(), (int)vjobs.size(), nodecay, r.st);
 }
 
 mrem_status check_common(const mrem_ctx* ctx, int32_t batch, int32_t seq, const void* workspace, size_t workspace_bytes, const char* who,
@@ -694,6 +730,10 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
         hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess)
       return fail(ctx, MREM_EHIP, "mrem_module_step: cannot create the side stream");
+    ctx->ev_layer.assign((size_t)ctx->L, nullptr);
+    for (hipEvent_t& e : ctx->ev_layer)
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess)
+        return fail(ctx, MREM_EHIP, "mrem_module_step: cannot create the side stream's events");
     ctx->side_device = dev;
   }
   if (dev != ctx->side_device) return fail(ctx, MREM_EINVAL, "mrem_module_step: the context was first used on another device");
@@ -711,8 +751,10 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
   prepare_weights(r, params);
   student_forward(r, params, x_q, per_layer_q);
   if (fork) (void)hipStreamWaitEvent(r.st, ctx->ev_join, 0);
-  student_backward(r, params, x_q, per_layer_fp, per_layer_q, grads, loss_out);
-  apply_update(r, params, grads, adam_m, adam_v, step_index, lr, grads_out != nullptr);
+  const Update up{params, adam_m, adam_v, adam_arg(ctx, step_index, lr), grads_out != nullptr, fork ? ctx->side : nullptr,
+                  ctx->ev_layer.data(), ctx->ev_join};
+  student_backward(r, params, x_q, per_layer_fp, per_layer_q, grads, loss_out, up);
+  update_vectors(r, up, grads);
   return finish(ctx, "mrem_module_step");
 }
 
