@@ -27,6 +27,8 @@ struct mrem_ctx {
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   std::vector<hipEvent_t> ev_layer;  // "the backward pass of layer l is enqueued", one per layer
+  std::vector<hipEvent_t> ev_ready;  // [4 * l + i]: the output gradient of linear layer i of layer l is written
+  std::vector<hipEvent_t> ev_done;   // [4 * l + i]: its weight-gradient product has read it
   int side_device = -1;
 };
 
@@ -79,6 +81,8 @@ extern "C" void mrem_destroy(mrem_ctx* ctx) {
     (void)hipEventDestroy(ctx->ev_fork);
     (void)hipEventDestroy(ctx->ev_join);
     for (hipEvent_t e : ctx->ev_layer) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ctx->ev_ready) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ctx->ev_done) (void)hipEventDestroy(e);
     (void)hipStreamDestroy(ctx->side);
   }
   delete ctx;
@@ -382,7 +386,7 @@ void wgrad(const Run& r, const float* params, float* grads, int l, int i, const 
   const QArg q = make_q(c, params, l, kInQuant[i]);
   if (q.on) e.alpha = q.s;  // the offset term z * db[n] of an asymmetric input quantizer is added by the update kernel
   e.out_f32 = 1;
-  e.c_zeroed = 1;  // the backward pass starts by zeroing the whole gradient buffer
+  e.c_zeroed = 1;  // the step starts by zeroing the whole gradient buffer
   gemm(c->dt, 1, 1, dy, c->wN[i], codes_in, c->wK[i], g + c->foff[kWField[i]], c->wK[i], c->wN[i], c->wK[i], r.T, e, r.st);
 }
 // input-gradient product: d(in^) = dY * W^ with the dequantized weights [N_out, K_in]
@@ -402,6 +406,8 @@ struct Update {
   int write_grads;
   hipStream_t side;            // nullptr: everything on the caller's stream
   const hipEvent_t* ev_layer;  // one per layer when side != nullptr
+  const hipEvent_t* ev_ready;  // four per layer
+  const hipEvent_t* ev_done;   // four per layer
   hipEvent_t ev_join;
 };
 void update_matrices(const Run& r, const Update& u, float* grads, int l, hipStream_t st);
@@ -414,9 +420,6 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
   const size_t slice = (size_t)T * H * es;
   const int64_t numel = (int64_t)T * H;
   Reductions red;
-  // One fill for everything that is added into (split weight-gradient products) or never written
-  // (the gradient slots of the fixed quantizer offsets).
-  fill_f32(grads, 0.f, mrem_param_count(c), r.st);
   for (int l = L - 1; l >= 0; --l) {
     const size_t first_job = red.jobs.size();
     const LayerWs& w = r.p.lw[l];
@@ -427,6 +430,22 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
     const void* ffp = (const char*)per_layer_fp + slice * l;
     const bool in_loss = (c->cfg.loss_layer_mask >> l) & 1u;
     red.next = r.at<float>(r.p.partials) + r.p.partials_per_layer * l;
+    // The weight-gradient products feed nothing but the update, so with a side stream they run
+    // there, beside the input-gradient products and the bandwidth-bound kernels of this stream.
+    // The output-gradient buffers are shared by all layers: before this stream overwrites one, it
+    // waits until the product of the layer above has read it.
+    auto issue_wgrad = [&](int i, const void* dy, const void* codes) {
+      if (!up.side) { wgrad(r, params, grads, l, i, dy, codes); return; }
+      (void)hipEventRecord(up.ev_ready[4 * l + i], r.st);
+      (void)hipStreamWaitEvent(up.side, up.ev_ready[4 * l + i], 0);
+      Run rs = r;
+      rs.st = up.side;
+      wgrad(rs, params, grads, l, i, dy, codes);
+      (void)hipEventRecord(up.ev_done[4 * l + i], up.side);
+    };
+    auto before_overwrite = [&](int i) {
+      if (up.side && l < L - 1) (void)hipStreamWaitEvent(r.st, up.ev_done[4 * (l + 1) + i], 0);
+    };
     // second LayerNorm: dy = [dr1 + dxh*mask of the layer above] + gradient of this layer's Eq. 3 term,
     // which the same kernel forms from the two layer outputs (it also returns the squared-error sum)
     {
@@ -435,6 +454,7 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       const float scale = c->cfg.loss_mean ? 1.0f / (float)numel : 1.0f;
       const int wd = 3 * H + 2;
       float* parts = red.take((size_t)ln_bwd_parts(T) * wd);
+      before_overwrite(3);
       const int n = ln_bwd(c->dt, top ? nullptr : r.at(r.p.dr1), nullptr, top ? nullptr : r.at(r.p.dxh), fq, q_above, r.at(w.x1), r.at(w.y),
                            r.at<float>(w.mu2), r.at<float>(w.rstd2), base + c->foff[MREM_F_LN2_G], r.at(r.p.dr2), parts, T, H, r.st,
                            in_loss ? ffp : nullptr, scale);
@@ -446,23 +466,25 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       red.add(parts, n, wd, 3 * H + 1, 1, loss_out + 1 + l, in_loss ? scale : 0.f);
     }
     // second feed-forward projection
-    wgrad(r, params, grads, l, 3, r.at(r.p.dr2), r.at(w.gcodes));
+    issue_wgrad(3, r.at(r.p.dr2), r.at(w.gcodes));
     dgrad(r, l, 3, r.at(r.p.dr2), r.at(r.p.dgh));
     // GELU and its output quantizer
     {
       // the kernel also leaves the column sums of du per row slab: the bias gradient of the first projection
       float* parts = red.take(2048);
       float* cols = red.take((size_t)kColMaxParts * F);
+      before_overwrite(2);
       const ColGrid cg = gelu_quant_bwd(c->dt, r.at(r.p.dgh), r.at(w.u), r.at(r.p.du), T, F, make_q(c, params, l, 7), parts, cols, r.st);
       red.add(parts, cg.gx * cg.gy, 1, 0, 1, g + c->foff[MREM_F_S_A] + 7);
       red.add(cols, cg.gy, F, 0, F, g + c->foff[MREM_F_B_1]);
     }
     // first feed-forward projection
-    wgrad(r, params, grads, l, 2, r.at(r.p.du), r.at(w.x1codes));
+    issue_wgrad(2, r.at(r.p.du), r.at(w.x1codes));
     dgrad(r, l, 2, r.at(r.p.du), r.at(r.p.dx1h));
     // first LayerNorm: dy = dr2 (residual) + dx1h through the FFN-input quantizer
     {
       float* parts = red.take((size_t)ln_bwd_parts(T) * (3 * H + 2));
+      before_overwrite(1);
       const int n = ln_bwd(c->dt, r.at(r.p.dr2), nullptr, r.at(r.p.dx1h), r.at(w.x1), make_q(c, params, l, 6), x, r.at(w.o),
                            r.at<float>(w.mu1), r.at<float>(w.rstd1), base + c->foff[MREM_F_LN1_G], r.at(r.p.dr1), parts, T, H, r.st);
       const int wd = 3 * H + 2;
@@ -472,7 +494,7 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       red.add(parts, n, wd, 3 * H, 1, g + c->foff[MREM_F_S_A] + 6);
     }
     // attention output projection
-    wgrad(r, params, grads, l, 1, r.at(r.p.dr1), r.at(w.ctxcodes));
+    issue_wgrad(1, r.at(r.p.dr1), r.at(w.ctxcodes));
     dgrad(r, l, 1, r.at(r.p.dr1), r.at(r.p.dch));
     {
       float* parts = red.take(2048);
@@ -496,6 +518,7 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       // the kernel also leaves the column sums of dqkv per row slab: the bias gradient of the projection
       float* parts = red.take(2048 * 3);
       float* cols = red.take((size_t)kColMaxParts * 3 * H);
+      before_overwrite(0);
       const ColGrid cg = qkv_quant_bwd(c->dt, r.at(r.p.dqkvh), r.at(w.qkv), r.at(r.p.dqkv), T, H, aq.q, aq.k, aq.v, parts, cols, r.st);
       const int n = cg.gx * cg.gy;
       red.add(parts, n, 3, 0, 1, g + c->foff[MREM_F_S_A] + 1);
@@ -504,7 +527,7 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       red.add(cols, cg.gy, 3 * H, 0, 3 * H, g + c->foff[MREM_F_B_QKV]);
     }
     // query/key/value projection
-    wgrad(r, params, grads, l, 0, r.at(r.p.dqkv), r.at(w.xcodes));
+    issue_wgrad(0, r.at(r.p.dqkv), r.at(w.xcodes));
     dgrad(r, l, 0, r.at(r.p.dqkv), r.at(r.p.dxh));
     if (l == 0) {
       // nothing flows out of the module (Section 4.2); only the input quantizer's step needs dxh
@@ -731,9 +754,12 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
         hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess)
       return fail(ctx, MREM_EHIP, "mrem_module_step: cannot create the side stream");
     ctx->ev_layer.assign((size_t)ctx->L, nullptr);
-    for (hipEvent_t& e : ctx->ev_layer)
-      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess)
-        return fail(ctx, MREM_EHIP, "mrem_module_step: cannot create the side stream's events");
+    ctx->ev_ready.assign((size_t)ctx->L * 4, nullptr);
+    ctx->ev_done.assign((size_t)ctx->L * 4, nullptr);
+    for (std::vector<hipEvent_t>* evs : {&ctx->ev_layer, &ctx->ev_ready, &ctx->ev_done})
+      for (hipEvent_t& e : *evs)
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess)
+          return fail(ctx, MREM_EHIP, "mrem_module_step: cannot create the side stream's events");
     ctx->side_device = dev;
   }
   if (dev != ctx->side_device) return fail(ctx, MREM_EINVAL, "mrem_module_step: the context was first used on another device");
@@ -748,11 +774,15 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
   } else {
     teacher_forward(r, teacher, teacher_cache, x_fp, per_layer_fp, nullptr);
   }
+  // One fill for everything in the gradient buffer that is added into (split weight-gradient
+  // products) or never written (the slots of the fixed quantizer offsets); it goes first because
+  // this stream has time to spare while the full-precision pass runs beside it.
+  fill_f32(grads, 0.f, mrem_param_count(ctx), r.st);
   prepare_weights(r, params);
   student_forward(r, params, x_q, per_layer_q);
   if (fork) (void)hipStreamWaitEvent(r.st, ctx->ev_join, 0);
   const Update up{params, adam_m, adam_v, adam_arg(ctx, step_index, lr), grads_out != nullptr, fork ? ctx->side : nullptr,
-                  ctx->ev_layer.data(), ctx->ev_join};
+                  ctx->ev_layer.data(), ctx->ev_ready.data(), ctx->ev_done.data(), ctx->ev_join};
   student_backward(r, params, x_q, per_layer_fp, per_layer_q, grads, loss_out, up);
   update_vectors(r, up, grads);
   return finish(ctx, "mrem_module_step");
