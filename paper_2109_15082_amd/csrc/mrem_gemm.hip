@@ -613,10 +613,12 @@ static void launch_mfma_modes(const void* A, int lda, const void* B, int ldb, vo
                               hipStream_t st) {
   const int tiles = (M / 128) * (N / 128);
   if (e.out_f32) {
-    // Few tiles and a long contraction (weight gradients of the square projections): two
-    // k-slices.  Two atomic adds onto a zeroed fp32 value commute exactly, so the result
-    // does not depend on which slice arrives first.
-    const int splits = (tiles <= 256 && K >= 2048 && (K / kBK) % 2 == 0 && !e.gelu) ? 2 : 1;
+    // Tiles for at most half of the compute units and a long contraction (weight gradients of
+    // the square projections): two k-slices.  (Larger weight gradients run beside the rest of the
+    // backward pass, where a second slice only adds atomic traffic.)  Two atomic adds onto a
+    // zeroed fp32 value commute exactly, so the result does not depend on which slice arrives
+    // first.
+    const int splits = (tiles <= 128 && K >= 2048 && (K / kBK) % 2 == 0 && !e.gelu) ? 2 : 1;
     if (splits > 1 && !e.c_zeroed) fill_f32((float*)C, 0.f, (int64_t)M * ldc, st);
     launch_mfma<128, 128, 2, 2, AT, BT, kRegBK, float>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
   } else {
