@@ -152,7 +152,7 @@ def main():
         "config": {"workload": wl.name, "n_layers": wl.n_layers, "hidden": wl.hidden, "n_heads": wl.n_heads, "ffn": wl.ffn,
                    "seq_len": wl.seq, "batch": wl.batch, "w_bits": wl.w_bits, "a_bits": wl.a_bits,
                    "tokens_per_step": wl.tokens, "step_tflop": flops_total / 1e12, "loss_last_step": float(losses[0])},
-        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_k / gemm_nt_pc_k on bf16 operands (teacher forward, input and weight gradients)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_k on bf16 operands (teacher forward, input and weight gradients)",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(wl.name),
                      "traffic_unit": "bytes/launch",

@@ -324,233 +324,6 @@ static void launch_mfma(const void* A, int lda, const void* B, int ldb, void* C,
                      (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (TO*)C, ldc, M, N, K, e, tiles_m, tiles_n);
 }
 
-// ------------------------------------------------------------------------------
-// Producer/consumer variant.  Two extra wavefronts do nothing but move operand tiles
-// global -> LDS with the direct-to-LDS load (no registers involved), several k-steps
-// ahead of the WAVES_M x WAVES_N wavefronts that run the MFMAs; one s_barrier per
-// k-step hands a filled stage over and an emptied one back.  LDS rows are 128 bytes
-// (unpadded, as the direct load writes 1 KiB = 8 rows per instruction); the 16-byte
-// chunk c of row r is stored at slot c ^ ((r >> 1) & 7), which keeps the fragment
-// reads of 16 consecutive rows on distinct banks.
-// ------------------------------------------------------------------------------
-constexpr int kProducers = 2;
-
-__device__ __forceinline__ void wait_vmcnt_le(int n) {
-  // gfx9 encoding of s_waitcnt: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]
-  switch (n) {
-    case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
-    case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
-    case 16: __builtin_amdgcn_s_waitcnt(0x4F70); break;
-    case 24: __builtin_amdgcn_s_waitcnt(0x4F78); break;
-    case 32: __builtin_amdgcn_s_waitcnt(0x8F70); break;
-    case 48: __builtin_amdgcn_s_waitcnt(0xCF70); break;
-    default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
-  }
-}
-
-// TE: element type of A and B, bf16_t (values or integer codes, fp32 accumulation) or int8_t
-// (integer codes, exact int32 accumulation with the 32x32x32 int8 instruction).  A stage row is
-// 128 bytes either way: 64 bf16 or 128 int8 values of k.
-template <class TE>
-struct PcElem;
-template <>
-struct PcElem<bf16_t> {
-  typedef bf16x8_t frag_t;
-  typedef f32x16_t acc_t;
-  static __device__ __forceinline__ acc_t mfma(frag_t a, frag_t b, acc_t c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
-};
-template <>
-struct PcElem<int8_t> {
-  typedef i32x4_t frag_t;
-  typedef i32x16_t acc_t;
-  static __device__ __forceinline__ acc_t mfma(frag_t a, frag_t b, acc_t c) { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
-};
-
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, class TO, class TE>
-__global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + kProducers)) void gemm_nt_pc_k(const TE* __restrict__ A, int lda,
-                                                                                       const TE* __restrict__ B, int ldb,
-                                                                                       TO* __restrict__ C, int ldc, int M, int N, int K,
-                                                                                       Epilogue e, int tiles_m, int tiles_n) {
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-  constexpr int CE = 16 / (int)sizeof(TE);    // elements per 16-byte chunk
-  constexpr int SK = 128 / (int)sizeof(TE);   // k values per stage
-  typedef typename PcElem<TE>::frag_t frag_t;
-  typedef typename PcElem<TE>::acc_t acc_t;
-  constexpr int NCONS = WAVES_M * WAVES_N;
-  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
-  constexpr int MT = WM / 32, NT = WN / 32;
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE_BYTES = A_BYTES + B_BYTES;
-  constexpr int GROUPS = (BM + BN) / 8;            // direct loads (8 rows each) per stage
-  constexpr int PER_PROD = GROUPS / kProducers;    // ... per producer wavefront
-  static_assert(GROUPS % kProducers == 0 && PER_PROD * (STAGES - 1) <= 63, "outstanding loads must fit the 6-bit counter");
-
-  const int nblocks = tiles_m * tiles_n;
-  int pid = blockIdx.x;
-  if ((nblocks & 7) == 0) pid = (pid & 7) * (nblocks >> 3) + (pid >> 3);
-  constexpr int GROUP = 8;
-  const int group_sz = GROUP * tiles_n;
-  const int g = pid / group_sz;
-  const int first_m = g * GROUP;
-  const int gm = (tiles_m - first_m) < GROUP ? (tiles_m - first_m) : GROUP;
-  const int tm = first_m + (pid % group_sz) % gm;
-  const int tn = (pid % group_sz) / gm;
-  const int m0 = tm * BM, n0 = tn * BN;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // gridDim.y > 1: split-K, each y-slice accumulates its share of the k-steps into fp32 C with atomic adds
-  const int KT = K / SK / (int)gridDim.y;
-  const int kt0 = (int)blockIdx.y * KT;
-
-  if (wave >= NCONS) {
-    // ---------------- producer ----------------
-    // Rows of a stage are numbered 0 .. BM+BN-1 (A rows, then B rows); direct load `gi` moves
-    // rows 8*gi .. 8*gi+7.  Lane l writes slot l%8 of row 8*gi + l/8 and therefore fetches
-    // chunk (l%8) ^ ((row >> 1) & 7), which for even gi is (l%8) ^ (l/16) and for odd gi
-    // (l%8) ^ (4 + l/16).
-    const int pw = __builtin_amdgcn_readfirstlane(wave) - NCONS;
-    const int sub_row = lane >> 3, slot = lane & 7;
-    const int c_even = slot ^ (sub_row >> 1), c_odd = slot ^ (4 + (sub_row >> 1));
-    const size_t a_lane_even = (size_t)sub_row * lda + c_even * CE, a_lane_odd = (size_t)sub_row * lda + c_odd * CE;
-    const size_t b_lane_even = (size_t)sub_row * ldb + c_even * CE, b_lane_odd = (size_t)sub_row * ldb + c_odd * CE;
-    const TE* Ablk = A + (size_t)m0 * lda;
-    const TE* Bblk = B + (size_t)n0 * ldb;
-#define MREM_ISSUE_STAGE(kt_)                                                                                      \
-    {                                                                                                              \
-      unsigned char* stage_ = smem_raw + ((kt_) % STAGES) * STAGE_BYTES;                                           \
-      const int k0_ = (kt0 + (kt_)) * SK;                                                                                \
-      _Pragma("unroll") for (int i = 0; i < PER_PROD; ++i) {                                                       \
-        const int gi = pw * PER_PROD + i;                                                                          \
-        const TE* src;                                                                                             \
-        if (gi < BM / 8) src = Ablk + (size_t)(8 * gi) * lda + k0_ + ((gi & 1) ? a_lane_odd : a_lane_even);        \
-        else src = Bblk + (size_t)(8 * (gi - BM / 8)) * ldb + k0_ + ((gi & 1) ? b_lane_odd : b_lane_even);         \
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,                       \
-                                         (__attribute__((address_space(3))) void*)(stage_ + gi * 1024), 16, 0, 0);  \
-      }                                                                                                            \
-    }
-    const int pre = KT < STAGES - 1 ? KT : STAGES - 1;
-    for (int s = 0; s < pre; ++s) MREM_ISSUE_STAGE(s)
-    if (pre == STAGES - 1) wait_vmcnt_le(PER_PROD * (STAGES - 2)); else wait_vmcnt_le(0);
-    __builtin_amdgcn_s_barrier();
-    for (int kt = 0; kt < KT; ++kt) {
-      if (kt + STAGES - 1 < KT) {
-        MREM_ISSUE_STAGE(kt + STAGES - 1)
-        wait_vmcnt_le(PER_PROD * (STAGES - 2));
-      } else {
-        wait_vmcnt_le(0);
-      }
-      __builtin_amdgcn_s_barrier();
-    }
-#undef MREM_ISSUE_STAGE
-    return;
-  }
-
-  // ---------------- consumers ----------------
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  acc_t acc[MT][NT];
-#pragma unroll
-  for (int i = 0; i < MT; ++i)
-#pragma unroll
-    for (int j = 0; j < NT; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-  const int frag_row = lane & 31, half = lane >> 5;
-  // byte offsets of this lane's fragment rows inside a stage, and its swizzle term per MFMA tile
-  int a_off[MT], b_off[NT], a_sw[MT], b_sw[NT];
-#pragma unroll
-  for (int i = 0; i < MT; ++i) { const int r = wm * WM + i * 32 + frag_row; a_off[i] = r * 128; a_sw[i] = (r >> 1) & 7; }
-#pragma unroll
-  for (int j = 0; j < NT; ++j) { const int r = wn * WN + j * 32 + frag_row; b_off[j] = A_BYTES + r * 128; b_sw[j] = (r >> 1) & 7; }
-
-  // The barriers below carry no memory fence on purpose (a fence would make the producers wait
-  // for all their loads in flight); LDS itself is coherent within the workgroup, the asm
-  // statements keep the compiler from moving LDS reads across the barrier.
-  //
-  // Fragment reads run one k-substep (16 of the 64 columns of a stage) ahead of the MFMAs that
-  // use them; the reads of the first substep of the next stage are issued right after the
-  // barrier that hands that stage over, under the last MFMAs of the current one.
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_barrier();  // stage 0 has landed
-  asm volatile("" ::: "memory");
-  frag_t af[2][MT], bfr[2][NT];
-#define MREM_READ_FRAGS(buf, stage_ptr, kk_)                                                                       \
-  {                                                                                                                \
-    const int c_ = 2 * (kk_) + half;                                                                               \
-    _Pragma("unroll") for (int i = 0; i < MT; ++i)                                                                 \
-        af[buf][i] = *reinterpret_cast<const frag_t*>((stage_ptr) + a_off[i] + ((c_ ^ a_sw[i]) << 4));           \
-    _Pragma("unroll") for (int j = 0; j < NT; ++j)                                                                 \
-        bfr[buf][j] = *reinterpret_cast<const frag_t*>((stage_ptr) + b_off[j] + ((c_ ^ b_sw[j]) << 4));          \
-  }
-#define MREM_MFMAS(buf)                                                                                            \
-  {                                                                                                                \
-    _Pragma("unroll") for (int i = 0; i < MT; ++i)                                                                 \
-        _Pragma("unroll") for (int j = 0; j < NT; ++j)                                                             \
-            acc[i][j] = PcElem<TE>::mfma(af[buf][i], bfr[buf][j], acc[i][j]);             \
-  }
-  MREM_READ_FRAGS(0, smem_raw, 0)
-  for (int kt = 0; kt < KT; ++kt) {
-    const unsigned char* stage = smem_raw + (kt % STAGES) * STAGE_BYTES;
-    const unsigned char* next_stage = smem_raw + ((kt + 1) % STAGES) * STAGE_BYTES;
-    MREM_READ_FRAGS(1, stage, 1)
-    MREM_MFMAS(0)
-    MREM_READ_FRAGS(0, stage, 2)
-    MREM_MFMAS(1)
-    MREM_READ_FRAGS(1, stage, 3)
-    MREM_MFMAS(0)
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // all fragment reads of this stage are done
-    __builtin_amdgcn_s_barrier();                       // this stage is free again; the next one has landed
-    asm volatile("" ::: "memory");
-    if (kt + 1 < KT) MREM_READ_FRAGS(0, next_stage, 0)
-    MREM_MFMAS(1)
-  }
-#undef MREM_READ_FRAGS
-#undef MREM_MFMAS
-
-  const float alpha = e.alpha ? *e.alpha : 1.f;
-  const float beta = (e.beta ? *e.beta : 0.f) + e.beta_alpha * alpha;
-  const bool split = gridDim.y > 1, lead = blockIdx.y == 0;  // the additive terms go in once, with slice 0
-#pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    const int n = n0 + wn * WN + j * 32 + (lane & 31);
-    const float cs = alpha * (e.col_scale ? e.col_scale[n] : 1.f);
-    float cb = (e.bias && lead) ? e.bias[n] : 0.f;
-    if (e.beta && e.col_vec && lead) cb += beta * e.col_vec[n];
-#pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      const int mb = m0 + wm * WM + i * 32 + 4 * (lane >> 5);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = mb + 8 * (r >> 2) + (r & 3);
-        float v = (float)acc[i][j][r] * cs + cb;
-        if (e.beta && e.row_vec && lead) v += beta * e.row_vec[m];
-        if constexpr (sizeof(TO) == 4) {
-          if (split) {
-            atomicAdd(reinterpret_cast<float*>(C) + (size_t)m * ldc + n, v);
-            continue;
-          }
-        }
-        if (e.gelu) v = gelu_t<TO>(round_to<TO>(v));
-        stf(C, (size_t)m * ldc + n, v);
-      }
-    }
-  }
-}
-
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, class TO, class TE = bf16_t>
-static void launch_pc(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
-                      hipStream_t st, int k_splits = 1) {
-  constexpr size_t lds = (size_t)STAGES * (BM + BN) * 128;
-  static bool configured = false;
-  if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_pc_k<BM, BN, WAVES_M, WAVES_N, STAGES, TO, TE>),
-                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    configured = true;
-  }
-  const int tiles_m = M / BM, tiles_n = N / BN;
-  hipLaunchKernelGGL((gemm_nt_pc_k<BM, BN, WAVES_M, WAVES_N, STAGES, TO, TE>), dim3(tiles_m * tiles_n, k_splits),
-                     dim3(64 * (WAVES_M * WAVES_N + kProducers)), lds, st, (const TE*)A, lda, (const TE*)B, ldb, (TO*)C, ldc, M, N, K,
-                     e, tiles_m, tiles_n);
-}
-
 static bool mfma_ok(const void* A, int lda, const void* B, int ldb, int M, int N, int K) {
   return M % 128 == 0 && N % 128 == 0 && K % kBK == 0 && lda % 8 == 0 && ldb % 8 == 0 &&
          (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (reinterpret_cast<uintptr_t>(B) & 15) == 0;
@@ -579,13 +352,11 @@ bool gemm_i8_ok(const void* A, int lda, const void* B, int ldb, int M, int N, in
   return M % 128 == 0 && N % 128 == 0 && K % 128 == 0 && lda % 16 == 0 && ldb % 16 == 0 &&
          (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (reinterpret_cast<uintptr_t>(B) & 15) == 0;
 }
-// Measured on MI355X: the producer/consumer kernel for one-tile-per-CU shapes, two co-resident
-// blocks of the register-staged kernel when a compute unit works through several tiles.
+// The register-staged kernel in its int8 mode: two int8 codes travel as one 16-bit element, so
+// leading dimensions and the contraction length are halved.
 static void gemm_i8_launch(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
                            hipStream_t st) {
-  const int tiles = (M / 128) * (N / 128);
-  if (tiles <= 256) launch_pc<128, 128, 2, 2, 3, bf16_t, int8_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
-  else launch_mfma<128, 128, 2, 2, false, false, kRegBK, bf16_t, true>(A, lda / 2, B, ldb / 2, C, ldc, M, N, K / 2, e, st);
+  launch_mfma<128, 128, 2, 2, false, false, kRegBK, bf16_t, true>(A, lda / 2, B, ldb / 2, C, ldc, M, N, K / 2, e, st);
 }
 void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e, hipStream_t st) {
   if (!g_prof_on) {
@@ -629,17 +400,8 @@ static void launch_mfma_modes(const void* A, int lda, const void* B, int ldb, vo
 static void gemm_launch(int dt, int a_t, int b_t, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
                         const Epilogue& e, hipStream_t st) {
   if (dt == DT_BF16 && mfma_ok(A, lda, B, ldb, M, N, K)) {
-    const int tiles = (M / 128) * (N / 128);
     if (!a_t && !b_t) {
-      // Measured on MI355X: with at most one 128x128 tile per compute unit the producer/consumer
-      // kernel (three stages in flight) is faster; with two or more tiles per compute unit two
-      // co-resident blocks of the register-staged kernel hide each other's latencies better.
-      if (tiles <= 256) {
-        if (e.out_f32) launch_pc<128, 128, 2, 2, 3, float>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
-        else launch_pc<128, 128, 2, 2, 3, bf16_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
-      } else {
-        launch_mfma_modes<false, false>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
-      }
+      launch_mfma_modes<false, false>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
     } else if (!a_t && b_t) {
       launch_mfma_modes<false, true>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
     } else if (a_t && b_t) {
