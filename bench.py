@@ -24,7 +24,7 @@ MFMA_INT8_PEAK_TOPS = 5000.0
 # HBM bytes per matrix-product launch (read + written), from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE), each scaled by what the counter reads for a 256 MiB device copy; summary with the commands in
 # profiles/module_step_bert_large_6l_hbm_traffic.md.  Only for the workload it was measured on.
-MEASURED_GEMM_TRAFFIC_BYTES = {"bert_large_6l": 84.3e6}
+MEASURED_GEMM_TRAFFIC_BYTES = {"bert_large_6l": 81.6e6}
 
 
 def step_flops(wl):
@@ -122,11 +122,12 @@ def main():
         t += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    # pass 2, the same K steps again with a HIP event pair around every matrix-product launch (on the
-    # stream the products run on).  Kept out of pass 1 because each recorded event stalls the queue for
-    # about 5 us, which with 96 products a step would add about a millisecond to every step.  In this
-    # pass the library also keeps the teacher's forward pass on the caller's stream (in pass 1 it runs on
-    # a side stream next to the quantized forward pass), so that every product is timed alone.
+    # pass 2, the same K steps again with a HIP event pair on every matrix-product launch (the pair the
+    # launch itself carries: kernel begin and end, on the stream the product runs on).  Kept out of
+    # pass 1 because a timed launch still costs the queue a few microseconds, which with 96 products a
+    # step adds up, and because in this pass the library keeps everything on the caller's stream (in
+    # pass 1 the full-precision forward pass, the weight-gradient products and the per-layer updates run
+    # on a side stream beside the rest), so that every product is timed alone.
     B.mrem_profile_gemm_begin()
     t1 = time.perf_counter()
     for _ in range(args.steps):
@@ -167,7 +168,7 @@ def main():
                      "all_products": {"achieved": all_flops / (all_ms * 1e-3) / 1e12 if all_ms > 0 else 0.0, "peak": MFMA_BF16_PEAK_TFLOPS,
                                       "unit": "TFLOP/s", "frac": (all_flops / (all_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS) if all_ms > 0 else 0.0,
                                       "launches_per_step": all_launches / args.steps, "ms_per_step": all_ms / args.steps},
-                     "measured_on": "a second pass of the same K steps with an event pair around every product launch",
+                     "measured_on": "a second pass of the same K steps, one stream, with a HIP event pair (kernel begin, kernel end) on every product launch",
                      "ms_per_step_with_events": dt_events * 1e3 / args.steps,
                      "flops_per_launch": gemm_flops / max(gemm_launches, 1)},
         "step_tflops": flops_total / 1e12 / (ms_per_step * 1e-3),

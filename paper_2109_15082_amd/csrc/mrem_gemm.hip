@@ -5,6 +5,8 @@
 #include "mrem_common.h"
 #include "mrem_kernels.h"
 
+#include <hip/hip_ext.h>
+
 #include <type_traits>
 
 #include <vector>
@@ -22,6 +24,10 @@ struct GemmRecord {
 };
 bool g_prof_on = false;
 std::vector<GemmRecord> g_prof;
+// While a timed launch is being issued: the event pair that the launch itself carries (the
+// runtime stamps them with the kernel's own begin and end, so no packet is added to the queue
+// and the elapsed time is the kernel's duration).
+hipEvent_t g_launch_e0 = nullptr, g_launch_e1 = nullptr;
 }  // namespace
 
 bool gemm_profile_active() { return g_prof_on; }
@@ -320,6 +326,12 @@ static void launch_mfma(const void* A, int lda, const void* B, int ldb, void* C,
     configured = true;
   }
   const int tiles_m = M / BM, tiles_n = N / BN;
+  if (g_launch_e0) {
+    hipExtLaunchKernelGGL((gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, BK, TO, I8>), dim3(tiles_m * tiles_n, k_splits), dim3(NTHREADS),
+                          lds, st, g_launch_e0, g_launch_e1, 0, (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (TO*)C, ldc, M, N, K, e,
+                          tiles_m, tiles_n);
+    return;
+  }
   hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, BK, TO, I8>), dim3(tiles_m * tiles_n, k_splits), dim3(NTHREADS), lds, st,
                      (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (TO*)C, ldc, M, N, K, e, tiles_m, tiles_n);
 }
@@ -342,9 +354,10 @@ void gemm(int dt, int a_t, int b_t, const void* A, int lda, const void* B, int l
   r.flops = 2.0 * (double)M * (double)N * (double)K;
   (void)hipEventCreate(&r.e0);
   (void)hipEventCreate(&r.e1);
-  (void)hipEventRecord(r.e0, st);
+  g_launch_e0 = r.e0;
+  g_launch_e1 = r.e1;
   gemm_launch(dt, a_t, b_t, A, lda, B, ldb, C, ldc, M, N, K, e, st);
-  (void)hipEventRecord(r.e1, st);
+  g_launch_e0 = g_launch_e1 = nullptr;
   g_prof.push_back(r);
 }
 
@@ -367,9 +380,10 @@ void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, i
   r.flops = 2.0 * (double)M * (double)N * (double)K;
   (void)hipEventCreate(&r.e0);
   (void)hipEventCreate(&r.e1);
-  (void)hipEventRecord(r.e0, st);
+  g_launch_e0 = r.e0;
+  g_launch_e1 = r.e1;
   gemm_i8_launch(A, lda, B, ldb, C, ldc, M, N, K, e, st);
-  (void)hipEventRecord(r.e1, st);
+  g_launch_e0 = g_launch_e1 = nullptr;
   r.cls = 1;
   g_prof.push_back(r);
 }
@@ -412,6 +426,8 @@ static void gemm_launch(int dt, int a_t, int b_t, const void* A, int lda, const 
     return;
   }
   dim3 g((N + 63) / 64, (M + 63) / 64);
+  const hipEvent_t t0 = g_launch_e0, t1 = g_launch_e1;  // the fallback kernels are timed by recorded events
+  if (t0) (void)hipEventRecord(t0, st);
   if (dt == DT_BF16) {
     if (e.out_f32)
       hipLaunchKernelGGL((gemm_nt_simt_k<bf16_t, float>), g, dim3(256), 0, st, (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (float*)C, ldc,
@@ -423,6 +439,7 @@ static void gemm_launch(int dt, int a_t, int b_t, const void* A, int lda, const 
     hipLaunchKernelGGL((gemm_nt_simt_k<float, float>), g, dim3(256), 0, st, (const float*)A, lda, (const float*)B, ldb, (float*)C, ldc, M,
                        N, K, e, a_t, b_t);
   }
+  if (t1) (void)hipEventRecord(t1, st);
 }
 
 }  // namespace mrem
