@@ -269,12 +269,14 @@ void prepare_weights(const Run& r, const float* params) {
   weight_prepare(c->dt, jobs.data(), (int)jobs.size(), c->cfg.w_bits, r.st);
 }
 
-void student_forward(const Run& r, const float* params, const void* x_q, void* per_layer_q) {
+// Layers [l0, l1) of the quantized module (l1 < 0: to the last layer).
+void student_forward(const Run& r, const float* params, const void* x_q, void* per_layer_q, int l0 = 0, int l1 = -1) {
   const mrem_ctx* c = r.c;
   const size_t es = dt_size(c->dt);
   const int H = c->H, F = c->F, T = r.T;
   const size_t slice = (size_t)T * H * es;
-  for (int l = 0; l < c->L; ++l) {
+  if (l1 < 0) l1 = c->L;
+  for (int l = l0; l < l1; ++l) {
     const LayerWs& w = r.p.lw[l];
     const float* base = params + c->layer_stride * l;
     const void* x = l == 0 ? x_q : (const char*)per_layer_q + slice * (l - 1);
@@ -315,7 +317,9 @@ void student_forward(const Run& r, const float* params, const void* x_q, void* p
 
 // Full-precision module.  With calib_params != null the clipping ranges of the
 // eight activation quantizers of every layer are derived on the way.
-void teacher_forward(const Run& r, const float* teacher, const void* cache, const void* x_fp, void* per_layer_fp, float* calib_params) {
+// Layers [l0, l1) (l1 < 0: to the last layer).
+void teacher_forward(const Run& r, const float* teacher, const void* cache, const void* x_fp, void* per_layer_fp, float* calib_params,
+                     int l0 = 0, int l1 = -1) {
   const mrem_ctx* c = r.c;
   const size_t es = dt_size(c->dt);
   const int H = c->H, F = c->F, T = r.T;
@@ -328,7 +332,8 @@ void teacher_forward(const Run& r, const float* teacher, const void* cache, cons
     const int n = absminmax(dt, a, rows, cols, ld, gelu, parts, r.st);
     calib_finalize(parts, n, mode, mode == 0 ? qp_s : qp_u, base + c->foff[MREM_F_S_A] + idx, base + c->foff[MREM_F_Z_A] + idx, r.st);
   };
-  for (int l = 0; l < c->L; ++l) {
+  if (l1 < 0) l1 = c->L;
+  for (int l = l0; l < l1; ++l) {
     const float* base = teacher + c->layer_stride * l;
     const char* wc = (const char*)cache + (size_t)c->tc_layer_stride * l * es;
     auto W = [&](int i) { return (const void*)(wc + (size_t)c->tc_off[i] * es); };
@@ -764,22 +769,28 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
   }
   if (dev != ctx->side_device) return fail(ctx, MREM_EINVAL, "mrem_module_step: the context was first used on another device");
   const bool fork = !gemm_profile_active();  // per-launch timing wants every product alone on the device
+  // Before the passes: one fill for everything in the gradient buffer that is added into (split
+  // weight-gradient products) or never written (the slots of the fixed quantizer offsets).
   if (fork) {
     Run rt = r;
     rt.st = ctx->side;
     (void)hipEventRecord(ctx->ev_fork, r.st);
     (void)hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
-    teacher_forward(rt, teacher, teacher_cache, x_fp, per_layer_fp, nullptr);
+    fill_f32(grads, 0.f, mrem_param_count(ctx), r.st);
+    prepare_weights(r, params);
+    // the two passes are enqueued layer by layer in turn, so that both streams have work from the
+    // start also when the caller's queue was empty
+    for (int l = 0; l < ctx->L; ++l) {
+      teacher_forward(rt, teacher, teacher_cache, x_fp, per_layer_fp, nullptr, l, l + 1);
+      student_forward(r, params, x_q, per_layer_q, l, l + 1);
+    }
     (void)hipEventRecord(ctx->ev_join, ctx->side);
   } else {
     teacher_forward(r, teacher, teacher_cache, x_fp, per_layer_fp, nullptr);
+    fill_f32(grads, 0.f, mrem_param_count(ctx), r.st);
+    prepare_weights(r, params);
+    student_forward(r, params, x_q, per_layer_q);
   }
-  // One fill for everything in the gradient buffer that is added into (split weight-gradient
-  // products) or never written (the slots of the fixed quantizer offsets); it goes first because
-  // this stream has time to spare while the full-precision pass runs beside it.
-  fill_f32(grads, 0.f, mrem_param_count(ctx), r.st);
-  prepare_weights(r, params);
-  student_forward(r, params, x_q, per_layer_q);
   if (fork) (void)hipStreamWaitEvent(r.st, ctx->ev_join, 0);
   const Update up{params, adam_m, adam_v, adam_arg(ctx, step_index, lr), grads_out != nullptr, fork ? ctx->side : nullptr,
                   ctx->ev_layer.data(), ctx->ev_ready.data(), ctx->ev_done.data(), ctx->ev_join};
