@@ -218,6 +218,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_k(const bf16_t* __restrict_
 // row statistics, forms dP^ = dC * V^T, applies the straight-through rule of the
 // probability quantizer, the softmax backward, and dQ^ = dA * K^.  Writes the transposed
 // tiles P^T[key][query] and dA^T[key][query] (bf16) for the key-major kernel.
+// NT > 0: rows of at most NT key tiles, kept in registers; NT = 0: any length, tiles formed twice.
 // ------------------------------------------------------------------------------
 template <int NT>
 __global__ __launch_bounds__(256) void attn_bwd_q_mfma_k(const bf16_t* __restrict__ codes, const bf16_t* __restrict__ dctx,
@@ -268,59 +269,89 @@ __global__ __launch_bounds__(256) void attn_bwd_q_mfma_k(const bf16_t* __restric
     for (int r = 0; r < 16; ++r) dqacc[et][r] = 0.f;
   const size_t tbase = ((size_t)b * nh + h) * s_pad * s_pad;
 
-  // phase 0 accumulates rowdot = sum_j dP[q][j] * P[q][j]; phase 1 forms dA and consumes it
-#pragma unroll 1
-  for (int phase = 0; phase < 2; ++phase) {
-#pragma unroll 1
-    for (int t = 0; t < nt; ++t) {
-      f32x16_t sacc, dacc;
+  // one tile of 32 keys: P (recomputed with the rounding steps of the forward) and dP after the
+  // straight-through rule of the probability quantizer; adds the tile's terms to dsp when asked
+  auto probs = [&](int t, float* p_out, float* dp_out, bool add_dsp) {
+    f32x16_t sacc, dacc;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[r] = dacc[r] = 0.f;
-      const bf16_t* kp = Ks + (32 * t + (lane & 31)) * kRowStride + half * 8;
-      const bf16_t* vp = Vs + (32 * t + (lane & 31)) * kRowStride + half * 8;
+    for (int r = 0; r < 16; ++r) sacc[r] = dacc[r] = 0.f;
+    const bf16_t* kp = Ks + (32 * t + (lane & 31)) * kRowStride + half * 8;
+    const bf16_t* vp = Vs + (32 * t + (lane & 31)) * kRowStride + half * 8;
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(kp + kk * 16), qf[kk], sacc, 0, 0, 0);
-        dacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(vp + kk * 16), cf[kk], dacc, 0, 0, 0);
+    for (int kk = 0; kk < 4; ++kk) {
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(kp + kk * 16), qf[kk], sacc, 0, 0, 0);
+      dacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(vp + kk * 16), cf[kk], dacc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int j = key_of(t, r, half);
+      const float p = j < len ? div_by(__expf(__fsub_rn(__fmul_rn(sacc[r], sc.qk), mx)), inv_l, rl) : 0.f;
+      const float dph = dacc[r] * sc.sv;
+      float dp = dph;
+      if (sc.p_on) {
+        const float v = div_by(p, sc.sp, sc.rsp);
+        const bool in = v <= sc.p_qp;
+        if (add_dsp) dsp += dph * (rintf(fminf(v, sc.p_qp)) - (in ? v : 0.f));
+        dp = in ? dph : 0.f;
       }
-      float pcode[16], da[16];
+      p_out[r] = p;
+      dp_out[r] = dp;
+    }
+  };
+  // the same tile once rowdot = sum_j dP[q][j] * P[q][j] is known: dA = P * (dP - rowdot), the
+  // transposed tiles for the key-major kernel, and the tile's share of dQ^ = dA * K^
+  auto consume = [&](int t, const float* p_in, const float* dp_in) {
+    float da[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = key_of(t, r, half);
-        const float p = j < len ? div_by(__expf(__fsub_rn(__fmul_rn(sacc[r], sc.qk), mx)), inv_l, rl) : 0.f;  // same rounding steps as the forward
-        const float dph = dacc[r] * sc.sv;
-        float dp = dph, c = p;
-        if (sc.p_on) {
-          const float v = div_by(p, sc.sp, sc.rsp);
-          const bool in = v <= sc.p_qp;
-          c = rintf(fminf(v, sc.p_qp));
-          if (phase == 0) dsp += dph * (c - (in ? v : 0.f));
-          dp = in ? dph : 0.f;
-        }
-        if (phase == 0) rowdot += dp * p;
-        pcode[r] = c;
-        da[r] = p * (dp - rowdot);
-      }
-      if (phase == 1) {
+    for (int r = 0; r < 16; ++r) {
+      const float p = p_in[r];
+      const float c = sc.p_on ? rintf(fminf(div_by(p, sc.sp, sc.rsp), sc.p_qp)) : p;
+      da[r] = p * (dp_in[r] - rowdot);
+      const int j = key_of(t, r, half);
+      const size_t o = tbase + (size_t)j * s_pad + q;
+      pt_out[o] = static_cast<bf16_t>(qvalid ? c : 0.f);
+      dat_out[o] = static_cast<bf16_t>(qvalid ? da[r] : 0.f);
+    }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = key_of(t, r, half);
-          const size_t o = tbase + (size_t)j * s_pad + q;
-          pt_out[o] = static_cast<bf16_t>(qvalid ? pcode[r] : 0.f);
-          dat_out[o] = static_cast<bf16_t>(qvalid ? da[r] : 0.f);
-        }
+    for (int s = 0; s < 2; ++s) {
+      bf16x8_t af;
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-          bf16x8_t af;
+      for (int i = 0; i < 8; ++i) af[i] = static_cast<bf16_t>(da[8 * s + i]);
+      const int k0 = 32 * t + 16 * s + 4 * half;
+      dqacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_tr(Ks, 0, k0, k0 + 8, lane), af, dqacc[0], 0, 0, 0);
+      dqacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_tr(Ks, 32, k0, k0 + 8, lane), af, dqacc[1], 0, 0, 0);
+    }
+  };
+  if constexpr (NT > 0) {
+    // at most NT key tiles: P and dP of the whole row stay in registers between the two passes
+    float pk[NT][16], dpk[NT][16];
 #pragma unroll
-          for (int i = 0; i < 8; ++i) af[i] = static_cast<bf16_t>(da[8 * s + i]);
-          const int k0 = 32 * t + 16 * s + 4 * half;
-          dqacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_tr(Ks, 0, k0, k0 + 8, lane), af, dqacc[0], 0, 0, 0);
-          dqacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_tr(Ks, 32, k0, k0 + 8, lane), af, dqacc[1], 0, 0, 0);
-        }
+    for (int t = 0; t < NT; ++t) {
+      if (t < nt) {
+        probs(t, pk[t], dpk[t], true);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) rowdot += dpk[t][r] * pk[t][r];
       }
     }
-    if (phase == 0) rowdot += __shfl_xor(rowdot, 32, 64);
+    rowdot += __shfl_xor(rowdot, 32, 64);
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+      if (t < nt) consume(t, pk[t], dpk[t]);
+  } else {
+    // longer rows: the tiles are formed twice, first for rowdot (and dsp), then to be consumed
+    float pt[16], dpt[16];
+#pragma unroll 1
+    for (int t = 0; t < nt; ++t) {
+      probs(t, pt, dpt, true);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) rowdot += dpt[r] * pt[r];
+    }
+    rowdot += __shfl_xor(rowdot, 32, 64);
+#pragma unroll 1
+    for (int t = 0; t < nt; ++t) {
+      probs(t, pt, dpt, false);
+      consume(t, pt, dpt);
+    }
   }
   // step-size gradient terms of the probability quantizer (padded query rows excluded)
   dsp = wave_sum(qvalid ? dsp : 0.f);
@@ -433,11 +464,16 @@ int attn_bwd_mfma(const void* codes, const void* dctx, void* d_qkvh, const AttnQ
   static size_t configured = 0;
   if (lds > configured) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_q_mfma_k<4>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_q_mfma_k<0>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     configured = lds;
   }
   dim3 gq((s_pad + 127) / 128, nh, B);
-  hipLaunchKernelGGL(attn_bwd_q_mfma_k<4>, gq, dim3(256), lds, st, (const bf16_t*)codes, (const bf16_t*)dctx, (bf16_t*)d_qkvh, aq, seqlens,
-                     S, nh * kD, nt, stat_m, stat_l, (bf16_t*)pt_scratch, (bf16_t*)dat_scratch, ds_parts);
+  if (nt <= 4)
+    hipLaunchKernelGGL(attn_bwd_q_mfma_k<4>, gq, dim3(256), lds, st, (const bf16_t*)codes, (const bf16_t*)dctx, (bf16_t*)d_qkvh, aq,
+                       seqlens, S, nh * kD, nt, stat_m, stat_l, (bf16_t*)pt_scratch, (bf16_t*)dat_scratch, ds_parts);
+  else
+    hipLaunchKernelGGL(attn_bwd_q_mfma_k<0>, gq, dim3(256), lds, st, (const bf16_t*)codes, (const bf16_t*)dctx, (bf16_t*)d_qkvh, aq,
+                       seqlens, S, nh * kD, nt, stat_m, stat_l, (bf16_t*)pt_scratch, (bf16_t*)dat_scratch, ds_parts);
   dim3 gk((nt + 3) / 4, nh, B);
   hipLaunchKernelGGL(attn_bwd_k_mfma_k, gk, dim3(256), 0, st, (const bf16_t*)codes, (const bf16_t*)dctx, (bf16_t*)d_qkvh, aq, S, nh * kD, nt,
                      (const bf16_t*)pt_scratch, (const bf16_t*)dat_scratch);
