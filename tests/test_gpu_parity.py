@@ -288,6 +288,39 @@ def test_forward_entry_matches_step_outputs_and_is_deterministic(B):
     mod.close()
 
 
+def test_steps_back_to_back_equal_steps_with_synchronisation(B):
+    """The step forks work onto a stream of its own and joins it again; consecutive steps queued
+    without any host synchronisation, on the default stream or on another one, must leave exactly
+    the state that fully synchronised steps leave (parameters, moments, losses, outputs)."""
+    torch = _torch()
+    wl = CASES_BF16["aligned_bf16"]
+    case = Hh.make_case(wl)
+    x, sl = Hh.device_inputs(case)
+    xs = [x, (x * 0.5).contiguous(), (x * 1.5).contiguous()]
+
+    def run(mode):
+        mod = Hh.device_module(case)
+        losses, outs = [], None
+        stream = torch.cuda.Stream() if mode == "other_stream" else torch.cuda.current_stream()
+        stream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(stream):
+            for t in range(6):
+                outs = mod.step(xs[t % 3], xs[t % 3], 1e-3 * (1 - t / 6), sl)
+                losses.append(mod.loss.clone())
+                if mode == "synchronised":
+                    torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        state = (mod.params.clone(), mod.adam_m.clone(), mod.adam_v.clone(), torch.stack(losses), outs[0].clone(), outs[1].clone())
+        mod.close()
+        return state
+
+    ref = run("synchronised")
+    for mode in ("back_to_back", "other_stream"):
+        got = run(mode)
+        for a, b in zip(ref, got):
+            assert torch.equal(a, b), mode
+
+
 def test_calibrate_and_init_steps_match_oracle(B):
     torch = _torch()
     for name, wl in (("mid_f32", MID_F32), ("mid_bf16", CASES_BF16["mid_bf16"])):
