@@ -391,7 +391,7 @@ void wgrad(const Run& r, const float* params, float* grads, int l, int i, const 
   const QArg q = make_q(c, params, l, kInQuant[i]);
   if (q.on) e.alpha = q.s;  // the offset term z * db[n] of an asymmetric input quantizer is added by the update kernel
   e.out_f32 = 1;
-  e.c_zeroed = 1;  // the step starts by zeroing the whole gradient buffer
+  e.c_zeroed = 1;  // the step starts by zeroing the gradients that are formed in k-slices
   gemm(c->dt, 1, 1, dy, c->wN[i], codes_in, c->wK[i], g + c->foff[kWField[i]], c->wK[i], c->wN[i], c->wK[i], r.T, e, r.st);
 }
 // input-gradient product: d(in^) = dY * W^ with the dequantized weights [N_out, K_in]
@@ -399,6 +399,21 @@ void dgrad(const Run& r, int l, int i, const void* dy, void* out) {
   const mrem_ctx* c = r.c;
   Epilogue e;
   gemm(c->dt, 0, 1, dy, c->wN[i], r.at(r.p.lw[l].what[i]), c->wK[i], out, c->wK[i], r.T, c->wK[i], c->wN[i], e, r.st);
+}
+
+// Zeroes what the backward pass adds into (weight gradients formed in two k-slices) or never
+// writes (the slots of the fixed quantizer offsets; the vectors of a layer are one region).
+void zero_gradient_slots(const Run& r, float* grads) {
+  const mrem_ctx* c = r.c;
+  std::vector<FillRegion> regions;
+  for (int l = 0; l < c->L; ++l) {
+    float* g = grads + c->layer_stride * l;
+    regions.push_back(FillRegion{g + c->foff[MREM_F_B_QKV], c->layer_stride - c->foff[MREM_F_B_QKV]});
+    for (int i = 0; i < 4; ++i)
+      if (gemm_f32_k_slices(c->dt, c->wN[i], c->wK[i], r.T) > 1)
+        regions.push_back(FillRegion{g + c->foff[kWField[i]], (int64_t)c->wN[i] * c->wK[i]});
+  }
+  zero_regions(regions.data(), (int)regions.size(), r.st);
 }
 
 // What the backward pass needs to update the weight matrices of a layer as soon as that layer's
@@ -769,14 +784,13 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
   }
   if (dev != ctx->side_device) return fail(ctx, MREM_EINVAL, "mrem_module_step: the context was first used on another device");
   const bool fork = !gemm_profile_active();  // per-launch timing wants every product alone on the device
-  // Before the passes: one fill for everything in the gradient buffer that is added into (split
-  // weight-gradient products) or never written (the slots of the fixed quantizer offsets).
+  // Before the passes: the gradient slots that are added into or never written are zeroed.
   if (fork) {
     Run rt = r;
     rt.st = ctx->side;
     (void)hipEventRecord(ctx->ev_fork, r.st);
     (void)hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
-    fill_f32(grads, 0.f, mrem_param_count(ctx), r.st);
+    zero_gradient_slots(r, grads);
     prepare_weights(r, params);
     // the two passes are enqueued layer by layer in turn, so that both streams have work from the
     // start also when the caller's queue was empty
@@ -787,7 +801,7 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
     (void)hipEventRecord(ctx->ev_join, ctx->side);
   } else {
     teacher_forward(r, teacher, teacher_cache, x_fp, per_layer_fp, nullptr);
-    fill_f32(grads, 0.f, mrem_param_count(ctx), r.st);
+    zero_gradient_slots(r, grads);
     prepare_weights(r, params);
     student_forward(r, params, x_q, per_layer_q);
   }

@@ -706,6 +706,37 @@ void fill_f32(float* p, float v, int64_t n, hipStream_t st) {
   if (g < 1) g = 1;
   hipLaunchKernelGGL(fill_k, dim3(g), dim3(256), 0, st, p, v, n);
 }
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+struct FillTable {
+  FillRegion r[kMaxFillRegions];
+};
+__global__ void zero_regions_k(FillTable t) {
+  const FillRegion rg = t.r[blockIdx.y];
+  f32x4_t* p4 = reinterpret_cast<f32x4_t*>(rg.p);  // regions start 16-byte aligned (checked on the host)
+  const int64_t n4 = rg.n / 4;
+  const f32x4_t z = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x) p4[i] = z;
+  if (blockIdx.x == 0 && threadIdx.x < (rg.n & 3)) rg.p[n4 * 4 + threadIdx.x] = 0.f;
+}
+void zero_regions(const FillRegion* regions, int count, hipStream_t st) {
+  for (int c0 = 0; c0 < count; c0 += kMaxFillRegions) {
+    FillTable t;
+    const int nr = count - c0 < kMaxFillRegions ? count - c0 : kMaxFillRegions;
+    int64_t longest = 1;
+    for (int k = 0; k < nr; ++k) {
+      t.r[k] = regions[c0 + k];
+      if ((reinterpret_cast<uintptr_t>(t.r[k].p) & 15) != 0) {  // unaligned start: plain fill
+        fill_f32(t.r[k].p, 0.f, t.r[k].n, st);
+        t.r[k].n = 0;
+      }
+      if (t.r[k].n > longest) longest = t.r[k].n;
+    }
+    int gx = (int)((longest / 4 + 255) / 256);
+    if (gx > 2048) gx = 2048;
+    if (gx < 1) gx = 1;
+    hipLaunchKernelGGL(zero_regions_k, dim3(gx, nr), dim3(256), 0, st, t);
+  }
+}
 
 // Eq. 4: out = wa * a + wb * b
 template <class T>
@@ -904,7 +935,6 @@ __device__ __forceinline__ float adam_one(float p, float g, float& m, float& v, 
 // One block per output channel.  g_w holds d(loss)/d(w_hat) on entry; the
 // straight-through mask and the step-size gradient (row reduction) are formed
 // here, from the weights and the step before their update.
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 struct AdamJobTable {
   AdamJob job[kMaxMatrixJobs];

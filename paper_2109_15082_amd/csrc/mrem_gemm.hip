@@ -393,17 +393,23 @@ void gemm_nt(int dt, const void* A, int lda, const void* B, int ldb, void* C, in
   gemm(dt, 0, 0, A, lda, B, ldb, C, ldc, M, N, K, e, st);
 }
 
+// Tiles for at most half of the compute units and a long contraction (weight gradients of the
+// square projections): two k-slices.  (Larger weight gradients run beside the rest of the backward
+// pass, where a second slice only adds atomic traffic.)  Two atomic adds onto a zeroed fp32 value
+// commute exactly, so the result does not depend on which slice arrives first.
+static int f32_k_slices(int M, int N, int K) {
+  const int tiles = (M / 128) * (N / 128);
+  return (tiles <= 128 && K >= 2048 && (K / kBK) % 2 == 0) ? 2 : 1;
+}
+int gemm_f32_k_slices(int dt, int M, int N, int K) {
+  return (dt == DT_BF16 && M % 128 == 0 && N % 128 == 0 && K % kBK == 0) ? f32_k_slices(M, N, K) : 1;
+}
+
 template <bool AT, bool BT>
 static void launch_mfma_modes(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
                               hipStream_t st) {
-  const int tiles = (M / 128) * (N / 128);
   if (e.out_f32) {
-    // Tiles for at most half of the compute units and a long contraction (weight gradients of
-    // the square projections): two k-slices.  (Larger weight gradients run beside the rest of the
-    // backward pass, where a second slice only adds atomic traffic.)  Two atomic adds onto a
-    // zeroed fp32 value commute exactly, so the result does not depend on which slice arrives
-    // first.
-    const int splits = (tiles <= 128 && K >= 2048 && (K / kBK) % 2 == 0 && !e.gelu) ? 2 : 1;
+    const int splits = e.gelu ? 1 : f32_k_slices(M, N, K);
     if (splits > 1 && !e.c_zeroed) fill_f32((float*)C, 0.f, (int64_t)M * ldc, st);
     launch_mfma<128, 128, 2, 2, AT, BT, kRegBK, float>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
   } else {

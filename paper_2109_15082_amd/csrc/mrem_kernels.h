@@ -123,6 +123,13 @@ constexpr int kMaxReduceJobs = 64;
 void reduce_jobs(const ReduceJob* jobs, int njobs, hipStream_t st);
 void loss_total(float* loss_out, int n_layers, hipStream_t st);
 void fill_f32(float* p, float v, int64_t n, hipStream_t st);
+// zeroes up to kMaxFillRegions regions in one launch
+constexpr int kMaxFillRegions = 64;
+struct FillRegion { float* p; int64_t n; };
+void zero_regions(const FillRegion* regions, int count, hipStream_t st);
+// 2 if a product with fp32 output of this shape is accumulated into its (zeroed) output in two
+// k-slices, 1 if it is written
+int gemm_f32_k_slices(int dt, int M, int N, int K);
 void axpby(int dt, const void* a, const void* b, float wa, float wb, void* out, int64_t n, hipStream_t st);
 
 // ---- attention -----------------------------------------------------------------
