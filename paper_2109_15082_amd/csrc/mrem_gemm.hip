@@ -284,33 +284,45 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16
 #undef MREM_STORE_LDS
 
   // epilogue: out = acc * (alpha * col_scale[n]) + beta * (col_vec[n] + row_vec[m]) + bias[n]
+  // The rare terms (row vector, GELU) are decided once per block, not once per element.
   const float alpha = e.alpha ? *e.alpha : 1.f;
   const float beta = (e.beta ? *e.beta : 0.f) + e.beta_alpha * alpha;
   const bool split = gridDim.y > 1, lead = blockIdx.y == 0;  // the additive terms go in once, with slice 0
+  auto write_out = [&](auto with_row, auto with_gelu) {
 #pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    const int n = n0 + wn * WN + j * 32 + (lane & 31);
-    const float cs = alpha * (e.col_scale ? e.col_scale[n] : 1.f);
-    float cb = (e.bias && lead) ? e.bias[n] : 0.f;
-    if (e.beta && e.col_vec && lead) cb += beta * e.col_vec[n];
+    for (int j = 0; j < NT; ++j) {
+      const int n = n0 + wn * WN + j * 32 + (lane & 31);
+      const float cs = alpha * (e.col_scale ? e.col_scale[n] : 1.f);
+      float cb = (e.bias && lead) ? e.bias[n] : 0.f;
+      if (e.beta && e.col_vec && lead) cb += beta * e.col_vec[n];
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      const int mb = m0 + wm * WM + i * 32 + 4 * (lane >> 5);
+      for (int i = 0; i < MT; ++i) {
+        const int mb = m0 + wm * WM + i * 32 + 4 * (lane >> 5);
+        TO* __restrict__ out = C + (size_t)mb * ldc + n;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = mb + 8 * (r >> 2) + (r & 3);
-        float v = (float)acc[i][j][r] * cs + cb;
-        if (e.beta && e.row_vec && lead) v += beta * e.row_vec[m];
-        if constexpr (sizeof(TO) == 4) {
-          if (split) {
-            atomicAdd(reinterpret_cast<float*>(C) + (size_t)m * ldc + n, v);
-            continue;
+        for (int r = 0; r < 16; ++r) {
+          const int dm = 8 * (r >> 2) + (r & 3);
+          float v = (float)acc[i][j][r] * cs + cb;
+          if constexpr (decltype(with_row)::value) v += beta * e.row_vec[mb + dm];
+          if constexpr (sizeof(TO) == 4) {
+            if (split) {
+              atomicAdd(reinterpret_cast<float*>(out) + (size_t)dm * ldc, v);
+              continue;
+            }
           }
+          if constexpr (decltype(with_gelu)::value) v = gelu_t<TO>(round_to<TO>(v));
+          stf(out, (size_t)dm * ldc, v);
         }
-        if (e.gelu) v = gelu_t<TO>(round_to<TO>(v));
-        stf(C, (size_t)m * ldc + n, v);
       }
     }
+  };
+  const bool row_term = e.beta && e.row_vec && lead;
+  if (e.gelu) {
+    if (row_term) write_out(std::true_type{}, std::true_type{});
+    else write_out(std::false_type{}, std::true_type{});
+  } else {
+    if (row_term) write_out(std::true_type{}, std::false_type{});
+    else write_out(std::false_type{}, std::false_type{});
   }
 }
 
