@@ -288,7 +288,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16
   const float alpha = e.alpha ? *e.alpha : 1.f;
   const float beta = (e.beta ? *e.beta : 0.f) + e.beta_alpha * alpha;
   const bool split = gridDim.y > 1, lead = blockIdx.y == 0;  // the additive terms go in once, with slice 0
-  auto write_out = [&](auto with_row, auto with_gelu) {
+  auto write_out = [&](auto with_row, auto with_gelu, auto with_split) {
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
       const int n = n0 + wn * WN + j * 32 + (lane & 31);
@@ -304,25 +304,30 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16
           const int dm = 8 * (r >> 2) + (r & 3);
           float v = (float)acc[i][j][r] * cs + cb;
           if constexpr (decltype(with_row)::value) v += beta * e.row_vec[mb + dm];
-          if constexpr (sizeof(TO) == 4) {
-            if (split) {
-              atomicAdd(reinterpret_cast<float*>(out) + (size_t)dm * ldc, v);
-              continue;
-            }
+          if constexpr (decltype(with_split)::value) {
+            atomicAdd(reinterpret_cast<float*>(out) + (size_t)dm * ldc, v);
+          } else {
+            if constexpr (decltype(with_gelu)::value) v = gelu_t<TO>(round_to<TO>(v));
+            stf(out, (size_t)dm * ldc, v);
           }
-          if constexpr (decltype(with_gelu)::value) v = gelu_t<TO>(round_to<TO>(v));
-          stf(out, (size_t)dm * ldc, v);
         }
       }
     }
   };
   const bool row_term = e.beta && e.row_vec && lead;
+  if constexpr (sizeof(TO) == 4) {
+    if (split) {  // k-slices: fp32 output only, never with GELU (the launcher sees to both)
+      if (row_term) write_out(std::true_type{}, std::false_type{}, std::true_type{});
+      else write_out(std::false_type{}, std::false_type{}, std::true_type{});
+      return;
+    }
+  }
   if (e.gelu) {
-    if (row_term) write_out(std::true_type{}, std::true_type{});
-    else write_out(std::false_type{}, std::true_type{});
+    if (row_term) write_out(std::true_type{}, std::true_type{}, std::false_type{});
+    else write_out(std::false_type{}, std::true_type{}, std::false_type{});
   } else {
-    if (row_term) write_out(std::true_type{}, std::false_type{});
-    else write_out(std::false_type{}, std::false_type{});
+    if (row_term) write_out(std::true_type{}, std::false_type{}, std::false_type{});
+    else write_out(std::false_type{}, std::false_type{}, std::false_type{});
   }
 }
 
