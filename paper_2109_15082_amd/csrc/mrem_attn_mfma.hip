@@ -441,7 +441,12 @@ static void fwd_launch(const void* codes, void* ctx, void* ctx_codes, const Attn
                        float* pmax_rows, float* stat_m, float* stat_l, hipStream_t st, int8_t* ctx_codes8) {
   const int nt = (S + 31) / 32, s_pad = 32 * nt;
   const size_t lds = (size_t)2 * s_pad * kRowStride * sizeof(bf16_t);
+  // the attribute belongs to the (kernel, device) pair: set again when the current device changes
   static size_t configured = 0;
+  static int configured_dev = -1;
+  int dev = -1;
+  (void)hipGetDevice(&dev);
+  if (dev != configured_dev) { configured = 0; configured_dev = dev; }
   if (lds > configured) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_mfma_k<NT>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     configured = lds;
@@ -461,7 +466,12 @@ int attn_bwd_mfma(const void* codes, const void* dctx, void* d_qkvh, const AttnQ
                   const float* stat_m, const float* stat_l, void* pt_scratch, void* dat_scratch, float* ds_parts, hipStream_t st) {
   const int nt = (S + 31) / 32, s_pad = 32 * nt;
   const size_t lds = (size_t)2 * s_pad * kRowStride * sizeof(bf16_t);
+  // the attribute belongs to the (kernel, device) pair: set again when the current device changes
   static size_t configured = 0;
+  static int configured_dev = -1;
+  int dev = -1;
+  (void)hipGetDevice(&dev);
+  if (dev != configured_dev) { configured = 0; configured_dev = dev; }
   if (lds > configured) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_q_mfma_k<4>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_q_mfma_k<0>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -336,11 +336,14 @@ static void launch_mfma(const void* A, int lda, const void* B, int ldb, void* C,
                         hipStream_t st, int k_splits = 1) {
   constexpr int NTHREADS = 64 * WAVES_M * WAVES_N;
   constexpr size_t lds = 2 * (size_t)(OperandTile<AT, BM, NTHREADS, BK>::ELEMS + OperandTile<BT, BN, NTHREADS, BK>::ELEMS) * sizeof(bf16_t);
-  static bool configured = false;
-  if (!configured) {
+  // the attribute belongs to the (kernel, device) pair: set again when the current device changes
+  static int configured_dev = -1;
+  int dev = -1;
+  (void)hipGetDevice(&dev);
+  if (dev != configured_dev) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, BK, TO, I8>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    configured = true;
+    configured_dev = dev;
   }
   const int tiles_m = M / BM, tiles_n = N / BN;
   if (g_launch_e0) {
