@@ -74,17 +74,45 @@ extern "C" mrem_status mrem_create(const mrem_config* cfg, mrem_ctx** out) {
   return MREM_OK;
 }
 
+// Releases the side stream and its events (null handles are skipped, so it also cleans up after
+// a creation that failed half way).
+static void release_side(mrem_ctx* ctx) {
+  if (ctx->side) (void)hipStreamSynchronize(ctx->side);
+  for (hipEvent_t* e : {&ctx->ev_fork, &ctx->ev_join}) {
+    if (*e) (void)hipEventDestroy(*e);
+    *e = nullptr;
+  }
+  for (std::vector<hipEvent_t>* evs : {&ctx->ev_layer, &ctx->ev_ready, &ctx->ev_done}) {
+    for (hipEvent_t e : *evs)
+      if (e) (void)hipEventDestroy(e);
+    evs->clear();
+  }
+  if (ctx->side) (void)hipStreamDestroy(ctx->side);
+  ctx->side = nullptr;
+  ctx->side_device = -1;
+}
+// All or nothing: on failure nothing is left behind and the next call tries again.
+static bool create_side(mrem_ctx* ctx, int dev) {
+  bool ok = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess &&
+            hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) == hipSuccess;
+  ctx->ev_layer.assign((size_t)ctx->L, nullptr);
+  ctx->ev_ready.assign((size_t)ctx->L * 4, nullptr);
+  ctx->ev_done.assign((size_t)ctx->L * 4, nullptr);
+  for (std::vector<hipEvent_t>* evs : {&ctx->ev_layer, &ctx->ev_ready, &ctx->ev_done})
+    for (hipEvent_t& e : *evs) ok = ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
+  if (!ok) {
+    release_side(ctx);
+    (void)hipGetLastError();  // the failure is reported by the caller's return value
+    return false;
+  }
+  ctx->side_device = dev;
+  return true;
+}
+
 extern "C" void mrem_destroy(mrem_ctx* ctx) {
   if (!ctx) return;
-  if (ctx->side) {
-    (void)hipStreamSynchronize(ctx->side);
-    (void)hipEventDestroy(ctx->ev_fork);
-    (void)hipEventDestroy(ctx->ev_join);
-    for (hipEvent_t e : ctx->ev_layer) (void)hipEventDestroy(e);
-    for (hipEvent_t e : ctx->ev_ready) (void)hipEventDestroy(e);
-    for (hipEvent_t e : ctx->ev_done) (void)hipEventDestroy(e);
-    (void)hipStreamDestroy(ctx->side);
-  }
+  release_side(ctx);
   delete ctx;
 }
 extern "C" int64_t mrem_param_count(const mrem_ctx* ctx) { return ctx ? ctx->layer_stride * ctx->L : -1; }
@@ -768,20 +796,8 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
   // the loss: kernels of the two passes fill each other's tails.
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) return fail(ctx, MREM_EHIP, "mrem_module_step: no current device");
-  if (!ctx->side) {
-    if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
-        hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess)
-      return fail(ctx, MREM_EHIP, "mrem_module_step: cannot create the side stream");
-    ctx->ev_layer.assign((size_t)ctx->L, nullptr);
-    ctx->ev_ready.assign((size_t)ctx->L * 4, nullptr);
-    ctx->ev_done.assign((size_t)ctx->L * 4, nullptr);
-    for (std::vector<hipEvent_t>* evs : {&ctx->ev_layer, &ctx->ev_ready, &ctx->ev_done})
-      for (hipEvent_t& e : *evs)
-        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess)
-          return fail(ctx, MREM_EHIP, "mrem_module_step: cannot create the side stream's events");
-    ctx->side_device = dev;
-  }
+  if (!ctx->side && !create_side(ctx, dev))
+    return fail(ctx, MREM_EHIP, "mrem_module_step: cannot create the side stream and its events");
   if (dev != ctx->side_device) return fail(ctx, MREM_EINVAL, "mrem_module_step: the context was first used on another device");
   const bool fork = !gemm_profile_active();  // per-launch timing wants every product alone on the device
   // Before the passes: the gradient slots that are added into or never written are zeroed.
