@@ -315,6 +315,9 @@ class _AQ:
             self.s = float(lp["s_a"][idx])
             self.z = float(lp["z_a"][idx]) if ACT_Q_UNSIGNED[idx] else 0.0
         self.decide32 = cfg.act_round is not None
+        # relative width of the band around a clip bound inside which a value stored in bf16 may
+        # land on the other side of the bound (one rounding of the type); none for exact storage
+        self.band = 2.0 ** -7 if cfg.act_round == "bf16" else 0.0
 
     def fwd(self, x):
         self.margin = np.inf
@@ -325,12 +328,27 @@ class _AQ:
         return xh
 
     def bwd(self, d_xhat):
-        """Also records ds_abs = sum |terms of ds|, the natural scale for judging a
-        computed ds (the sum itself cancels heavily)."""
-        self.ds_abs = 0.0
+        """Also records two diagnostics for judging a computed ds: ds_abs = sum |terms of ds|, its
+        natural scale (the sum itself cancels heavily), and ds_down / ds_up, by how much ds falls
+        or rises if every value within `band` of a clip bound is given the other in/out decision
+        (the term of an element jumps from d*(q - v), about zero there, to d*q_bound when it
+        crosses the bound, so a single such element can move ds by a visible amount)."""
+        self.ds_abs = self.ds_down = self.ds_up = 0.0
         if not self.enabled:
             return d_xhat, 0.0
-        self.ds_abs = float(np.abs(np.asarray(d_xhat) * (self.q - self.v * self.inside)).sum())
+        d = np.asarray(d_xhat, dtype=np.float64)
+        cur = d * (self.q - self.v * self.inside)
+        self.ds_abs = float(np.abs(cur).sum())
+        lim = self.band * max(abs(self.qn), abs(self.qp))
+        near_p = np.abs(self.v - self.qp) < lim
+        near_n = (np.abs(self.v - self.qn) < lim) if self.qn < 0 else np.zeros_like(near_p)
+        for near, bound in ((near_p, float(self.qp)), (near_n, float(self.qn))):
+            if near.any():
+                dn, vn, inn = d[near], self.v[near], self.inside[near]
+                alt = np.where(inn, dn * bound, dn * (bound - vn))   # the other decision
+                diff = alt - cur[near]
+                self.ds_up += float(diff[diff > 0].sum())
+                self.ds_down += float(-diff[diff < 0].sum())
         return fake_quant_backward(d_xhat, self.q, self.v, self.inside)
 
 
@@ -453,7 +471,9 @@ def layer_backward(df, c, cfg: Config):
     t, ds_a[AQ_X] = aq[AQ_X].bwd(dxh)
     dx = dx + t
     g["s_a"] = ds_a
-    g["s_a_abs"] = np.array([a.ds_abs for a in aq])     # diagnostic, not a gradient
+    g["s_a_abs"] = np.array([a.ds_abs for a in aq])     # diagnostics, not gradients
+    g["s_a_down"] = np.array([a.ds_down for a in aq])
+    g["s_a_up"] = np.array([a.ds_up for a in aq])
     return dx, g
 
 

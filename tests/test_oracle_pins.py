@@ -739,3 +739,29 @@ def test_per_tensor_weight_steps_vs_autograd_of_a_scalar_step():
     O.module_step(x, x, teacher, student, m, v, 1, 1e-3, cfg, batch, seq, None)
     for n in O.STEP_NAMES:
         assert np.all(student[0][n] == student[0][n][0])
+
+
+def test_step_gradient_interval_at_a_clip_bound():
+    """The diagnostic that accompanies ds: with bf16 storage a value within one rounding of a clip
+    bound may be decided either way, and the element's term jumps between d*(q - v) and d*q_bound.
+    Checked by hand on four elements: one just inside the upper bound, one just outside, two far."""
+    cfg = O.Config(n_layers=1, hidden=8, n_heads=1, ffn=8, a_bits=8, w_bits=4, act_round="bf16")
+    lp = {"s_a": np.full(8, 0.5), "z_a": np.zeros(8)}
+    aq = O._AQ(cfg, lp, O.AQ_X, True)               # symmetric, Qp = 127
+    x = np.array([126.6, 127.4, 10.2, -50.3]) * 0.5  # v = 126.6 (inside), 127.4 (clipped), far, far
+    d = np.array([2.0, -3.0, 1.0, 1.0])
+    aq.fwd(x)
+    _, ds = aq.bwd(d)
+    terms = np.array([2.0 * (127 - 126.6), -3.0 * 127, 1.0 * (10 - 10.2), 1.0 * (-50 + 50.3)])
+    assert np.isclose(ds, terms.sum())
+    # element 0 decided "outside": 2*127 instead of 2*0.4 -> ds rises by 253.2
+    # element 1 decided "inside": -3*(127 - 127.4) = 1.2 instead of -381 -> ds rises by 382.2
+    assert np.isclose(aq.ds_up, 253.2 + 382.2) and aq.ds_down == 0.0
+    _, _ = aq.bwd(-d)
+    assert np.isclose(aq.ds_down, 253.2 + 382.2) and aq.ds_up == 0.0
+    # exact storage: no band, no interval
+    cfg32 = O.Config(n_layers=1, hidden=8, n_heads=1, ffn=8, a_bits=8, w_bits=4, act_round="f32")
+    aq32 = O._AQ(cfg32, lp, O.AQ_X, True)
+    aq32.fwd(x)
+    aq32.bwd(d)
+    assert aq32.ds_up == 0.0 and aq32.ds_down == 0.0
