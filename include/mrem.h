@@ -158,7 +158,9 @@ mrem_status mrem_teacher_prepare(mrem_ctx* ctx, const float* teacher, void* cach
  * s = max(P) / (2^b - 1), for the GELU output z = min(g), s = (max(g) - z) / (2^b - 1).
  * Writes the S_A and Z_A fields of every layer of params; nothing else is touched.
  *   x_fp     device act_dtype [batch, seq, hidden]
- *   seqlens  device int32 [batch] valid keys per sequence, or NULL (no padding)
+ *   seqlens  device int32 [batch] valid keys per sequence, each in 1..seq, or NULL (no
+ *            padding).  The values live on the device and are not checked: a sequence
+ *            without a valid key has no softmax and yields NaN in its rows.
  */
 mrem_status mrem_module_calibrate(mrem_ctx* ctx, float* params, const float* teacher, const void* teacher_cache,
                                   const void* x_fp, const int32_t* seqlens, int32_t batch, int32_t seq,
@@ -172,7 +174,7 @@ mrem_status mrem_module_calibrate(mrem_ctx* ctx, float* params, const float* tea
  *   teacher        device fp32 [mrem_teacher_count] (in: biases and LayerNorm parameters)
  *   teacher_cache  device, from mrem_teacher_prepare (in: matrices)
  *   x_fp, x_q      device act_dtype [batch, seq, hidden]; may alias
- *   seqlens        device int32 [batch] or NULL
+ *   seqlens        device int32 [batch], each in 1..seq, or NULL (as for mrem_module_calibrate)
  *   per_layer_fp, per_layer_q  device act_dtype [n_layers, batch, seq, hidden] (out):
  *                  the layer outputs f_l and f^_l of Eq. 3; the last slice is the
  *                  module output handed to the next module.  Either may be NULL to
