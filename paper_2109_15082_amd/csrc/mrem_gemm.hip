@@ -185,8 +185,10 @@ struct OperandTile {
 // I8: the operands are int8 codes seen as pairs (the caller passes K, lda and ldb in units of two
 // bytes): data movement and fragment addresses are those of the bf16 case, the product runs on
 // the 32x32x32 int8 instruction with exact int32 accumulation.  Not for transposed operands.
+// Two blocks per compute unit are part of the design (LDS: 2 x 74 KB); the launch bound makes the
+// compiler keep the register budget that goes with it (256 per lane, accumulators included).
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, int BK, class TO, bool I8 = false>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_k(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B,
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void gemm_mfma_k(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B,
                                                                       int ldb, TO* __restrict__ C, int ldc, int M, int N, int K, Epilogue e,
                                                                       int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
