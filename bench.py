@@ -24,7 +24,7 @@ MFMA_INT8_PEAK_TOPS = 5000.0
 # HBM bytes per matrix-product launch (read + written), from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE), each scaled by what the counter reads for a 256 MiB device copy; summary with the commands in
 # profiles/module_step_bert_large_6l_hbm_traffic.md.  Only for the workload it was measured on.
-MEASURED_GEMM_TRAFFIC_BYTES = {"bert_large_6l": 81.0e6}
+MEASURED_GEMM_TRAFFIC_BYTES = {"bert_large_6l": 81.1e6}
 
 
 def step_flops(wl):
