@@ -85,3 +85,22 @@ def test_entry_points_reject_bad_arguments_on_the_host(B):
     assert B._lib.mrem_quantize(None, 4, 8, 4, 1, fake, fake, None) == B.MREM_EINVAL
     assert B._lib.mrem_quantize(fake, 4, 8, 1, 1, fake, fake, None) == B.MREM_EINVAL
     B.mrem_destroy(ctx)
+
+
+def test_binding_refuses_to_import_without_the_library(B, tmp_path):
+    """There is no fallback path: a copy of the binding in a folder without libmrem.so must fail at
+    import, naming the missing file."""
+    import importlib
+    import sys
+    pkg = tmp_path / "mrem_without_library"
+    pkg.mkdir()
+    (pkg / "__init__.py").write_text("")
+    (pkg / "binding.py").write_text(open(B.__file__).read())
+    sys.path.insert(0, str(tmp_path))
+    try:
+        with pytest.raises(ImportError, match="libmrem.so is missing"):
+            importlib.import_module("mrem_without_library.binding")
+    finally:
+        sys.path.remove(str(tmp_path))
+        sys.modules.pop("mrem_without_library", None)
+        sys.modules.pop("mrem_without_library.binding", None)
