@@ -15,11 +15,11 @@
  *    ordinary host memory.
  *  - All work is enqueued on the caller's hipStream_t (passed as void*, NULL = the
  *    default stream) or ordered with it: mrem_module_step runs the full-precision
- *    forward pass, and the update of each layer's weight matrices once that layer's
- *    gradients are complete, on a side stream that the context owns (default
- *    priority, created on the first step), forked from the caller's stream by
- *    events and joined to it before the loss and before the call's last kernels; to
- *    the caller the call behaves like work on its own stream.  Calls return without
+ *    forward pass, the weight-gradient products and the update of each layer's
+ *    weight matrices on a side stream that the context owns (default priority,
+ *    created on the first step), forked from the caller's stream by events and
+ *    joined to it before the loss and before the call's last kernels; to the caller
+ *    the call behaves like work on its own stream.  Calls return without
  *    synchronising.
  *  - Arguments are validated on the host before anything is enqueued; a call that
  *    returns an error has had no effect on device memory.
@@ -214,10 +214,9 @@ mrem_status mrem_mix_inputs(mrem_ctx* ctx, const void* x_fp, const void* x_q, fl
 
 /*
  * Measurement aid (not part of the method): between mrem_profile_gemm_begin() and
- * mrem_profile_gemm_end() every matrix-product kernel launch of this process is
- * bracketed by a pair of HIP events on its stream, and mrem_module_step keeps the
- * full-precision forward pass on the caller's stream so that every product runs
- * alone.  _end waits for the events and returns, for products on bf16 operands in
+ * mrem_profile_gemm_end() every matrix-product kernel launch of this process
+ * carries a pair of HIP events (kernel begin, kernel end), and mrem_module_step
+ * keeps all its work on the caller's stream so that every product runs alone.  _end waits for the events and returns, for products on bf16 operands in
  * element [0] and for products on int8 operands in element [1] of each host array:
  * the summed kernel time in milliseconds, the summed 2*M*N*K of those launches and
  * their number.  Not thread-safe; events are host-side objects.
