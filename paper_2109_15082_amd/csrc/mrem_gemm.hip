@@ -258,6 +258,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void gemm_mfma_k(const b
     if (kt + 1 < KT) MREM_LOAD_GLOBAL((kt + 1) * BK)
     const bf16_t* As = smem + cur * STAGE;
     const bf16_t* Bs = As + OpA::ELEMS;
+    __builtin_amdgcn_s_setprio(1);  // the wavefront that multiplies goes first: the other one of the SIMD is fetching
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       bf16x8_t af[MT], bfr[NT];
@@ -279,6 +280,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void gemm_mfma_k(const b
           }
         }
     }
+    __builtin_amdgcn_s_setprio(0);
     if (kt + 1 < KT) MREM_STORE_LDS(cur ^ 1)
     __syncthreads();
   }
