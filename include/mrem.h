@@ -186,6 +186,23 @@ mrem_status mrem_module_forward(mrem_ctx* ctx, const float* params, const float*
                                 size_t workspace_bytes, void* hip_stream);
 
 /*
+ * mrem_module_forward_static -- mrem_module_forward for callers that cannot allocate device
+ * memory and have no workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments without the workspace pair, same kernels,
+ * same results; the scratch memory is a static device array of MREM_STATIC_SCRATCH_BYTES that
+ * the library's code object carries (each GPU the library runs on holds its copy until the
+ * process ends).  The call allocates and frees nothing, on the device or through any library.
+ * Error MREM_EWORKSPACE if mrem_workspace_bytes(ctx, batch, seq) exceeds
+ * MREM_STATIC_SCRATCH_BYTES (nothing is enqueued).  All calls on one GPU share that GPU's
+ * array: calls that overlap in time on one GPU (different streams or threads) race on it.
+ */
+#define MREM_STATIC_SCRATCH_BYTES (64u << 20)
+size_t mrem_static_scratch_bytes(void); /* MREM_STATIC_SCRATCH_BYTES of the loaded library */
+mrem_status mrem_module_forward_static(mrem_ctx* ctx, const float* params, const float* teacher, const void* teacher_cache,
+                                       const void* x_fp, const void* x_q, const int32_t* seqlens, int32_t batch,
+                                       int32_t seq, void* per_layer_fp, void* per_layer_q, void* hip_stream);
+
+/*
  * mrem_module_step -- one full iteration of Algorithm 2 (without its input mixing):
  * both forward passes, the loss of Eq. 3, the straight-through backward pass
  * confined to the module (Section 4.2), and one AdamW update with rate lr of every

@@ -29,7 +29,7 @@ FIELD_ID = {n: i for i, n in enumerate(FIELDS)}
 EXPORTS = ("mrem_create", "mrem_destroy", "mrem_last_error", "mrem_param_count", "mrem_teacher_count",
            "mrem_param_offset", "mrem_param_size", "mrem_workspace_bytes", "mrem_teacher_cache_bytes",
            "mrem_quantize", "mrem_module_init_steps", "mrem_teacher_prepare", "mrem_module_calibrate",
-           "mrem_module_forward", "mrem_module_step", "mrem_mix_inputs", "mrem_profile_gemm_begin",
+           "mrem_module_forward", "mrem_module_forward_static", "mrem_static_scratch_bytes", "mrem_module_step", "mrem_mix_inputs", "mrem_profile_gemm_begin",
            "mrem_profile_gemm_end")
 
 
@@ -70,6 +70,10 @@ _lib.mrem_module_calibrate.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
 _lib.mrem_module_calibrate.restype = C.c_int
 _lib.mrem_module_forward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]
 _lib.mrem_module_forward.restype = C.c_int
+_lib.mrem_module_forward_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp]
+_lib.mrem_module_forward_static.restype = C.c_int
+_lib.mrem_static_scratch_bytes.argtypes = []
+_lib.mrem_static_scratch_bytes.restype = _sz
 _lib.mrem_module_step.argtypes = [_vp, _vp, _vp, _vp, _i64, _f32, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp,
                                   _vp, _vp, _sz, _vp]
 _lib.mrem_module_step.restype = C.c_int
@@ -178,6 +182,16 @@ def mrem_module_forward(ctx, params, teacher, teacher_cache, x_fp, x_q, seqlens,
     _check(_lib.mrem_module_forward(ctx, _ptr(params), _ptr(teacher), _ptr(teacher_cache), _ptr(x_fp), _ptr(x_q),
                                     _ptr(seqlens), batch, seq, _ptr(per_layer_fp), _ptr(per_layer_q), _ptr(workspace),
                                     workspace.numel() * workspace.element_size(), _stream(stream)), ctx)
+
+
+def mrem_static_scratch_bytes() -> int:
+    return _lib.mrem_static_scratch_bytes()
+
+
+def mrem_module_forward_static(ctx, params, teacher, teacher_cache, x_fp, x_q, seqlens, batch, seq, per_layer_fp, per_layer_q,
+                               stream=None) -> None:
+    _check(_lib.mrem_module_forward_static(ctx, _ptr(params), _ptr(teacher), _ptr(teacher_cache), _ptr(x_fp), _ptr(x_q),
+                                           _ptr(seqlens), batch, seq, _ptr(per_layer_fp), _ptr(per_layer_q), _stream(stream)), ctx)
 
 
 def mrem_module_step(ctx, params, adam_m, adam_v, step_index, lr, teacher, teacher_cache, x_fp, x_q, seqlens, batch, seq,

@@ -743,31 +743,80 @@ extern "C" mrem_status mrem_module_calibrate(mrem_ctx* ctx, float* params, const
   return finish(ctx, "mrem_module_calibrate");
 }
 
-extern "C" mrem_status mrem_module_forward(mrem_ctx* ctx, const float* params, const float* teacher, const void* teacher_cache,
-                                           const void* x_fp, const void* x_q, const int32_t* seqlens, int32_t batch, int32_t seq,
-                                           void* per_layer_fp, void* per_layer_q, void* workspace, size_t workspace_bytes, void* hip_stream) {
+namespace {
+mrem_status forward_impl(mrem_ctx* ctx, const float* params, const float* teacher, const void* teacher_cache, const void* x_fp,
+                         const void* x_q, const int32_t* seqlens, int32_t batch, int32_t seq, void* per_layer_fp, void* per_layer_q,
+                         void* workspace, size_t workspace_bytes, void* hip_stream, const char* who) {
   Plan plan;
-  mrem_status s = check_common(ctx, batch, seq, workspace, workspace_bytes, "mrem_module_forward", &plan);
+  mrem_status s = check_common(ctx, batch, seq, workspace, workspace_bytes, who, &plan);
   if (s != MREM_OK) return s;
-  if (!per_layer_fp && !per_layer_q) return fail(ctx, MREM_EINVAL, "mrem_module_forward: both outputs are null");
+  if (!per_layer_fp && !per_layer_q) return fail(ctx, MREM_EINVAL, std::string(who) + ": both outputs are null");
   Run r{ctx, plan, (char*)workspace, (hipStream_t)hip_stream, batch, seq, batch * seq, seqlens};
   if (per_layer_fp) {
-    REQUIRE_PTR(teacher, "mrem_module_forward");
-    REQUIRE_PTR(teacher_cache, "mrem_module_forward");
-    REQUIRE_PTR(x_fp, "mrem_module_forward");
-    if (!aligned16(per_layer_fp)) return fail(ctx, MREM_EINVAL, "mrem_module_forward: per_layer_fp misaligned");
+    REQUIRE_PTR(teacher, who);
+    REQUIRE_PTR(teacher_cache, who);
+    REQUIRE_PTR(x_fp, who);
+    if (!aligned16(per_layer_fp)) return fail(ctx, MREM_EINVAL, std::string(who) + ": per_layer_fp misaligned");
   }
   if (per_layer_q) {
-    REQUIRE_PTR(params, "mrem_module_forward");
-    REQUIRE_PTR(x_q, "mrem_module_forward");
-    if (!aligned16(per_layer_q)) return fail(ctx, MREM_EINVAL, "mrem_module_forward: per_layer_q misaligned");
+    REQUIRE_PTR(params, who);
+    REQUIRE_PTR(x_q, who);
+    if (!aligned16(per_layer_q)) return fail(ctx, MREM_EINVAL, std::string(who) + ": per_layer_q misaligned");
   }
   if (per_layer_fp) teacher_forward(r, teacher, teacher_cache, x_fp, per_layer_fp, nullptr);
   if (per_layer_q) {
     prepare_weights(r, params);
     student_forward(r, params, x_q, per_layer_q);
   }
-  return finish(ctx, "mrem_module_forward");
+  return finish(ctx, who);
+}
+}  // namespace
+
+extern "C" mrem_status mrem_module_forward(mrem_ctx* ctx, const float* params, const float* teacher, const void* teacher_cache,
+                                           const void* x_fp, const void* x_q, const int32_t* seqlens, int32_t batch, int32_t seq,
+                                           void* per_layer_fp, void* per_layer_q, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return forward_impl(ctx, params, teacher, teacher_cache, x_fp, x_q, seqlens, batch, seq, per_layer_fp, per_layer_q, workspace,
+                      workspace_bytes, hip_stream, "mrem_module_forward");
+}
+
+// ------------------------------------------------------------------------------
+// The forward passes for callers that cannot allocate: the workspace is a static device array.
+// ------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[MREM_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+// Device address of `scratch` on each device (every device holds its own copy of the array at its
+// own address; the array's name itself is only a host-side handle).  Looked up once per device,
+// with that device current.
+void* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+extern "C" size_t mrem_static_scratch_bytes(void) { return MREM_STATIC_SCRATCH_BYTES; }
+
+extern "C" mrem_status mrem_module_forward_static(mrem_ctx* ctx, const float* params, const float* teacher, const void* teacher_cache,
+                                                  const void* x_fp, const void* x_q, const int32_t* seqlens, int32_t batch,
+                                                  int32_t seq, void* per_layer_fp, void* per_layer_q, void* hip_stream) {
+  const char* who = "mrem_module_forward_static";
+  if (!ctx) return fail(nullptr, MREM_EINVAL, std::string(who) + ": null context");
+  if (batch < 1 || seq < 1) return fail(ctx, MREM_ESHAPE, std::string(who) + ": batch and seq must be >= 1");
+  const size_t need = make_plan(ctx, batch, seq).total;
+  if (need > (size_t)MREM_STATIC_SCRATCH_BYTES)
+    return fail(ctx, MREM_EWORKSPACE, std::string(who) + ": this module at this batch and seq needs " + std::to_string(need) +
+                                          " bytes of scratch, the static array holds " + std::to_string((size_t)MREM_STATIC_SCRATCH_BYTES) +
+                                          "; use mrem_module_forward with a caller-owned workspace");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return fail(ctx, MREM_EHIP, std::string(who) + ": no current device");
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(ctx, MREM_EHIP, std::string(who) + ": hipGetSymbolAddress: " + hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  // Nothing in the forward passes reads scratch memory that the same call has not written, so the
+  // contents a previous call left behind need no clearing.
+  return forward_impl(ctx, params, teacher, teacher_cache, x_fp, x_q, seqlens, batch, seq, per_layer_fp, per_layer_q,
+                      g_scratch_ptr[dev], MREM_STATIC_SCRATCH_BYTES, hip_stream, who);
 }
 
 extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* adam_m, float* adam_v, int64_t step_index, float lr,
