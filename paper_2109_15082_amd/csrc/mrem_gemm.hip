@@ -7,6 +7,7 @@
 
 #include <hip/hip_ext.h>
 
+#include <cstdlib>
 #include <type_traits>
 
 #include <vector>
@@ -335,6 +336,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void gemm_mfma_k(const b
   }
 }
 
+}  // namespace mrem
+#include "mrem_gemm_dl.h"
+namespace mrem {
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, int BK, class TO, bool I8 = false>
 static void launch_mfma(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
                         hipStream_t st, int k_splits = 1) {
@@ -391,9 +396,31 @@ bool gemm_i8_ok(const void* A, int lda, const void* B, int ldb, int M, int N, in
 }
 // The register-staged kernel in its int8 mode: two int8 codes travel as one 16-bit element, so
 // leading dimensions and the contraction length are halved.
+static int gemm_policy() {
+  static int pol = -1;
+  if (pol < 0) { const char* v = getenv("MREM_GEMM_POLICY"); pol = v ? atoi(v) : 15; }
+  return pol;
+}
+// experimental dispatch: policy = 10 * big + small
+template <bool AT, bool BT, class TO, bool I8>
+static void launch_dl_policy(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
+                             hipStream_t st, int splits) {
+  const int pol = gemm_policy(), small = pol % 10, big = pol / 10;
+  if (big && splits == 1 && M % 256 == 0 && N % 256 == 0 && (M / 256) * (N / 256) >= 192) {
+    if (big == 1) return launch_dl<256, 256, 4, 2, AT, BT, 2, 128, TO, I8, 1>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+    if (big == 2) return launch_dl<256, 128, 2, 2, AT, BT, 3, 64, TO, I8, 2>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+    if (big == 3) return launch_dl<256, 256, 4, 2, AT, BT, 4, 64, TO, I8, 1>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+    if (big == 4) return launch_dl<128, 256, 2, 2, AT, BT, 3, 64, TO, I8, 2>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+  }
+  if (small == 1) return launch_dl<128, 128, 2, 2, AT, BT, 2, 128, TO, I8, 2>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
+  if (small == 3) return launch_dl<128, 128, 2, 2, AT, BT, 4, 128, TO, I8, 1>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
+  if (small == 4) return launch_dl<128, 128, 2, 2, AT, BT, 3, 128, TO, I8, 1>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
+  return launch_dl<128, 128, 2, 2, AT, BT, 4, 64, TO, I8, 2>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
+}
 static void gemm_i8_launch(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
                            hipStream_t st) {
-  launch_mfma<128, 128, 2, 2, false, false, kRegBK, bf16_t, true>(A, lda / 2, B, ldb / 2, C, ldc, M, N, K / 2, e, st);
+  if (gemm_policy() == 0) { launch_mfma<128, 128, 2, 2, false, false, kRegBK, bf16_t, true>(A, lda / 2, B, ldb / 2, C, ldc, M, N, K / 2, e, st); return; }
+  launch_dl_policy<false, false, bf16_t, true>(A, lda / 2, B, ldb / 2, C, ldc, M, N, K / 2, e, st, 1);
 }
 void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e, hipStream_t st) {
   if (!g_prof_on) {
@@ -435,9 +462,11 @@ static void launch_mfma_modes(const void* A, int lda, const void* B, int ldb, vo
   if (e.out_f32) {
     const int splits = e.gelu ? 1 : f32_k_slices(M, N, K);
     if (splits > 1 && !e.c_zeroed) fill_f32((float*)C, 0.f, (int64_t)M * ldc, st);
-    launch_mfma<128, 128, 2, 2, AT, BT, kRegBK, float>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
+    if (gemm_policy() == 0) launch_mfma<128, 128, 2, 2, AT, BT, kRegBK, float>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
+    else launch_dl_policy<AT, BT, float, false>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
   } else {
-    launch_mfma<128, 128, 2, 2, AT, BT, kRegBK, bf16_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+    if (gemm_policy() == 0) launch_mfma<128, 128, 2, 2, AT, BT, kRegBK, bf16_t>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+    else launch_dl_policy<AT, BT, bf16_t, false>(A, lda, B, ldb, C, ldc, M, N, K, e, st, 1);
   }
 }
 
