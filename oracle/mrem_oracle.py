@@ -49,10 +49,27 @@ are the ones the HIP path implements):
   quantizer is on (the codes are); when it is off (the full-precision module)
   they are matrix-product operands and therefore stored tensors too.
 
-parity unpinned: none of the functions below -- every one is pinned in
-tests/test_oracle_pins.py (hand-computed fixtures under tests/golden/, closed
-forms, brute force on tiny inputs, torch fp64 autograd of the frozen-residual
-surrogate, torch.optim.AdamW).
+* `accumulate`: None = every matrix product in fp64.  'f32' forms the products of
+  stored tensors in fp32 (numpy's own summation order), which is what "fp32
+  accumulation" means in the workloads.  It is a second statement of the same
+  forward pass, used by the tests only to MEASURE how far an accumulation-level
+  perturbation is amplified by the chained quantized layers (a code that flips at
+  a rounding tie changes an element by a whole step): the distance between the
+  two oracle runs is the conditioning bound that the chained GPU outputs are
+  held to on top of the stated tolerance.
+
+Diagnostics next to the method's quantities (each pinned by hand in
+tests/test_oracle_pins.py): `decision_margin` (distance of the quantizer ratios
+from a discontinuity), `flag_near_discontinuity` (the elements within a band
+tau of a rounding tie or a clip bound; tau = 2^-7 for bf16 storage, 2^-20 for
+fp32), `ds_abs` / `ds_up` / `ds_down` (natural scale of a step-size gradient and
+the interval it spans when the flagged clip-bound elements are decided either
+way).
+
+parity unpinned: none of the functions below -- every one, the diagnostics
+included, is pinned in tests/test_oracle_pins.py (hand-computed fixtures under
+tests/golden/, hand vectors, closed forms, brute force on tiny inputs, torch fp64
+autograd of the frozen-residual surrogate, torch.optim.AdamW).
 """
 from __future__ import annotations
 
@@ -93,6 +110,7 @@ class Config:
     w_bits: int = 4            # 0 switches the weight quantizers off
     a_bits: int = 8            # 0 switches the activation quantizers off
     act_round: Optional[str] = None   # None | 'f32' | 'bf16'
+    accumulate: Optional[str] = None  # None (fp64 products) | 'f32' (fp32 products: conditioning measurements only)
     loss_layer_mask: int = -1  # bit l set => layer l contributes to Eq. 3
     loss_mean: bool = True     # mean over elements (True) or raw sum of squares
     ln_eps: float = 1e-12
@@ -212,6 +230,25 @@ def decision_margin(v, qn: int, qp: int, nonnegative: bool = False) -> float:
     return float(min(tie.min(), edge.min()))
 
 
+def discontinuity_band(act_round: Optional[str]) -> float:
+    """Band tau around a discontinuity of the quantizer inside which two computations of
+    the same ratio in different precisions may decide differently: 2^-7 of a step (of the
+    range, for a clip bound) with bf16 storage, 2^-20 with fp32, nothing in exact arithmetic."""
+    return {None: 0.0, "f32": 2.0 ** -20, "bf16": 2.0 ** -7}[act_round]
+
+
+def flag_near_discontinuity(v, qn: int, qp: int, tau: float):
+    """Masks (near_tie, near_bound) of the ratios v that lie within tau of a rounding tie
+    k + 1/2 strictly inside the range, or within tau * max(|qn|, |qp|) of a clip bound."""
+    v = np.asarray(v, dtype=np.float64)
+    inside = (v > qn) & (v < qp)
+    frac = v - np.floor(v)
+    near_tie = inside & (np.abs(frac - 0.5) < tau)
+    lim = tau * max(abs(qn), abs(qp))
+    near_bound = (np.abs(v - qp) < lim) | (np.abs(v - qn) < lim)
+    return near_tie, near_bound
+
+
 def weight_step_init(w, bits: int, per_channel: bool = True) -> np.ndarray:
     """Initial step max |w| / Qp, one fp32 division: per output channel (row), or over the
     whole matrix (then every entry of the returned vector holds that one value)."""
@@ -318,13 +355,17 @@ class _AQ:
         # relative width of the band around a clip bound inside which a value stored in bf16 may
         # land on the other side of the bound (one rounding of the type); none for exact storage
         self.band = 2.0 ** -7 if cfg.act_round == "bf16" else 0.0
+        self.tau = discontinuity_band(cfg.act_round)
 
     def fwd(self, x):
         self.margin = np.inf
+        self.n_near_tie = self.n_near_bound = 0
         if not self.enabled:
             return x
         xh, self.q, self.v, self.inside = fake_quant_forward(x, self.s, self.qn, self.qp, self.z, self.decide32)
         self.margin = decision_margin(self.v, self.qn, self.qp, nonnegative=(self.idx == AQ_P))
+        near_tie, near_bound = flag_near_discontinuity(self.v, self.qn, self.qp, self.tau)
+        self.n_near_tie, self.n_near_bound = int(near_tie.sum()), int(near_bound.sum())
         return xh
 
     def bwd(self, d_xhat):
@@ -378,6 +419,12 @@ def layer_forward(x, lp, cfg: Config, batch: int, seq: int, seqlens=None, quant:
     layer output f[T,H] and a cache for layer_backward."""
     H, nh, d = cfg.hidden, cfg.n_heads, cfg.head_dim
     R = lambda t: round_store(t, cfg.act_round)
+    if cfg.accumulate == "f32":
+        mm = lambda a, b: (np.asarray(a, dtype=np.float32) @ np.asarray(b, dtype=np.float32)).astype(np.float64)
+    elif cfg.accumulate is None:
+        mm = lambda a, b: a @ b
+    else:
+        raise ValueError(f"unknown accumulation mode {cfg.accumulate!r}")
     c = {"lp": lp, "batch": batch, "seq": seq, "x": x}
     aq = [_AQ(cfg, lp, i, quant) for i in range(8)]
     wq = {n: _WQ(cfg, lp[n], lp["s" + n] if quant and cfg.w_bits > 0 else None, quant) for n in WEIGHT_NAMES}
@@ -385,27 +432,27 @@ def layer_forward(x, lp, cfg: Config, batch: int, seq: int, seqlens=None, quant:
 
     # self-attention: three projections of one quantized input
     xh = aq[AQ_X].fwd(x)
-    qkv = R(xh @ wq["w_qkv"].w_hat.T + lp["b_qkv"])
+    qkv = R(mm(xh, wq["w_qkv"].w_hat.T) + lp["b_qkv"])
     Q = split_heads(qkv[:, :H], batch, seq, nh)
     K = split_heads(qkv[:, H:2 * H], batch, seq, nh)
     V = split_heads(qkv[:, 2 * H:], batch, seq, nh)
     Qh, Kh, Vh = aq[AQ_Q].fwd(Q), aq[AQ_K].fwd(K), aq[AQ_V].fwd(V)
-    A = Qh @ Kh.transpose(0, 1, 3, 2) / math.sqrt(d) + key_mask(seqlens, batch, seq)
+    A = mm(Qh, Kh.transpose(0, 1, 3, 2)) / math.sqrt(d) + key_mask(seqlens, batch, seq)
     P = softmax_rows(A)
     # an operand of a matrix product is either quantizer codes or a stored tensor
     Ph = aq[AQ_P].fwd(P) if aq[AQ_P].enabled else R(P)
-    C = R(merge_heads(Ph @ Vh))
+    C = R(merge_heads(mm(Ph, Vh)))
     Ch = aq[AQ_C].fwd(C)
-    o = R(Ch @ wq["w_o"].w_hat.T + lp["b_o"])
+    o = R(mm(Ch, wq["w_o"].w_hat.T) + lp["b_o"])
     x1_pre, ln1 = layernorm_forward(x + o, lp["ln1_g"], lp["ln1_b"], cfg.ln_eps)
     x1 = R(x1_pre)
 
     # feed-forward network
     x1h = aq[AQ_X1].fwd(x1)
-    u = R(x1h @ wq["w_1"].w_hat.T + lp["b_1"])
+    u = R(mm(x1h, wq["w_1"].w_hat.T) + lp["b_1"])
     g = gelu(u)
     gh = aq[AQ_G].fwd(g) if aq[AQ_G].enabled else R(g)
-    y = R(gh @ wq["w_2"].w_hat.T + lp["b_2"])
+    y = R(mm(gh, wq["w_2"].w_hat.T) + lp["b_2"])
     f_pre, ln2 = layernorm_forward(x1 + y, lp["ln2_g"], lp["ln2_b"], cfg.ln_eps)
     f = R(f_pre)
 

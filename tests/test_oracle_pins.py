@@ -765,3 +765,103 @@ def test_step_gradient_interval_at_a_clip_bound():
     aq32.fwd(x)
     aq32.bwd(d)
     assert aq32.ds_up == 0.0 and aq32.ds_down == 0.0
+
+
+# --------------------------------------------------------------------------------
+# diagnostics that the GPU parity tests select inputs with, divide by or widen intervals with
+# --------------------------------------------------------------------------------
+
+def test_decision_margin_hand_vectors():
+    """decision_margin: distance (in steps) to the nearest rounding tie inside the range or clip bound."""
+    # ties: |frac - 1/2| = 0.3, 0.05, 0.4 ; bounds (qn, qp = -7, 7): 5.8, 3.55, 0.1
+    assert np.isclose(O.decision_margin(np.array([1.2, 3.45, -6.9]), -7, 7), 0.05)
+    # an exact tie inside the range
+    assert O.decision_margin(np.array([1.2, 2.5]), -7, 7) == 0.0
+    # a clipped value just beyond the upper bound: no tie counts outside the range, the bound does
+    assert np.isclose(O.decision_margin(np.array([7.02]), -7, 7), 0.02)
+    # ... and just beyond the lower one
+    assert np.isclose(O.decision_margin(np.array([-7.25, 0.0]), -7, 7), 0.25)
+    # a value sitting on the bound itself (the largest element at initialisation)
+    assert O.decision_margin(np.array([7.0, 0.9]), -7, 7) == 0.0
+    # unsigned grid: the lower bound 0 counts ...
+    assert np.isclose(O.decision_margin(np.array([0.05, 200.0]), 0, 255), 0.05)
+    # ... unless the values cannot go below it (softmax probabilities): then only ties and the upper bound
+    assert np.isclose(O.decision_margin(np.array([0.05, 200.0]), 0, 255, nonnegative=True), 0.45)
+    assert np.isclose(O.decision_margin(np.array([254.9]), 0, 255, nonnegative=True), 0.1)
+
+
+@pytest.mark.parametrize("qn,qp", [(-7, 7), (0, 15)])
+def test_decision_margin_is_a_safe_perturbation_radius(qn, qp):
+    """Brute force: moving every ratio by less than the margin changes no code and no mask."""
+    rng = np.random.default_rng(3)
+    v = rng.uniform(qn - 2.0, qp + 2.0, size=400)
+    m = O.decision_margin(v, qn, qp)
+    assert m > 0
+    code = lambda t: np.rint(np.clip(t, qn, qp))
+    mask = lambda t: (t >= qn) & (t <= qp)
+    for sign in (-1.0, 1.0):
+        w = v + sign * 0.999 * m
+        assert np.array_equal(code(w), code(v)) and np.array_equal(mask(w), mask(v))
+    # and the margin is attained: a move a little larger than it flips one code or one mask entry
+    flipped = False
+    for sign in (-1.0, 1.0):
+        w = v + sign * 1.001 * m
+        flipped |= (not np.array_equal(code(w), code(v))) or (not np.array_equal(mask(w), mask(v)))
+    assert flipped
+
+
+def test_flag_near_discontinuity_hand_vectors():
+    tau = O.discontinuity_band("bf16")
+    assert tau == 2.0 ** -7 and O.discontinuity_band("f32") == 2.0 ** -20 and O.discontinuity_band(None) == 0.0
+    #            tie      near tie   far      at bound  near bound(in)  near bound(out)  far outside
+    v = np.array([2.5,    -3.496,    1.2,     127.0,    126.3,          127.9,           140.0, -126.2, 0.504])
+    tie, bound = O.flag_near_discontinuity(v, -127, 127, tau)        # bound band: 127 / 128 = 0.992 steps
+    assert tie.tolist() == [True, True, False, False, False, False, False, False, True]
+    assert bound.tolist() == [False, False, False, True, True, True, False, True, False]
+    # a tie position outside the range is no tie (the value is clipped there)
+    tie, bound = O.flag_near_discontinuity(np.array([7.5, -8.5]), -7, 7, tau)
+    assert not tie.any() and not bound.any()
+    # fp32 band: only values within 2^-20 of the tie
+    tie, _ = O.flag_near_discontinuity(np.array([2.5 + 2.0 ** -21, 2.5 + 2.0 ** -19]), -7, 7, O.discontinuity_band("f32"))
+    assert tie.tolist() == [True, False]
+    # the counts reach the per-quantizer records of a forward pass
+    cfg = O.Config(n_layers=1, hidden=8, n_heads=1, ffn=8, a_bits=4, w_bits=4, act_round="bf16")
+    aq = O._AQ(cfg, {"s_a": np.full(8, 0.5), "z_a": np.zeros(8)}, O.AQ_X, True)   # symmetric 4-bit: [-7, 7], band 7/128 at a bound
+    aq.fwd(np.array([1.25, 0.6, 3.48, 3.6, -3.52]))                                  # v = 2.5, 1.2, 6.96, 7.2, -7.04
+    assert (aq.n_near_tie, aq.n_near_bound) == (1, 2)
+
+
+def test_step_gradient_scale_hand_vector():
+    """ds_abs = sum of |terms| of the step-size gradient (the scale a computed ds is judged on)."""
+    cfg = O.Config(n_layers=1, hidden=8, n_heads=1, ffn=8, a_bits=4, w_bits=4)
+    aq = O._AQ(cfg, {"s_a": np.full(8, 0.25), "z_a": np.zeros(8)}, O.AQ_X, True)      # [-7, 7]
+    x = np.array([0.3, -0.9, 2.5, -0.625])          # v = 1.2, -3.6, 10 (clipped), -2.5 (tie -> -2)
+    d = np.array([2.0, -1.0, 0.5, 4.0])
+    aq.fwd(x)
+    _, ds = aq.bwd(d)
+    terms = np.array([2.0 * (1 - 1.2), -1.0 * (-4 + 3.6), 0.5 * 7, 4.0 * (-2 + 2.5)])   # -0.4, 0.4, 3.5, 2.0
+    assert np.isclose(ds, terms.sum()) and np.isclose(ds, 5.5)
+    assert np.isclose(aq.ds_abs, 0.4 + 0.4 + 3.5 + 2.0)
+    # unsigned quantizer with an offset: v = (x - z) / s
+    cfgu = O.Config(n_layers=1, hidden=8, n_heads=1, ffn=8, a_bits=2, w_bits=4)
+    lp = {"s_a": np.full(8, 0.5), "z_a": np.full(8, -0.25)}
+    aqu = O._AQ(cfgu, lp, O.AQ_G, True)                                                  # {0..3}, z = -0.25
+    aqu.fwd(np.array([0.35, -0.5, 2.0]))           # v = 1.2, -0.5 (below 0: clipped), 4.5 (clipped to 3)
+    _, dsu = aqu.bwd(np.array([1.0, 2.0, -1.0]))
+    assert np.isclose(dsu, 1.0 * (1 - 1.2) + 2.0 * 0 + -1.0 * 3)
+    assert np.isclose(aqu.ds_abs, 0.2 + 0.0 + 3.0)
+
+
+def test_fp32_accumulation_mode_is_the_same_forward_pass():
+    """accumulate='f32' forms the same products in fp32: without quantizers and storage rounding it differs
+    from the fp64 pass at fp32 rounding level only; with them it measures the amplification."""
+    cfg = tiny_cfg(n_layers=2, w_bits=0, a_bits=0)
+    teacher, student, x = tiny_student(cfg)
+    ref, _ = O.module_forward(x, teacher, cfg, 2, 6, quant=False)
+    cfg32 = tiny_cfg(n_layers=2, w_bits=0, a_bits=0, accumulate="f32")
+    got, _ = O.module_forward(x, teacher, cfg32, 2, 6, quant=False)
+    for a, b in zip(ref, got):
+        e = np.linalg.norm(a - b) / np.linalg.norm(a)
+        assert 0 < e < 1e-5
+    with pytest.raises(ValueError):
+        O.module_forward(x, teacher, tiny_cfg(accumulate="f16"), 2, 6, quant=False)
