@@ -61,8 +61,8 @@ are the ones the HIP path implements):
 Diagnostics next to the method's quantities (each pinned by hand in
 tests/test_oracle_pins.py): `decision_margin` (distance of the quantizer ratios
 from a discontinuity), `flag_near_discontinuity` (the elements within a band
-tau of a rounding tie or a clip bound; tau = 2^-7 for bf16 storage, 2^-20 for
-fp32), `ds_abs` / `ds_up` / `ds_down` (natural scale of a step-size gradient and
+tau of a rounding tie, or within the relative uncertainty tau of the stored value
+of a clip bound; tau = 2^-7 for bf16 storage, 2^-20 for fp32), `ds_abs` / `ds_up` / `ds_down` (natural scale of a step-size gradient and
 the interval it spans when the flagged clip-bound elements are decided either
 way).
 
@@ -237,15 +237,16 @@ def discontinuity_band(act_round: Optional[str]) -> float:
     return {None: 0.0, "f32": 2.0 ** -20, "bf16": 2.0 ** -7}[act_round]
 
 
-def flag_near_discontinuity(v, qn: int, qp: int, tau: float):
-    """Masks (near_tie, near_bound) of the ratios v that lie within tau of a rounding tie
-    k + 1/2 strictly inside the range, or within tau * max(|qn|, |qp|) of a clip bound."""
+def flag_near_discontinuity(v, qn: int, qp: int, tau: float, offset_steps: float = 0.0):
+    """Masks (near_tie, near_bound) of the ratios v = (a - z) / s that lie within tau of a rounding tie
+    k + 1/2 strictly inside the range, or within the band of a clip bound.  A stored value a carries a
+    relative uncertainty tau, i.e. tau * |a| / s steps: at the bound b that is tau * |b + z / s|
+    (offset_steps = z / s; tau * |b| for the symmetric quantizers, nothing at a lower bound 0 without offset)."""
     v = np.asarray(v, dtype=np.float64)
     inside = (v > qn) & (v < qp)
     frac = v - np.floor(v)
     near_tie = inside & (np.abs(frac - 0.5) < tau)
-    lim = tau * max(abs(qn), abs(qp))
-    near_bound = (np.abs(v - qp) < lim) | (np.abs(v - qn) < lim)
+    near_bound = (np.abs(v - qp) < tau * abs(qp + offset_steps)) | (np.abs(v - qn) < tau * abs(qn + offset_steps))
     return near_tie, near_bound
 
 
@@ -364,9 +365,15 @@ class _AQ:
             return x
         xh, self.q, self.v, self.inside = fake_quant_forward(x, self.s, self.qn, self.qp, self.z, self.decide32)
         self.margin = decision_margin(self.v, self.qn, self.qp, nonnegative=(self.idx == AQ_P))
-        near_tie, near_bound = flag_near_discontinuity(self.v, self.qn, self.qp, self.tau)
+        near_tie, near_bound = self.flags()
         self.n_near_tie, self.n_near_bound = int(near_tie.sum()), int(near_bound.sum())
         return xh
+
+    def flags(self):
+        """(near_tie, near_bound) masks of the last forward pass (all False when the quantizer is off)."""
+        if not self.enabled:
+            return None, None
+        return flag_near_discontinuity(self.v, self.qn, self.qp, self.tau, self.z / self.s)
 
     def bwd(self, d_xhat):
         """Also records two diagnostics for judging a computed ds: ds_abs = sum |terms of ds|, its
@@ -518,6 +525,9 @@ def layer_backward(df, c, cfg: Config):
     t, ds_a[AQ_X] = aq[AQ_X].bwd(dxh)
     dx = dx + t
     g["s_a"] = ds_a
+    # kept for the tests' element-wise protocol (what a flipped mask decision of a flagged element can change):
+    # the gradients that the straight-through masks of the GELU-output and Q/K/V quantizers gate
+    c["bwd"] = {"dgh": dgh, "dQh": dQh, "dKh": dKh, "dVh": dVh}
     g["s_a_abs"] = np.array([a.ds_abs for a in aq])     # diagnostics, not gradients
     g["s_a_down"] = np.array([a.ds_down for a in aq])
     g["s_a_up"] = np.array([a.ds_up for a in aq])

@@ -824,11 +824,21 @@ def test_flag_near_discontinuity_hand_vectors():
     # fp32 band: only values within 2^-20 of the tie
     tie, _ = O.flag_near_discontinuity(np.array([2.5 + 2.0 ** -21, 2.5 + 2.0 ** -19]), -7, 7, O.discontinuity_band("f32"))
     assert tie.tolist() == [True, False]
+    # unsigned grid with an offset: x^ = s q + z, z / s = -8.5 steps: the stored value at the lower bound 0 is
+    # 8.5 steps large (band 8.5 / 128 = 0.066), at the upper bound 255 it is 246.5 steps large (band 1.93)
+    v = np.array([0.05, 0.08, -0.06, 253.2, 252.9, 256.5, 100.0])
+    _, bound = O.flag_near_discontinuity(v, 0, 255, tau, offset_steps=-8.5)
+    assert bound.tolist() == [True, False, True, True, False, True, False]
+    # ... and without offset nothing can be decided differently at the lower bound 0 (probabilities)
+    _, bound = O.flag_near_discontinuity(np.array([0.0, 0.001, 254.0]), 0, 255, tau)
+    assert bound.tolist() == [False, False, True]
     # the counts reach the per-quantizer records of a forward pass
     cfg = O.Config(n_layers=1, hidden=8, n_heads=1, ffn=8, a_bits=4, w_bits=4, act_round="bf16")
     aq = O._AQ(cfg, {"s_a": np.full(8, 0.5), "z_a": np.zeros(8)}, O.AQ_X, True)   # symmetric 4-bit: [-7, 7], band 7/128 at a bound
     aq.fwd(np.array([1.25, 0.6, 3.48, 3.6, -3.52]))                                  # v = 2.5, 1.2, 6.96, 7.2, -7.04
     assert (aq.n_near_tie, aq.n_near_bound) == (1, 2)
+    tie, bound = aq.flags()
+    assert tie.tolist() == [True, False, False, False, False] and bound.tolist() == [False, False, True, False, True]
 
 
 def test_step_gradient_scale_hand_vector():
