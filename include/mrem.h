@@ -120,6 +120,28 @@ size_t mrem_workspace_bytes(const mrem_ctx* ctx, int32_t batch, int32_t seq);
 size_t mrem_teacher_cache_bytes(const mrem_ctx* ctx);
 
 /*
+ * Inspection aid (tests): where the forward pass of the quantized module leaves some of its
+ * intermediate tensors inside the workspace.  Byte offset from the workspace pointer for the
+ * given batch and seq, or -1 if that tensor does not exist in this configuration.  The contents
+ * are those of the last mrem_module_forward / mrem_module_step on that workspace.
+ *   MREM_WS_WCODES8 + i  int8 [N,K] codes of linear weight i (0 query/key/value, 1 attention output,
+ *                        2 first, 3 second feed-forward projection): Eq. 1 applied to the current
+ *                        parameters; present when the forward products run on int8 codes
+ *                        (bf16 storage, both bit widths on, hidden and ffn multiples of 128, batch*seq
+ *                        a multiple of 128)
+ *   MREM_WS_WCODES + i   the same codes as integer values of the activation type; present otherwise
+ *   MREM_WS_QKV          act_dtype [batch*seq, 3*hidden]: output of the query/key/value projection
+ *   MREM_WS_XCODES8      int8 [batch*seq, hidden]: codes of the layer input (when int8 products are in use)
+ */
+typedef enum {
+  MREM_WS_WCODES8 = 0, /* .. 3 */
+  MREM_WS_WCODES = 4,  /* .. 7 */
+  MREM_WS_QKV = 8,
+  MREM_WS_XCODES8 = 9
+} mrem_ws_item;
+int64_t mrem_workspace_offset(const mrem_ctx* ctx, int32_t batch, int32_t seq, int32_t layer, int32_t item);
+
+/*
  * mrem_quantize -- the uniform quantizer of Section 3.1, Eq. 1, per output channel:
  *   codes[n,k] = nearest_even( clamp( w[n,k] / scale[n], -Qp, Qp ) ),  Qp = 2^(bits-1) - 1,
  * with the quotient formed as one IEEE fp32 division.

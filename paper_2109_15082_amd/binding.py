@@ -27,7 +27,7 @@ FIELDS = ("w_qkv", "w_o", "w_1", "w_2", "b_qkv", "b_o", "ln1_g", "ln1_b", "b_1",
 FIELD_ID = {n: i for i, n in enumerate(FIELDS)}
 
 EXPORTS = ("mrem_create", "mrem_destroy", "mrem_last_error", "mrem_param_count", "mrem_teacher_count",
-           "mrem_param_offset", "mrem_param_size", "mrem_workspace_bytes", "mrem_teacher_cache_bytes",
+           "mrem_param_offset", "mrem_param_size", "mrem_workspace_bytes", "mrem_workspace_offset", "mrem_teacher_cache_bytes",
            "mrem_quantize", "mrem_module_init_steps", "mrem_teacher_prepare", "mrem_module_calibrate",
            "mrem_module_forward", "mrem_module_forward_static", "mrem_static_scratch_bytes", "mrem_module_step", "mrem_mix_inputs", "mrem_profile_gemm_begin",
            "mrem_profile_gemm_end")
@@ -58,6 +58,8 @@ _lib.mrem_param_size.argtypes = [_vp, _i32]
 _lib.mrem_param_size.restype = _i64
 _lib.mrem_workspace_bytes.argtypes = [_vp, _i32, _i32]
 _lib.mrem_workspace_bytes.restype = _sz
+_lib.mrem_workspace_offset.argtypes = [_vp, _i32, _i32, _i32, _i32]
+_lib.mrem_workspace_offset.restype = _i64
 _lib.mrem_teacher_cache_bytes.argtypes = [_vp]
 _lib.mrem_teacher_cache_bytes.restype = _sz
 _lib.mrem_quantize.argtypes = [_vp, _i64, _i64, _i32, _i32, _vp, _vp, _vp]
@@ -153,6 +155,13 @@ def mrem_param_size(ctx, field) -> int:
 
 def mrem_workspace_bytes(ctx, batch: int, seq: int) -> int:
     return _lib.mrem_workspace_bytes(ctx, batch, seq)
+
+
+MREM_WS_WCODES8, MREM_WS_WCODES, MREM_WS_QKV, MREM_WS_XCODES8 = 0, 4, 8, 9
+
+
+def mrem_workspace_offset(ctx, batch: int, seq: int, layer: int, item: int) -> int:
+    return _lib.mrem_workspace_offset(ctx, batch, seq, layer, item)
 
 
 def mrem_teacher_cache_bytes(ctx) -> int:

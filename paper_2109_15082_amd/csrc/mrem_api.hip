@@ -673,6 +673,18 @@ extern "C" size_t mrem_workspace_bytes(const mrem_ctx* ctx, int32_t batch, int32
   return make_plan(ctx, batch, seq).total;
 }
 
+extern "C" int64_t mrem_workspace_offset(const mrem_ctx* ctx, int32_t batch, int32_t seq, int32_t layer, int32_t item) {
+  if (!ctx || batch < 1 || seq < 1 || layer < 0 || layer >= ctx->L) return -1;
+  const Plan p = make_plan(ctx, batch, seq);
+  const LayerWs& w = p.lw[layer];
+  const bool i8 = i8_config(ctx) && (batch * seq) % 128 == 0;
+  if (item >= MREM_WS_WCODES8 && item < MREM_WS_WCODES8 + 4) return i8 ? (int64_t)w.wcodes8[item - MREM_WS_WCODES8] : -1;
+  if (item >= MREM_WS_WCODES && item < MREM_WS_WCODES + 4) return i8 ? -1 : (int64_t)w.wcodes[item - MREM_WS_WCODES];
+  if (item == MREM_WS_QKV) return (int64_t)w.qkv;
+  if (item == MREM_WS_XCODES8) return i8 ? (int64_t)w.xcodes8 : -1;
+  return -1;
+}
+
 extern "C" mrem_status mrem_quantize(const float* w, int64_t N, int64_t K, int32_t bits, int32_t init_scale, float* scale, int8_t* codes,
                                      void* hip_stream) {
   const mrem_ctx* ctx = nullptr;

@@ -185,7 +185,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_k(const bf16_t* __restrict_
   if (q < S) {
     const float os = sc.sp * sc.sv;
     QuantParam qc5 = {aq.c.on ? *aq.c.s : 1.f, 0.f, aq.c.qn, aq.c.qp, aq.c.on, 0.f};
-    qc5.rs = __fdiv_rn(1.0f, qc5.s);
+    qc5.rs = quant_reciprocal(qc5.s);
     const size_t orow = ((size_t)b * S + q) * H + h * kD;
 #pragma unroll
     for (int et = 0; et < 2; ++et)

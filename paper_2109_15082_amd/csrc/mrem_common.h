@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "mrem_quant_math.h"
+
 namespace mrem {
 
 typedef __bf16 bf16_t;
@@ -33,17 +35,9 @@ struct QuantParam {
   float rs;  // correctly rounded 1 / s (only for q_ratio_fma)
 };
 
-__device__ __forceinline__ float q_ratio(float a, const QuantParam& q) { return __fdiv_rn(__fsub_rn(a, q.z), q.s); }
-// The same quotient without the division sequence: t = fl(n * rs), then t + fl(n - s * t) * rs with
-// fused multiply-adds.  With rs the correctly rounded reciprocal, the residual n - s * t is exact
-// and the last operation rounds the true quotient (the residual-correction step of FMA division);
-// activations and step sizes are far from the overflow and underflow ranges where that needs
-// care.  One step size serves millions of elements, so the reciprocal is taken once per thread.
-__device__ __forceinline__ float q_ratio_fma(float a, const QuantParam& q) {
-  const float n = __fsub_rn(a, q.z);
-  const float t = __fmul_rn(n, q.rs);
-  return __fmaf_rn(__fmaf_rn(-q.s, t, n), q.rs, t);
-}
+__device__ __forceinline__ float q_ratio(float a, const QuantParam& q) { return quant_ratio_div(a, q.z, q.s); }
+// the FMA form of the same quotient (mrem_quant_math.h), with q.rs = quant_reciprocal(q.s)
+__device__ __forceinline__ float q_ratio_fma(float a, const QuantParam& q) { return quant_ratio_fma(a, q.z, q.s, q.rs); }
 // fp32 storage (the check mode) divides; bf16 storage uses the FMA form
 template <class T>
 __device__ __forceinline__ float q_ratio_t(float a, const QuantParam& q) {

@@ -84,7 +84,7 @@ __device__ __forceinline__ QuantParam load_q(const QArg& a) {
   q.z = (a.on && a.z) ? *a.z : 0.f;
   q.qn = a.qn;
   q.qp = a.qp;
-  q.rs = __fdiv_rn(1.0f, q.s);
+  q.rs = quant_reciprocal(q.s);
   return q;
 }
 
@@ -444,7 +444,8 @@ int ln_bwd_parts(int T_) { return (T_ + kLnBwdRows - 1) / kLnBwdRows; }
 // One wavefront per token row, kLnBwdRowsPerWave rows per wavefront with the column sums
 // (gamma, beta and residual-bias gradients) accumulated in registers; the wavefronts of a block
 // then meet in LDS (upper half onto lower half, then the lower half) and the block writes one partial row
-// [3H + 1] (the last value is the step-size gradient of the quantizer in front of the next layer).
+// [3H + 2] (the last two values are the step-size gradient of the quantizer in front of the next layer
+// and the squared-error sum of this layer's term of Eq. 3).
 // NCH: 8-element chunks per lane (hidden <= 512 * NCH)
 template <class T, int NCH>
 __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict__ d_a, const T* __restrict__ d_b, const T* __restrict__ d_q,
@@ -816,7 +817,7 @@ __global__ void tie_steps_max_k(float* __restrict__ scale, int64_t N) {
 void tie_steps_max(float* scale, int64_t N, hipStream_t st) { hipLaunchKernelGGL(tie_steps_max_k, dim3(1), dim3(256), 0, st, scale, N); }
 
 // codes (integer-valued, storage type), dequantized weights s*code (same layout), and
-// zcorr[n] = s[n] * sum_k code; one block per output channel, all matrices of a table in one launch
+// zcorr[n] = s[n] * sum_k code (sum_k of the stored weight when the quantizers are off); one block per output channel, all matrices of a table in one launch
 struct WeightJobTable {
   WeightJob job[kMaxMatrixJobs];
   int first_row[kMaxMatrixJobs + 1];
@@ -842,13 +843,16 @@ __global__ __launch_bounds__(128) void weight_codes_k(WeightJobTable tab, float 
     for (int j = 0; j < 8; ++j) {
       c[j] = x[j];
       if (on) { c[j] = rintf(fminf(fmaxf(__fdiv_rn(x[j], s), -qp), qp)); acc += c[j]; x[j] = s * c[j]; }
+      else acc += round_to<T>(x[j]);  // quantizers off: the stored weights themselves are the operand
     }
     if (codes) store8(codes + row + k, c);
     if (jb.codes8) store8_i8(jb.codes8 + row + k, c, 0.f);
     if (what) store8(what + row + k, x);
   }
   acc = block_sum(acc, red);
-  if (threadIdx.x == 0) jb.zcorr[n] = on ? s * acc : 0.f;
+  // s * sum_k code (s = 1 with the weight quantizers off): what the offset z of an asymmetric input
+  // quantizer multiplies in the product's epilogue, x^ = s_a q + z (Section 3.1)
+  if (threadIdx.x == 0) jb.zcorr[n] = s * acc;
 }
 void weight_prepare(int dt, const WeightJob* jobs, int njobs, int bits, hipStream_t st) {
   const int on = bits > 0;

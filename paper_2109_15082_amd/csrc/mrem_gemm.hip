@@ -130,8 +130,10 @@ __global__ void gemm_nt_simt_k(const TA* __restrict__ A, int lda, const TA* __re
 // global -> registers -> LDS (two LDS stages, one barrier per k-step); LDS rows are
 // padded to 144 bytes so that the 16-byte fragment reads of 16 consecutive rows hit
 // distinct banks.  Integer codes (|q| <= 255) are exact in bf16 and their products
-// and partial sums are exact in fp32 up to 2^24, so the quantized forward products
-// are exact integers before the epilogue applies the step sizes.
+// and partial sums are exact in fp32 while they stay below 2^24 (always for 4-bit weights:
+// K * 255 * 7 < 2^24 up to K = 9398; with 8-bit weights only while K * 255 * 127 < 2^24,
+// K <= 518, beyond that the bf16 fallback rounds like any fp32 sum; the int8 mode below
+// accumulates in int32 and is exact for every supported K).
 // Requires M % BM == 0, N % BN == 0, K % 64 == 0 and 16-byte aligned rows.
 // ------------------------------------------------------------------------------
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -415,6 +417,8 @@ static void launch_dl_policy(const void* A, int lda, const void* B, int ldb, voi
   if (small == 1) return launch_dl<128, 128, 2, 2, AT, BT, 2, 128, TO, I8, 2>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
   if (small == 3) return launch_dl<128, 128, 2, 2, AT, BT, 4, 128, TO, I8, 1>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
   if (small == 4) return launch_dl<128, 128, 2, 2, AT, BT, 3, 128, TO, I8, 1>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
+  if (small == 6) return launch_dl<128, 128, 2, 2, AT, BT, 3, 64, TO, I8, 3>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
+  if (small == 7) return launch_dl<128, 128, 2, 2, AT, BT, 3, 64, TO, I8, 2>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
   return launch_dl<128, 128, 2, 2, AT, BT, 4, 64, TO, I8, 2>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
 }
 static void gemm_i8_launch(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,

@@ -63,7 +63,7 @@ void weight_step_init(const float* w, float* scale, int64_t N, int64_t K, int bi
 void tie_steps_max(float* scale, int64_t N, hipStream_t st);
 // Per matrix w[N,K] with steps sw[N]: codes[N,K] (integer-valued, storage type), what[N,K] =
 // round(s*q) (may be null), zcorr[N] = s[n] * sum_k q[n,k].  bits = 0: codes = what = round(w),
-// zcorr = 0.  All matrices of the list go into one launch (kMaxMatrixJobs per launch).
+// zcorr[n] = sum_k round(w[n,k]).  All matrices of the list go into one launch (kMaxMatrixJobs per launch).
 constexpr int kMaxMatrixJobs = 24;
 struct WeightJob {
   const float* w;

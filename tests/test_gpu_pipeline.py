@@ -17,8 +17,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(scope="module")
 def B():
     import torch
-    if not torch.cuda.is_available():
-        pytest.skip("no GPU")
+    assert torch.cuda.is_available(), "these tests need the GPU"
     from paper_2109_15082_amd import binding
     return binding
 
