@@ -122,14 +122,14 @@ def main():
     # step adds up, and because in this pass the library keeps everything on the caller's stream (in
     # pass 1 the full-precision forward pass, the weight-gradient products and the per-layer updates run
     # on a side stream beside the rest), so that every product is timed alone.
-    B.mrem_profile_gemm_begin()
+    B.mrem_profile_gemm_begin(mod.ctx)
     t1 = time.perf_counter()
     for _ in range(args.steps):
         mod.step(x, x, lr0 * (1 - (t % total) / total), sl, out_fp, out_q)
         t += 1
     torch.cuda.synchronize()
     dt_events = time.perf_counter() - t1
-    (gemm_ms, gemm_flops, gemm_launches), (i8_ms, i8_ops, i8_launches) = B.mrem_profile_gemm_end()
+    (gemm_ms, gemm_flops, gemm_launches), (i8_ms, i8_ops, i8_launches) = B.mrem_profile_gemm_end(mod.ctx)
     losses = mod.loss.cpu().numpy()
     assert np.isfinite(losses).all(), losses
 

@@ -13,6 +13,8 @@
  *  - Every pointer marked "device" is HIP device memory owned by the caller.  The
  *    library never allocates, frees or retains device memory.  "host" pointers are
  *    ordinary host memory.
+ *  - Boundary notes: quantizer placement (all six products of a layer) and the plain chain-rule step gradient
+ *    are fixed, not options; lr and lambda are arguments of the step, their schedules are mrem_schedule_*.
  *  - All work is enqueued on the caller's hipStream_t (passed as void*, NULL = the
  *    default stream) or ordered with it: mrem_module_step runs the full-precision
  *    forward pass, the weight-gradient products and the update of each layer's
@@ -49,6 +51,7 @@ typedef enum {
   MREM_EINVAL = -1,     /* null pointer, bad enum, misaligned pointer */
   MREM_ESHAPE = -2,     /* sizes the kernels do not support */
   MREM_EWORKSPACE = -3, /* workspace smaller than mrem_workspace_bytes() */
+  MREM_ENONFINITE = -4, /* mrem_check_nonfinite: a step produced a NaN or an infinite loss */
   MREM_EHIP = -5        /* a HIP runtime call failed */
 } mrem_status;
 
@@ -142,17 +145,19 @@ typedef enum {
 int64_t mrem_workspace_offset(const mrem_ctx* ctx, int32_t batch, int32_t seq, int32_t layer, int32_t item);
 
 /*
- * mrem_quantize -- the uniform quantizer of Section 3.1, Eq. 1, per output channel:
- *   codes[n,k] = nearest_even( clamp( w[n,k] / scale[n], -Qp, Qp ) ),  Qp = 2^(bits-1) - 1,
- * with the quotient formed as one IEEE fp32 division.
- *   w      device fp32 [N,K]      (in)
- *   scale  device fp32 [N]        (in; out if init_scale != 0)
- *   codes  device int8 [N,K]      (out)
- * init_scale != 0 first sets scale[n] = max_k |w[n,k]| / Qp (one fp32 division; a
- * row of zeros gets the smallest positive normal float).  bits in 2..8.
- * Errors: MREM_EINVAL (null/misaligned pointer, bits), MREM_ESHAPE (N or K < 1).
+ * mrem_quantize -- the uniform quantizer of Section 3.1, Eq. 1:
+ *   codes[n,k] = nearest_even( clamp( w[n,k] / s, -Qp, Qp ) ),  Qp = 2^(bits-1) - 1,
+ * with the quotient formed as one IEEE fp32 division; s = scale[n] with per_channel = 1 (one step per
+ * output channel, the granularity of the module step) or s = scale[0] with per_channel = 0 (one step
+ * for the whole tensor, Section 3.1's default granularity).
+ *   w      device fp32 [N,K]             (in)
+ *   scale  device fp32 [N] or [1]        (in; out if init_scale != 0)
+ *   codes  device int8 [N,K]             (out)
+ * init_scale != 0 first sets the step(s) to max |w| / Qp over the channel or the tensor (one fp32
+ * division; all zeros give the smallest positive normal float).  bits in 2..8.
+ * Errors: MREM_EINVAL (null/misaligned pointer, bits, per_channel), MREM_ESHAPE (N or K < 1).
  */
-mrem_status mrem_quantize(const float* w, int64_t N, int64_t K, int32_t bits, int32_t init_scale,
+mrem_status mrem_quantize(const float* w, int64_t N, int64_t K, int32_t bits, int32_t per_channel, int32_t init_scale,
                           float* scale, int8_t* codes, void* hip_stream);
 
 /*
@@ -225,13 +230,16 @@ mrem_status mrem_module_forward_static(mrem_ctx* ctx, const float* params, const
                                        int32_t seq, void* per_layer_fp, void* per_layer_q, void* hip_stream);
 
 /*
- * mrem_module_step -- one full iteration of Algorithm 2 (without its input mixing):
- * both forward passes, the loss of Eq. 3, the straight-through backward pass
+ * mrem_module_step -- one full iteration of Algorithm 2: the input mixing of Eq. 4, both forward
+ * passes, the loss of Eq. 3, the straight-through backward pass
  * confined to the module (Section 4.2), and one AdamW update with rate lr of every
  * trainable parameter and every step size.
  *   params, adam_m, adam_v   device fp32 [mrem_param_count]  (in/out)
  *   step_index               1-based count of this update (bias correction)
- *   lr                       learning rate of this step (caller applies the linear decay)
+ *   lr                       learning rate of this step (mrem_schedule_lr gives the linear decay)
+ *   lambda                   in [0,1], Eq. 4: the quantized module reads lambda * x_fp + (1 - lambda) * x_q
+ *                            (annealed teacher forcing, Section 4.2.1; mrem_schedule_lambda); formed and stored
+ *                            by the kernel that quantizes the first layer's input.  0: x_q as it is
  *   loss_out                 device fp32 [1 + n_layers] (out): total, then per layer
  *   per_layer_fp, per_layer_q  device act_dtype [n_layers, batch, seq, hidden] (out, required)
  *   grads_out                device fp32 [mrem_param_count] or NULL (out): the gradients
@@ -239,7 +247,7 @@ mrem_status mrem_module_forward_static(mrem_ctx* ctx, const float* params, const
  * A context must be used from the device that was current at its first step.
  */
 mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* adam_m, float* adam_v, int64_t step_index,
-                             float lr, const float* teacher, const void* teacher_cache, const void* x_fp,
+                             float lr, float lambda, const float* teacher, const void* teacher_cache, const void* x_fp,
                              const void* x_q, const int32_t* seqlens, int32_t batch, int32_t seq,
                              float* loss_out, void* per_layer_fp, void* per_layer_q, float* grads_out,
                              void* workspace, size_t workspace_bytes, void* hip_stream);
@@ -252,16 +260,56 @@ mrem_status mrem_mix_inputs(mrem_ctx* ctx, const void* x_fp, const void* x_q, fl
                             void* hip_stream);
 
 /*
- * Measurement aid (not part of the method): between mrem_profile_gemm_begin() and
- * mrem_profile_gemm_end() every matrix-product kernel launch of this process
- * carries a pair of HIP events (kernel begin, kernel end), and mrem_module_step
- * keeps all its work on the caller's stream so that every product runs alone.  _end waits for the events and returns, for products on bf16 operands in
- * element [0] and for products on int8 operands in element [1] of each host array:
- * the summed kernel time in milliseconds, the summed 2*M*N*K of those launches and
- * their number.  Not thread-safe; events are host-side objects.
+ * Non-finite detection.  mrem_set_nonfinite_flag gives the context a device int32 (caller-owned, cleared
+ * by the caller; NULL switches the check off): every mrem_module_step on the context then sets it to 1
+ * when its total loss is a NaN or infinite -- a non-finite value anywhere in a layer output reaches that
+ * layer's term of Eq. 3.  The flag is sticky and costs nothing on the host.  mrem_check_nonfinite waits for
+ * the stream, reads the flag and returns MREM_ENONFINITE if it is set (MREM_EINVAL if no flag was given).
  */
-void mrem_profile_gemm_begin(void);
-mrem_status mrem_profile_gemm_end(double ms[2] /*host*/, double flops[2] /*host*/, int64_t launches[2] /*host*/);
+mrem_status mrem_set_nonfinite_flag(mrem_ctx* ctx, int32_t* device_flag);
+mrem_status mrem_check_nonfinite(mrem_ctx* ctx, void* hip_stream);
+
+/*
+ * Schedules (host arithmetic only).  Section 5.1.2: linearly decayed rate lr0 * (1 - t / total),
+ * t = 0 .. total-1.  Section 4.2.1: lambda_t = max(1 - t / tf_steps, 0); 0 when tf_steps < 1.
+ */
+double mrem_schedule_lr(double lr0, int64_t t, int64_t total);
+double mrem_schedule_lambda(int64_t t, int64_t tf_steps);
+
+/*
+ * Input queue of Algorithm 1 (Section 4.2): the last `depth` pairs (f, f^) of module outputs, first in
+ * first out, with the sequence lengths of their batch, in device memory that the caller owns
+ * (mrem_queue_bytes).  The ring has depth + 1 slots: one is being written during a step while the
+ * depth published ones stay readable, so a reader of the oldest entry never sees a slot that its
+ * producer is overwriting.  Which entry a consumer samples is the caller's draw (an age, 0 = newest).
+ *   mrem_queue_push      copies one entry (device to device, on the stream) into the write slot
+ *   mrem_queue_write_slot  pointers of the write slot, for a producer that writes in place
+ *   mrem_queue_publish   hands the written slot over (host bookkeeping; call once the step's work is enqueued
+ *                        and ordered before the consumers' reads)
+ *   mrem_queue_entry     pointers of the entry of the given age, 0 <= age < mrem_queue_size
+ * The handle is host memory; calls on one queue from several threads need the caller's lock.
+ */
+typedef struct mrem_queue mrem_queue;
+size_t mrem_queue_bytes(int32_t depth, size_t half_bytes, size_t lengths_bytes);
+mrem_status mrem_queue_create(int32_t depth, size_t half_bytes, size_t lengths_bytes, void* device_mem, mrem_queue** out);
+void mrem_queue_destroy(mrem_queue* q);
+int32_t mrem_queue_size(const mrem_queue* q);
+mrem_status mrem_queue_write_slot(mrem_queue* q, void** fp, void** qd, void** lengths);
+mrem_status mrem_queue_push(mrem_queue* q, const void* fp, const void* qd, const void* lengths /* may be NULL */, size_t half_bytes,
+                            size_t lengths_bytes, void* hip_stream);
+mrem_status mrem_queue_publish(mrem_queue* q);
+mrem_status mrem_queue_entry(const mrem_queue* q, int32_t age, void** fp, void** qd, void** lengths /* may be NULL */);
+
+/*
+ * Measurement aid (not part of the method): between mrem_profile_gemm_begin(ctx) and
+ * mrem_profile_gemm_end(ctx, ...) every matrix-product kernel launch of that context carries a pair of HIP
+ * events (kernel begin, kernel end), and its mrem_module_step keeps all its work on the caller's stream so
+ * that every product runs alone.  _end waits for the events and returns, for products on bf16 operands in
+ * element [0] and for products on int8 operands in element [1] of each host array: the summed kernel time
+ * in milliseconds, the summed 2*M*N*K of those launches and their number.  The state lives in the context.
+ */
+mrem_status mrem_profile_gemm_begin(mrem_ctx* ctx);
+mrem_status mrem_profile_gemm_end(mrem_ctx* ctx, double ms[2] /*host*/, double flops[2] /*host*/, int64_t launches[2] /*host*/);
 
 #ifdef __cplusplus
 }

@@ -20,7 +20,7 @@ if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2109_15082_amd.build`")
 _lib = C.CDLL(LIB_PATH)
 
-MREM_OK, MREM_EINVAL, MREM_ESHAPE, MREM_EWORKSPACE, MREM_EHIP = 0, -1, -2, -3, -5
+MREM_OK, MREM_EINVAL, MREM_ESHAPE, MREM_EWORKSPACE, MREM_ENONFINITE, MREM_EHIP = 0, -1, -2, -3, -4, -5
 MREM_BF16, MREM_FP32 = 0, 1
 FIELDS = ("w_qkv", "w_o", "w_1", "w_2", "b_qkv", "b_o", "ln1_g", "ln1_b", "b_1", "b_2", "ln2_g", "ln2_b",
           "sw_qkv", "sw_o", "sw_1", "sw_2", "s_a", "z_a")
@@ -30,7 +30,9 @@ EXPORTS = ("mrem_create", "mrem_destroy", "mrem_last_error", "mrem_param_count",
            "mrem_param_offset", "mrem_param_size", "mrem_workspace_bytes", "mrem_workspace_offset", "mrem_teacher_cache_bytes",
            "mrem_quantize", "mrem_module_init_steps", "mrem_teacher_prepare", "mrem_module_calibrate",
            "mrem_module_forward", "mrem_module_forward_static", "mrem_static_scratch_bytes", "mrem_module_step", "mrem_mix_inputs", "mrem_profile_gemm_begin",
-           "mrem_profile_gemm_end")
+           "mrem_profile_gemm_end", "mrem_set_nonfinite_flag", "mrem_check_nonfinite", "mrem_schedule_lr", "mrem_schedule_lambda",
+           "mrem_queue_bytes", "mrem_queue_create", "mrem_queue_destroy", "mrem_queue_size", "mrem_queue_write_slot", "mrem_queue_push",
+           "mrem_queue_publish", "mrem_queue_entry")
 
 
 class mrem_config(C.Structure):
@@ -62,7 +64,7 @@ _lib.mrem_workspace_offset.argtypes = [_vp, _i32, _i32, _i32, _i32]
 _lib.mrem_workspace_offset.restype = _i64
 _lib.mrem_teacher_cache_bytes.argtypes = [_vp]
 _lib.mrem_teacher_cache_bytes.restype = _sz
-_lib.mrem_quantize.argtypes = [_vp, _i64, _i64, _i32, _i32, _vp, _vp, _vp]
+_lib.mrem_quantize.argtypes = [_vp, _i64, _i64, _i32, _i32, _i32, _vp, _vp, _vp]
 _lib.mrem_quantize.restype = C.c_int
 _lib.mrem_module_init_steps.argtypes = [_vp, _vp, _vp]
 _lib.mrem_module_init_steps.restype = C.c_int
@@ -76,17 +78,41 @@ _lib.mrem_module_forward_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _
 _lib.mrem_module_forward_static.restype = C.c_int
 _lib.mrem_static_scratch_bytes.argtypes = []
 _lib.mrem_static_scratch_bytes.restype = _sz
-_lib.mrem_module_step.argtypes = [_vp, _vp, _vp, _vp, _i64, _f32, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp,
+_lib.mrem_module_step.argtypes = [_vp, _vp, _vp, _vp, _i64, _f32, _f32, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp,
                                   _vp, _vp, _sz, _vp]
 _lib.mrem_module_step.restype = C.c_int
 _lib.mrem_mix_inputs.argtypes = [_vp, _vp, _vp, _f32, _vp, _i64, _vp]
 _lib.mrem_mix_inputs.restype = C.c_int
 
 
-_lib.mrem_profile_gemm_begin.argtypes = []
-_lib.mrem_profile_gemm_begin.restype = None
-_lib.mrem_profile_gemm_end.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i64)]
+_lib.mrem_profile_gemm_begin.argtypes = [_vp]
+_lib.mrem_profile_gemm_begin.restype = C.c_int
+_lib.mrem_profile_gemm_end.argtypes = [_vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i64)]
 _lib.mrem_profile_gemm_end.restype = C.c_int
+_lib.mrem_set_nonfinite_flag.argtypes = [_vp, _vp]
+_lib.mrem_set_nonfinite_flag.restype = C.c_int
+_lib.mrem_check_nonfinite.argtypes = [_vp, _vp]
+_lib.mrem_check_nonfinite.restype = C.c_int
+_lib.mrem_schedule_lr.argtypes = [C.c_double, _i64, _i64]
+_lib.mrem_schedule_lr.restype = C.c_double
+_lib.mrem_schedule_lambda.argtypes = [_i64, _i64]
+_lib.mrem_schedule_lambda.restype = C.c_double
+_lib.mrem_queue_bytes.argtypes = [_i32, _sz, _sz]
+_lib.mrem_queue_bytes.restype = _sz
+_lib.mrem_queue_create.argtypes = [_i32, _sz, _sz, _vp, C.POINTER(_vp)]
+_lib.mrem_queue_create.restype = C.c_int
+_lib.mrem_queue_destroy.argtypes = [_vp]
+_lib.mrem_queue_destroy.restype = None
+_lib.mrem_queue_size.argtypes = [_vp]
+_lib.mrem_queue_size.restype = _i32
+_lib.mrem_queue_write_slot.argtypes = [_vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp)]
+_lib.mrem_queue_write_slot.restype = C.c_int
+_lib.mrem_queue_push.argtypes = [_vp, _vp, _vp, _vp, _sz, _sz, _vp]
+_lib.mrem_queue_push.restype = C.c_int
+_lib.mrem_queue_publish.argtypes = [_vp]
+_lib.mrem_queue_publish.restype = C.c_int
+_lib.mrem_queue_entry.argtypes = [_vp, _i32, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp)]
+_lib.mrem_queue_entry.restype = C.c_int
 
 
 class MremError(RuntimeError):
@@ -168,8 +194,8 @@ def mrem_teacher_cache_bytes(ctx) -> int:
     return _lib.mrem_teacher_cache_bytes(ctx)
 
 
-def mrem_quantize(w, N, K, bits, init_scale, scale, codes, stream=None) -> None:
-    _check(_lib.mrem_quantize(_ptr(w), N, K, bits, init_scale, _ptr(scale), _ptr(codes), _stream(stream)))
+def mrem_quantize(w, N, K, bits, per_channel, init_scale, scale, codes, stream=None) -> None:
+    _check(_lib.mrem_quantize(_ptr(w), N, K, bits, per_channel, init_scale, _ptr(scale), _ptr(codes), _stream(stream)))
 
 
 def mrem_module_init_steps(ctx, params, stream=None) -> None:
@@ -203,9 +229,9 @@ def mrem_module_forward_static(ctx, params, teacher, teacher_cache, x_fp, x_q, s
                                            _ptr(seqlens), batch, seq, _ptr(per_layer_fp), _ptr(per_layer_q), _stream(stream)), ctx)
 
 
-def mrem_module_step(ctx, params, adam_m, adam_v, step_index, lr, teacher, teacher_cache, x_fp, x_q, seqlens, batch, seq,
+def mrem_module_step(ctx, params, adam_m, adam_v, step_index, lr, lam, teacher, teacher_cache, x_fp, x_q, seqlens, batch, seq,
                      loss_out, per_layer_fp, per_layer_q, grads_out, workspace, stream=None) -> None:
-    _check(_lib.mrem_module_step(ctx, _ptr(params), _ptr(adam_m), _ptr(adam_v), step_index, lr, _ptr(teacher),
+    _check(_lib.mrem_module_step(ctx, _ptr(params), _ptr(adam_m), _ptr(adam_v), step_index, lr, lam, _ptr(teacher),
                                  _ptr(teacher_cache), _ptr(x_fp), _ptr(x_q), _ptr(seqlens), batch, seq, _ptr(loss_out),
                                  _ptr(per_layer_fp), _ptr(per_layer_q), _ptr(grads_out), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream(stream)), ctx)
@@ -215,15 +241,75 @@ def mrem_mix_inputs(ctx, x_fp, x_q, lam, out, n, stream=None) -> None:
     _check(_lib.mrem_mix_inputs(ctx, _ptr(x_fp), _ptr(x_q), lam, _ptr(out), n, _stream(stream)), ctx)
 
 
-def mrem_profile_gemm_begin() -> None:
-    _lib.mrem_profile_gemm_begin()
+def mrem_profile_gemm_begin(ctx) -> None:
+    _check(_lib.mrem_profile_gemm_begin(ctx), ctx)
 
 
-def mrem_profile_gemm_end():
+def mrem_profile_gemm_end(ctx):
     """((ms, flops, launches) of the products on bf16 operands, the same for int8 operands) since _begin."""
     ms, fl, n = (C.c_double * 2)(), (C.c_double * 2)(), (_i64 * 2)()
-    _check(_lib.mrem_profile_gemm_end(ms, fl, n))
+    _check(_lib.mrem_profile_gemm_end(ctx, ms, fl, n), ctx)
     return (ms[0], fl[0], n[0]), (ms[1], fl[1], n[1])
+
+
+def mrem_set_nonfinite_flag(ctx, flag) -> None:
+    _check(_lib.mrem_set_nonfinite_flag(ctx, _ptr(flag)), ctx)
+
+
+def mrem_check_nonfinite(ctx, stream=None) -> None:
+    _check(_lib.mrem_check_nonfinite(ctx, _stream(stream)), ctx)
+
+
+def mrem_schedule_lr(lr0: float, t: int, total: int) -> float:
+    return _lib.mrem_schedule_lr(lr0, t, total)
+
+
+def mrem_schedule_lambda(t: int, tf_steps: int) -> float:
+    return _lib.mrem_schedule_lambda(t, tf_steps)
+
+
+def mrem_queue_bytes(depth: int, half_bytes: int, lengths_bytes: int) -> int:
+    return _lib.mrem_queue_bytes(depth, half_bytes, lengths_bytes)
+
+
+def mrem_queue_create(depth: int, half_bytes: int, lengths_bytes: int, device_mem) -> int:
+    out = _vp()
+    _check(_lib.mrem_queue_create(depth, half_bytes, lengths_bytes, _ptr(device_mem), C.byref(out)))
+    return out.value
+
+
+def mrem_queue_destroy(q) -> None:
+    _lib.mrem_queue_destroy(q)
+
+
+def mrem_queue_size(q) -> int:
+    return _lib.mrem_queue_size(q)
+
+
+def _three(fn, *args):
+    a, b, c = _vp(), _vp(), _vp()
+    _check(fn(*args, C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
+
+
+def mrem_queue_write_slot(q):
+    """Device addresses (fp half, quantized half, lengths or None) of the slot being written."""
+    return _three(_lib.mrem_queue_write_slot, q)
+
+
+def mrem_queue_push(q, fp, qd, lengths, stream=None) -> None:
+    nb = fp.numel() * fp.element_size()
+    lb = 0 if lengths is None else lengths.numel() * lengths.element_size()
+    _check(_lib.mrem_queue_push(q, _ptr(fp), _ptr(qd), _ptr(lengths), nb, lb, _stream(stream)))
+
+
+def mrem_queue_publish(q) -> None:
+    _check(_lib.mrem_queue_publish(q))
+
+
+def mrem_queue_entry(q, age: int):
+    """Device addresses (fp half, quantized half, lengths or None) of the entry of that age (0 = newest)."""
+    return _three(_lib.mrem_queue_entry, q, age)
 
 
 # ------------------------------------------------------------------------------
@@ -309,12 +395,12 @@ class MremModule:
                             self.workspace)
         return out_fp, out_q
 
-    def step(self, x_fp, x_q, lr, seqlens=None, out_fp=None, out_q=None, grads_out=None):
+    def step(self, x_fp, x_q, lr, seqlens=None, out_fp=None, out_q=None, grads_out=None, lam=0.0):
         b, s = x_fp.shape[0], x_fp.shape[1]
         if out_fp is None or out_q is None:
             out_fp, out_q = self.new_outputs(b, s)
         self.step_index += 1
-        mrem_module_step(self.ctx, self.params, self.adam_m, self.adam_v, self.step_index, lr, self.teacher,
+        mrem_module_step(self.ctx, self.params, self.adam_m, self.adam_v, self.step_index, lr, lam, self.teacher,
                          self.teacher_cache, x_fp, x_q, seqlens, b, s, self.loss, out_fp, out_q, grads_out, self.workspace)
         return out_fp, out_q
 

@@ -30,6 +30,8 @@ struct mrem_ctx {
   std::vector<hipEvent_t> ev_ready;  // [4 * l + i]: the output gradient of linear layer i of layer l is written
   std::vector<hipEvent_t> ev_done;   // [4 * l + i]: its weight-gradient product has read it
   int side_device = -1;
+  GemmProfile prof;                // per-launch timing of the matrix products (measurement aid)
+  int32_t* nonfinite_flag = nullptr;  // device, caller-owned, optional
 };
 
 static mrem_status fail(const mrem_ctx* ctx, mrem_status st, const std::string& msg) {
@@ -154,7 +156,7 @@ struct Plan {
   // teacher scratch
   size_t t_qkv, t_ctx, t_o, t_x1, t_g, t_y, t_mu, t_rstd;
   // backward scratch
-  size_t dr2, dr1, dxh, dx1h, dch, dc, dgh, du, dqkvh, dqkv, s_da, s_ph, partials, partials_per_layer, grads, pmax;
+  size_t dr2, dr1, dxh, dx1h, dch, dc, dgh, du, dqkvh, dqkv, s_da, s_ph, partials, partials_per_layer, grads, pmax, xmix;
   size_t total;
 };
 
@@ -205,6 +207,7 @@ Plan make_plan(const mrem_ctx* c, int B, int S) {
   p.partials_per_layer = np;
   p.partials = b.take(np * 4 * c->L);
   p.grads = b.take((size_t)mrem_param_count(c) * 4);
+  p.xmix = b.take(T * H * es);  // Eq. 4: the mixed module input, when a step is given a lambda > 0
   p.total = b.off;
   return p;
 }
@@ -216,6 +219,7 @@ struct Run {
   hipStream_t st;
   int B, S, T;
   const int32_t* seqlens;
+  GemmProfile* prof = nullptr;
   template <class X = void> X* at(size_t off) const { return reinterpret_cast<X*>(ws + off); }
   bool i8() const { return i8_config(c) && T % 128 == 0; }
   int8_t* at8(size_t off) const { return i8() ? reinterpret_cast<int8_t*>(ws + off) : nullptr; }
@@ -272,10 +276,10 @@ void student_linear(const Run& r, const float* params, int l, int i, const void*
   if (r.i8() && in_codes8) {
     // unsigned codes (GELU output) are stored recentred by half their range; the epilogue adds that back
     if (q.z) e.beta_alpha = 0.5f * (q.qp + 1.f);
-    gemm_i8(in_codes8, c->wK[i], r.at8(r.p.lw[l].wcodes8[i]), c->wK[i], out, c->wN[i], r.T, c->wN[i], c->wK[i], e, r.st);
+    gemm_i8(in_codes8, c->wK[i], r.at8(r.p.lw[l].wcodes8[i]), c->wK[i], out, c->wN[i], r.T, c->wN[i], c->wK[i], e, r.st, r.prof);
     return;
   }
-  gemm_nt(c->dt, in_codes, c->wK[i], r.at(r.p.lw[l].wcodes[i]), c->wK[i], out, c->wN[i], r.T, c->wN[i], c->wK[i], e, r.st);
+  gemm_nt(c->dt, in_codes, c->wK[i], r.at(r.p.lw[l].wcodes[i]), c->wK[i], out, c->wN[i], r.T, c->wN[i], c->wK[i], e, r.st, r.prof);
 }
 
 void prepare_weights(const Run& r, const float* params) {
@@ -298,7 +302,10 @@ void prepare_weights(const Run& r, const float* params) {
 }
 
 // Layers [l0, l1) of the quantized module (l1 < 0: to the last layer).
-void student_forward(const Run& r, const float* params, const void* x_q, void* per_layer_q, int l0 = 0, int l1 = -1) {
+// mix_fp != null (with 0 < lambda <= 1): the module input is lambda * mix_fp + (1 - lambda) * x_in (Eq. 4), formed and
+// stored in x_q (a workspace buffer) by the kernel that quantizes the first layer's input.
+void student_forward(const Run& r, const float* params, const void* x_q, void* per_layer_q, int l0 = 0, int l1 = -1,
+                     const void* mix_fp = nullptr, const void* mix_in = nullptr, float lambda = 0.f) {
   const mrem_ctx* c = r.c;
   const size_t es = dt_size(c->dt);
   const int H = c->H, F = c->F, T = r.T;
@@ -311,7 +318,10 @@ void student_forward(const Run& r, const float* params, const void* x_q, void* p
     void* f = (char*)per_layer_q + slice * l;
     // every code tensor that feeds a linear layer is also written as int8 when the int8 products are in use
     // (the input codes of layers 1.. come from the second LayerNorm of the layer before)
-    if (l == 0) act_quantize(c->dt, x, r.at(w.xcodes), (int64_t)T * H, make_q(c, params, l, 0), r.st, r.at8(w.xcodes8));
+    if (l == 0 && mix_fp)
+      mix_quantize(c->dt, mix_fp, mix_in, lambda, 1.f - lambda, const_cast<void*>(x), r.at(w.xcodes), (int64_t)T * H, make_q(c, params, l, 0), r.st,
+                   r.at8(w.xcodes8));
+    else if (l == 0) act_quantize(c->dt, x, r.at(w.xcodes), (int64_t)T * H, make_q(c, params, l, 0), r.st, r.at8(w.xcodes8));
     student_linear(r, params, l, 0, r.at(w.xcodes), r.at8(w.xcodes8), r.at(w.qkv));
     const AttnQ aq = make_attn_q(c, params, l, true);
     qkv_quantize(c->dt, r.at(w.qkv), r.at(w.qkvcodes), T, H, aq.q, aq.k, aq.v, r.st);
@@ -370,7 +380,7 @@ void teacher_forward(const Run& r, const float* teacher, const void* cache, cons
     Epilogue e;
     if (calib_params) calib(l, 0, x, c->dt, T, H, H, 0, 0);
     e.bias = base + c->foff[MREM_F_B_QKV];
-    gemm_nt(c->dt, x, H, W(0), H, r.at(r.p.t_qkv), 3 * H, T, 3 * H, H, e, r.st);
+    gemm_nt(c->dt, x, H, W(0), H, r.at(r.p.t_qkv), 3 * H, T, 3 * H, H, e, r.st, r.prof);
     if (calib_params) {
       const char* q = r.at<char>(r.p.t_qkv);
       calib(l, 1, q, c->dt, T, H, 3 * H, 0, 0);
@@ -388,23 +398,23 @@ void teacher_forward(const Run& r, const float* teacher, const void* cache, cons
       calib(l, 5, r.at(r.p.t_ctx), c->dt, T, H, H, 0, 0);
     }
     e.bias = base + c->foff[MREM_F_B_O];
-    gemm_nt(c->dt, r.at(r.p.t_ctx), H, W(1), H, r.at(r.p.t_o), H, T, H, H, e, r.st);
+    gemm_nt(c->dt, r.at(r.p.t_ctx), H, W(1), H, r.at(r.p.t_o), H, T, H, H, e, r.st, r.prof);
     ln_fwd(c->dt, x, r.at(r.p.t_o), base + c->foff[MREM_F_LN1_G], base + c->foff[MREM_F_LN1_B], r.at(r.p.t_x1), nullptr, QArg(),
            r.at<float>(r.p.t_mu), r.at<float>(r.p.t_rstd), T, H, c->cfg.ln_eps, r.st);
     if (calib_params) calib(l, 6, r.at(r.p.t_x1), c->dt, T, H, H, 0, 0);
     e.bias = base + c->foff[MREM_F_B_1];
     if (calib_params) {
       // pre-activation first, so that the range of gelu(u) can be measured on unrounded values
-      gemm_nt(c->dt, r.at(r.p.t_x1), H, W(2), H, r.at(r.p.t_g), F, T, F, H, e, r.st);
+      gemm_nt(c->dt, r.at(r.p.t_x1), H, W(2), H, r.at(r.p.t_g), F, T, F, H, e, r.st, r.prof);
       calib(l, 7, r.at(r.p.t_g), c->dt, T, F, F, 1, 2);
       gelu_quantize(c->dt, r.at(r.p.t_g), r.at(r.p.t_g), (int64_t)T * F, QArg(), r.st);
     } else {
       e.gelu = 1;
-      gemm_nt(c->dt, r.at(r.p.t_x1), H, W(2), H, r.at(r.p.t_g), F, T, F, H, e, r.st);
+      gemm_nt(c->dt, r.at(r.p.t_x1), H, W(2), H, r.at(r.p.t_g), F, T, F, H, e, r.st, r.prof);
       e.gelu = 0;
     }
     e.bias = base + c->foff[MREM_F_B_2];
-    gemm_nt(c->dt, r.at(r.p.t_g), F, W(3), F, r.at(r.p.t_y), H, T, H, F, e, r.st);
+    gemm_nt(c->dt, r.at(r.p.t_g), F, W(3), F, r.at(r.p.t_y), H, T, H, F, e, r.st, r.prof);
     ln_fwd(c->dt, r.at(r.p.t_x1), r.at(r.p.t_y), base + c->foff[MREM_F_LN2_G], base + c->foff[MREM_F_LN2_B], f, nullptr, QArg(),
            r.at<float>(r.p.t_mu), r.at<float>(r.p.t_rstd), T, H, c->cfg.ln_eps, r.st);
   }
@@ -420,13 +430,13 @@ void wgrad(const Run& r, const float* params, float* grads, int l, int i, const 
   if (q.on) e.alpha = q.s;  // the offset term z * db[n] of an asymmetric input quantizer is added by the update kernel
   e.out_f32 = 1;
   e.c_zeroed = 1;  // the step starts by zeroing the gradients that are formed in k-slices
-  gemm(c->dt, 1, 1, dy, c->wN[i], codes_in, c->wK[i], g + c->foff[kWField[i]], c->wK[i], c->wN[i], c->wK[i], r.T, e, r.st);
+  gemm(c->dt, 1, 1, dy, c->wN[i], codes_in, c->wK[i], g + c->foff[kWField[i]], c->wK[i], c->wN[i], c->wK[i], r.T, e, r.st, r.prof);
 }
 // input-gradient product: d(in^) = dY * W^ with the dequantized weights [N_out, K_in]
 void dgrad(const Run& r, int l, int i, const void* dy, void* out) {
   const mrem_ctx* c = r.c;
   Epilogue e;
-  gemm(c->dt, 0, 1, dy, c->wN[i], r.at(r.p.lw[l].what[i]), c->wK[i], out, c->wK[i], r.T, c->wK[i], c->wN[i], e, r.st);
+  gemm(c->dt, 0, 1, dy, c->wN[i], r.at(r.p.lw[l].what[i]), c->wK[i], out, c->wK[i], r.T, c->wK[i], c->wN[i], e, r.st, r.prof);
 }
 
 // Zeroes what the backward pass adds into (weight gradients formed in two k-slices) or never
@@ -600,7 +610,7 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
     (void)hipEventRecord(up.ev_join, up.side);
     (void)hipStreamWaitEvent(r.st, up.ev_join, 0);
   }
-  loss_total(loss_out, L, r.st);
+  loss_total(loss_out, L, c->nonfinite_flag, r.st);
 }
 
 AdamArg adam_arg(const mrem_ctx* c, int64_t step, float lr) {
@@ -685,15 +695,16 @@ extern "C" int64_t mrem_workspace_offset(const mrem_ctx* ctx, int32_t batch, int
   return -1;
 }
 
-extern "C" mrem_status mrem_quantize(const float* w, int64_t N, int64_t K, int32_t bits, int32_t init_scale, float* scale, int8_t* codes,
-                                     void* hip_stream) {
+extern "C" mrem_status mrem_quantize(const float* w, int64_t N, int64_t K, int32_t bits, int32_t per_channel, int32_t init_scale,
+                                     float* scale, int8_t* codes, void* hip_stream) {
   const mrem_ctx* ctx = nullptr;
   REQUIRE_PTR(w, "mrem_quantize");
   REQUIRE_PTR(scale, "mrem_quantize");
   REQUIRE_PTR(codes, "mrem_quantize");
   if (bits < 2 || bits > 8) return fail(nullptr, MREM_EINVAL, "mrem_quantize: bits must be in 2..8");
   if (N < 1 || K < 1 || N > 0x7fffffff) return fail(nullptr, MREM_ESHAPE, "mrem_quantize: N and K must be >= 1 (N < 2^31)");
-  weight_quantize_i8(w, scale, codes, N, K, bits, init_scale, (hipStream_t)hip_stream);
+  if (per_channel != 0 && per_channel != 1) return fail(nullptr, MREM_EINVAL, "mrem_quantize: per_channel must be 0 or 1");
+  weight_quantize_i8(w, scale, codes, N, K, bits, per_channel, init_scale, (hipStream_t)hip_stream);
   return finish(nullptr, "mrem_quantize");
 }
 
@@ -736,7 +747,7 @@ extern "C" mrem_status mrem_module_calibrate(mrem_ctx* ctx, float* params, const
   REQUIRE_PTR(teacher_cache, "mrem_module_calibrate");
   REQUIRE_PTR(x_fp, "mrem_module_calibrate");
   if (ctx->cfg.a_bits == 0) return fail(ctx, MREM_EINVAL, "mrem_module_calibrate: activation quantizers are off (a_bits = 0)");
-  Run r{ctx, plan, (char*)workspace, (hipStream_t)hip_stream, batch, seq, batch * seq, seqlens};
+  Run r{ctx, plan, (char*)workspace, (hipStream_t)hip_stream, batch, seq, batch * seq, seqlens, &ctx->prof};
   // Layer by layer with two alternating output buffers: only the ranges are wanted, not the per-layer outputs.
   {
     mrem_ctx one = *ctx;
@@ -763,7 +774,7 @@ mrem_status forward_impl(mrem_ctx* ctx, const float* params, const float* teache
   mrem_status s = check_common(ctx, batch, seq, workspace, workspace_bytes, who, &plan);
   if (s != MREM_OK) return s;
   if (!per_layer_fp && !per_layer_q) return fail(ctx, MREM_EINVAL, std::string(who) + ": both outputs are null");
-  Run r{ctx, plan, (char*)workspace, (hipStream_t)hip_stream, batch, seq, batch * seq, seqlens};
+  Run r{ctx, plan, (char*)workspace, (hipStream_t)hip_stream, batch, seq, batch * seq, seqlens, &ctx->prof};
   if (per_layer_fp) {
     REQUIRE_PTR(teacher, who);
     REQUIRE_PTR(teacher_cache, who);
@@ -832,7 +843,7 @@ extern "C" mrem_status mrem_module_forward_static(mrem_ctx* ctx, const float* pa
 }
 
 extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* adam_m, float* adam_v, int64_t step_index, float lr,
-                                        const float* teacher, const void* teacher_cache, const void* x_fp, const void* x_q,
+                                        float lambda, const float* teacher, const void* teacher_cache, const void* x_fp, const void* x_q,
                                         const int32_t* seqlens, int32_t batch, int32_t seq, float* loss_out, void* per_layer_fp,
                                         void* per_layer_q, float* grads_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
   Plan plan;
@@ -850,7 +861,8 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
   REQUIRE_PTR(per_layer_q, "mrem_module_step");
   if (grads_out && !aligned16(grads_out)) return fail(ctx, MREM_EINVAL, "mrem_module_step: grads_out misaligned");
   if (step_index < 1) return fail(ctx, MREM_EINVAL, "mrem_module_step: step_index is 1-based");
-  Run r{ctx, plan, (char*)workspace, (hipStream_t)hip_stream, batch, seq, batch * seq, seqlens};
+  if (!(lambda >= 0.f && lambda <= 1.f)) return fail(ctx, MREM_EINVAL, "mrem_module_step: lambda must be in [0,1]");
+  Run r{ctx, plan, (char*)workspace, (hipStream_t)hip_stream, batch, seq, batch * seq, seqlens, &ctx->prof};
   float* grads = grads_out ? grads_out : r.at<float>(r.p.grads);
   // The teacher's forward pass shares nothing with the quantized forward pass (its own scratch, its
   // own outputs), so it runs on a side stream, forked from the caller's stream and joined before
@@ -860,7 +872,11 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
   if (!ctx->side && !create_side(ctx, dev))
     return fail(ctx, MREM_EHIP, "mrem_module_step: cannot create the side stream and its events");
   if (dev != ctx->side_device) return fail(ctx, MREM_EINVAL, "mrem_module_step: the context was first used on another device");
-  const bool fork = !gemm_profile_active();  // per-launch timing wants every product alone on the device
+  const bool fork = !ctx->prof.on;  // per-launch timing wants every product alone on the device
+  // Eq. 4: with lambda > 0 the quantized module reads lambda * x_fp + (1 - lambda) * x_q, formed by its first kernel
+  const bool mix = lambda > 0.f && x_fp != x_q;
+  const void* x_in = mix ? r.at(r.p.xmix) : x_q;
+  const void* mix_fp = mix ? x_fp : nullptr;
   // Before the passes: the gradient slots that are added into or never written are zeroed.
   if (fork) {
     Run rt = r;
@@ -873,19 +889,19 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
     // start also when the caller's queue was empty
     for (int l = 0; l < ctx->L; ++l) {
       teacher_forward(rt, teacher, teacher_cache, x_fp, per_layer_fp, nullptr, l, l + 1);
-      student_forward(r, params, x_q, per_layer_q, l, l + 1);
+      student_forward(r, params, x_in, per_layer_q, l, l + 1, mix_fp, x_q, lambda);
     }
     (void)hipEventRecord(ctx->ev_join, ctx->side);
   } else {
     teacher_forward(r, teacher, teacher_cache, x_fp, per_layer_fp, nullptr);
     zero_gradient_slots(r, grads);
     prepare_weights(r, params);
-    student_forward(r, params, x_q, per_layer_q);
+    student_forward(r, params, x_in, per_layer_q, 0, -1, mix_fp, x_q, lambda);
   }
   if (fork) (void)hipStreamWaitEvent(r.st, ctx->ev_join, 0);
   const Update up{params, adam_m, adam_v, adam_arg(ctx, step_index, lr), grads_out != nullptr, fork ? ctx->side : nullptr,
                   ctx->ev_layer.data(), ctx->ev_ready.data(), ctx->ev_done.data(), ctx->ev_join};
-  student_backward(r, params, x_q, per_layer_fp, per_layer_q, grads, loss_out, up);
+  student_backward(r, params, x_in, per_layer_fp, per_layer_q, grads, loss_out, up);
   update_vectors(r, up, grads);
   return finish(ctx, "mrem_module_step");
 }
@@ -902,8 +918,97 @@ extern "C" mrem_status mrem_mix_inputs(mrem_ctx* ctx, const void* x_fp, const vo
   return finish(ctx, "mrem_mix_inputs");
 }
 
-extern "C" void mrem_profile_gemm_begin(void) { gemm_profile_begin(); }
-extern "C" mrem_status mrem_profile_gemm_end(double* ms, double* flops, int64_t* launches) {
-  if (!ms || !flops || !launches) return fail(nullptr, MREM_EINVAL, "mrem_profile_gemm_end: null argument");
-  return gemm_profile_end(ms, flops, launches) == 0 ? MREM_OK : fail(nullptr, MREM_EHIP, "mrem_profile_gemm_end: event query failed");
+extern "C" mrem_status mrem_profile_gemm_begin(mrem_ctx* ctx) {
+  if (!ctx) return fail(nullptr, MREM_EINVAL, "mrem_profile_gemm_begin: null context");
+  gemm_profile_begin(&ctx->prof);
+  return MREM_OK;
+}
+extern "C" mrem_status mrem_profile_gemm_end(mrem_ctx* ctx, double* ms, double* flops, int64_t* launches) {
+  if (!ctx || !ms || !flops || !launches) return fail(ctx, MREM_EINVAL, "mrem_profile_gemm_end: null argument");
+  return gemm_profile_end(&ctx->prof, ms, flops, launches) == 0 ? MREM_OK : fail(ctx, MREM_EHIP, "mrem_profile_gemm_end: event query failed");
+}
+
+extern "C" mrem_status mrem_set_nonfinite_flag(mrem_ctx* ctx, int32_t* device_flag) {
+  if (!ctx) return fail(nullptr, MREM_EINVAL, "mrem_set_nonfinite_flag: null context");
+  if (device_flag && (reinterpret_cast<uintptr_t>(device_flag) & 3u)) return fail(ctx, MREM_EINVAL, "mrem_set_nonfinite_flag: misaligned flag");
+  ctx->nonfinite_flag = device_flag;
+  return MREM_OK;
+}
+extern "C" mrem_status mrem_check_nonfinite(mrem_ctx* ctx, void* hip_stream) {
+  if (!ctx) return fail(nullptr, MREM_EINVAL, "mrem_check_nonfinite: null context");
+  if (!ctx->nonfinite_flag) return fail(ctx, MREM_EINVAL, "mrem_check_nonfinite: no flag has been set");
+  int32_t host = 0;
+  if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess ||
+      hipMemcpy(&host, ctx->nonfinite_flag, sizeof(host), hipMemcpyDeviceToHost) != hipSuccess)
+    return fail(ctx, MREM_EHIP, "mrem_check_nonfinite: cannot read the flag");
+  if (host) return fail(ctx, MREM_ENONFINITE, "a step since the flag was last cleared produced a non-finite loss");
+  return MREM_OK;
+}
+
+// ------------------------------------------------------------------------------
+// schedules (host arithmetic) and the input queue of Algorithm 1
+// ------------------------------------------------------------------------------
+extern "C" double mrem_schedule_lr(double lr0, int64_t t, int64_t total) {
+  if (total < 1 || t < 0) return 0.0;
+  return lr0 * (1.0 - (double)t / (double)total);
+}
+extern "C" double mrem_schedule_lambda(int64_t t, int64_t tf_steps) {
+  if (tf_steps < 1 || t < 0) return 0.0;
+  const double l = 1.0 - (double)t / (double)tf_steps;
+  return l > 0.0 ? l : 0.0;
+}
+
+struct mrem_queue {
+  int depth;            // readable entries
+  size_t half_bytes, len_bytes;
+  char* mem;            // device, caller-owned: (depth + 1) slots of [fp half | q half | lengths]
+  int64_t published;    // entries handed over so far
+  size_t slot_bytes() const { return 2 * half_bytes + len_bytes; }
+};
+static size_t round256(size_t b) { return (b + 255) & ~size_t(255); }
+extern "C" size_t mrem_queue_bytes(int32_t depth, size_t half_bytes, size_t lengths_bytes) {
+  if (depth < 1) return 0;
+  return (size_t)(depth + 1) * (2 * round256(half_bytes) + round256(lengths_bytes));
+}
+extern "C" mrem_status mrem_queue_create(int32_t depth, size_t half_bytes, size_t lengths_bytes, void* device_mem, mrem_queue** out) {
+  if (!out || !device_mem || !aligned16(device_mem)) return fail(nullptr, MREM_EINVAL, "mrem_queue_create: null or misaligned argument");
+  if (depth < 1 || half_bytes < 1) return fail(nullptr, MREM_ESHAPE, "mrem_queue_create: depth and half_bytes must be >= 1");
+  mrem_queue* q = new mrem_queue();
+  q->depth = depth; q->half_bytes = round256(half_bytes); q->len_bytes = round256(lengths_bytes); q->mem = (char*)device_mem; q->published = 0;
+  *out = q;
+  return MREM_OK;
+}
+extern "C" void mrem_queue_destroy(mrem_queue* q) { delete q; }
+extern "C" int32_t mrem_queue_size(const mrem_queue* q) { return q ? (int32_t)(q->published < q->depth ? q->published : q->depth) : -1; }
+extern "C" mrem_status mrem_queue_write_slot(mrem_queue* q, void** fp, void** qd, void** lengths) {
+  if (!q || !fp || !qd) return fail(nullptr, MREM_EINVAL, "mrem_queue_write_slot: null argument");
+  char* slot = q->mem + (size_t)(q->published % (q->depth + 1)) * q->slot_bytes();
+  *fp = slot; *qd = slot + q->half_bytes;
+  if (lengths) *lengths = q->len_bytes ? slot + 2 * q->half_bytes : nullptr;
+  return MREM_OK;
+}
+extern "C" mrem_status mrem_queue_push(mrem_queue* q, const void* fp, const void* qd, const void* lengths, size_t half_bytes,
+                                       size_t lengths_bytes, void* hip_stream) {
+  if (!q || !fp || !qd) return fail(nullptr, MREM_EINVAL, "mrem_queue_push: null argument");
+  if (half_bytes > q->half_bytes || lengths_bytes > q->len_bytes) return fail(nullptr, MREM_ESHAPE, "mrem_queue_push: entry larger than a slot");
+  void *dfp, *dq, *dl;
+  (void)mrem_queue_write_slot(q, &dfp, &dq, &dl);
+  hipStream_t st = (hipStream_t)hip_stream;
+  bool ok = hipMemcpyAsync(dfp, fp, half_bytes, hipMemcpyDeviceToDevice, st) == hipSuccess &&
+            hipMemcpyAsync(dq, qd, half_bytes, hipMemcpyDeviceToDevice, st) == hipSuccess;
+  if (lengths && lengths_bytes) ok = ok && hipMemcpyAsync(dl, lengths, lengths_bytes, hipMemcpyDeviceToDevice, st) == hipSuccess;
+  return ok ? MREM_OK : fail(nullptr, MREM_EHIP, "mrem_queue_push: copy failed");
+}
+extern "C" mrem_status mrem_queue_publish(mrem_queue* q) {
+  if (!q) return fail(nullptr, MREM_EINVAL, "mrem_queue_publish: null queue");
+  q->published += 1;
+  return MREM_OK;
+}
+extern "C" mrem_status mrem_queue_entry(const mrem_queue* q, int32_t age, void** fp, void** qd, void** lengths) {
+  if (!q || !fp || !qd) return fail(nullptr, MREM_EINVAL, "mrem_queue_entry: null argument");
+  if (age < 0 || age >= mrem_queue_size(q)) return fail(nullptr, MREM_EINVAL, "mrem_queue_entry: no entry of that age");
+  char* slot = q->mem + (size_t)((q->published - 1 - age) % (q->depth + 1)) * q->slot_bytes();
+  *fp = slot; *qd = slot + q->half_bytes;
+  if (lengths) *lengths = q->len_bytes ? slot + 2 * q->half_bytes : nullptr;
+  return MREM_OK;
 }

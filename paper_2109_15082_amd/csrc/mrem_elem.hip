@@ -121,6 +121,32 @@ __global__ void act_quantize_k(const T* __restrict__ a, T* __restrict__ codes, i
 void act_quantize(int dt, const void* a, void* codes, int64_t n, QArg q, hipStream_t st, int8_t* codes8) {
   MREM_DISPATCH(dt, hipLaunchKernelGGL(act_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)a, (T*)codes, n / 8, q, codes8));
 }
+// Eq. 4 folded into the input quantizer of a module's first layer: mixed = wa * a + wb * b is stored (the
+// layer's residual path and its backward pass read it) and quantized in the same pass.
+template <class T>
+__global__ void mix_quantize_k(const T* __restrict__ a, const T* __restrict__ b, float wa, float wb, T* __restrict__ mixed,
+                               T* __restrict__ codes, int64_t nchunks, QArg qa, int8_t* __restrict__ codes8) {
+  const QuantParam q = load_q(qa);
+  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
+    float x[8], y[8], v[8];
+    load8(a + c * 8, x);
+    load8(b + c * 8, y);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = round_to<T>(wa * x[j] + wb * y[j]);
+    store8(mixed + c * 8, v);
+    if (q.on) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = q_code(q_ratio_t<T>(v[j], q), q);
+    }
+    store8(codes + c * 8, v);
+    if (codes8) store8_i8(codes8 + c * 8, v, 0.f);
+  }
+}
+void mix_quantize(int dt, const void* a, const void* b, float wa, float wb, void* mixed, void* codes, int64_t n, QArg q, hipStream_t st,
+                  int8_t* codes8) {
+  MREM_DISPATCH(dt, hipLaunchKernelGGL(mix_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)a, (const T*)b, wa, wb, (T*)mixed,
+                                       (T*)codes, n / 8, q, codes8));
+}
 template <class T>
 __global__ void codes_to_i8_k(const T* __restrict__ codes, int8_t* __restrict__ codes8, int64_t nchunks, float shift) {
   for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
@@ -689,14 +715,18 @@ void reduce_jobs(const ReduceJob* jobs, int njobs, hipStream_t st) {
   }
 }
 
-__global__ void loss_total_k(float* loss_out, int n_layers) {
+__global__ void loss_total_k(float* loss_out, int n_layers, int* nonfinite_flag) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     float t = 0.f;
     for (int l = 0; l < n_layers; ++l) t += loss_out[1 + l];
     loss_out[0] = t;
+    // a NaN or infinity anywhere in the layer outputs reaches its layer's squared-error sum
+    if (nonfinite_flag && !(fabsf(t) <= FLT_MAX)) *nonfinite_flag = 1;
   }
 }
-void loss_total(float* loss_out, int n_layers, hipStream_t st) { hipLaunchKernelGGL(loss_total_k, dim3(1), dim3(64), 0, st, loss_out, n_layers); }
+void loss_total(float* loss_out, int n_layers, int* nonfinite_flag, hipStream_t st) {
+  hipLaunchKernelGGL(loss_total_k, dim3(1), dim3(64), 0, st, loss_out, n_layers, nonfinite_flag);
+}
 
 __global__ void fill_k(float* p, float v, int64_t n) {
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
@@ -792,9 +822,34 @@ __global__ void weight_quantize_i8_k(const float* __restrict__ w, float* __restr
     codes[n * K + k] = (int8_t)(int)rintf(fminf(fmaxf(v, -qp), qp));
   }
 }
-void weight_quantize_i8(const float* w, float* scale, int8_t* codes, int64_t N, int64_t K, int bits, int init_scale, hipStream_t st) {
+// one step for the whole tensor: a single block finds max |w| (initial step), every block then uses scale[0]
+__global__ void tensor_step_init_k(const float* __restrict__ w, float* __restrict__ scale, int64_t n, float qp) {
+  __shared__ float red[17];
+  float m = 0.f;
+  for (int64_t i = threadIdx.x; i < n; i += blockDim.x) m = fmaxf(m, fabsf(w[i]));
+  m = block_max(m, red);
+  float s = __fdiv_rn(m, qp);
+  if (!(s > 0.f)) s = FLT_MIN;
+  if (threadIdx.x == 0) scale[0] = s;
+}
+__global__ void tensor_quantize_i8_k(const float* __restrict__ w, const float* __restrict__ scale, int8_t* __restrict__ codes, int64_t n,
+                                     float qp) {
+  const float s = scale[0];
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    codes[i] = (int8_t)(int)rintf(fminf(fmaxf(__fdiv_rn(w[i], s), -qp), qp));
+}
+void weight_quantize_i8(const float* w, float* scale, int8_t* codes, int64_t N, int64_t K, int bits, int per_channel, int init_scale,
+                        hipStream_t st) {
   const float qp = (float)((1 << (bits - 1)) - 1);
-  hipLaunchKernelGGL(weight_quantize_i8_k, dim3((unsigned)N), dim3(256), 0, st, w, scale, codes, K, qp, init_scale);
+  if (per_channel) {
+    hipLaunchKernelGGL(weight_quantize_i8_k, dim3((unsigned)N), dim3(256), 0, st, w, scale, codes, K, qp, init_scale);
+    return;
+  }
+  const int64_t n = N * K;
+  if (init_scale) hipLaunchKernelGGL(tensor_step_init_k, dim3(1), dim3(1024), 0, st, w, scale, n, qp);
+  int g = (int)((n + 255) / 256);
+  if (g > 8192) g = 8192;
+  hipLaunchKernelGGL(tensor_quantize_i8_k, dim3(g), dim3(256), 0, st, w, (const float*)scale, codes, n, qp);
 }
 
 __global__ void weight_step_init_k(const float* __restrict__ w, float* __restrict__ scale, int64_t K, float qp) {

@@ -7,6 +7,7 @@
 
 #include <hip/hip_ext.h>
 
+#include <atomic>
 #include <cstdlib>
 #include <type_traits>
 
@@ -15,34 +16,27 @@
 namespace mrem {
 
 // ---- optional timing of every product launch with HIP events (measurement aid) ----
-// Return codes of event and attribute calls are not looked at here: the runtime keeps the last
-// error, and every entry point of the library ends by reading it (hipGetLastError).
+// The records live in a GemmProfile that the caller (a context) owns.  Return codes of event calls are
+// not looked at here: the runtime keeps the last error, and every entry point of the library ends by
+// reading it (hipGetLastError).
 namespace {
-struct GemmRecord {
-  hipEvent_t e0, e1;
-  double flops;
-  int cls = 0;  // 0: bf16 (or fp32) operands, 1: int8 operands
-};
-bool g_prof_on = false;
-std::vector<GemmRecord> g_prof;
-// While a timed launch is being issued: the event pair that the launch itself carries (the
-// runtime stamps them with the kernel's own begin and end, so no packet is added to the queue
-// and the elapsed time is the kernel's duration).
-hipEvent_t g_launch_e0 = nullptr, g_launch_e1 = nullptr;
+// While a timed launch is being issued on this thread: the event pair that the launch itself carries (the
+// runtime stamps them with the kernel's own begin and end, so no packet is added to the queue and the
+// elapsed time is the kernel's duration).
+thread_local hipEvent_t g_launch_e0 = nullptr, g_launch_e1 = nullptr;
 }  // namespace
 
-bool gemm_profile_active() { return g_prof_on; }
-void gemm_profile_begin() {
-  for (auto& r : g_prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
-  g_prof.clear();
-  g_prof_on = true;
+void gemm_profile_begin(GemmProfile* p) {
+  for (auto& r : p->recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+  p->recs.clear();
+  p->on = true;
 }
-int gemm_profile_end(double ms[2], double flops[2], int64_t launches[2]) {
-  g_prof_on = false;
+int gemm_profile_end(GemmProfile* p, double ms[2], double flops[2], int64_t launches[2]) {
+  p->on = false;
   ms[0] = ms[1] = flops[0] = flops[1] = 0.0;
   launches[0] = launches[1] = 0;
   int rc = 0;
-  for (auto& r : g_prof) {
+  for (auto& r : p->recs) {
     float e = 0.f;
     if (hipEventSynchronize(r.e1) != hipSuccess || hipEventElapsedTime(&e, r.e0, r.e1) != hipSuccess) rc = -1;
     ms[r.cls] += e;
@@ -51,7 +45,7 @@ int gemm_profile_end(double ms[2], double flops[2], int64_t launches[2]) {
     (void)hipEventDestroy(r.e0);
     (void)hipEventDestroy(r.e1);
   }
-  g_prof.clear();
+  p->recs.clear();
   return rc;
 }
 
@@ -348,13 +342,13 @@ static void launch_mfma(const void* A, int lda, const void* B, int ldb, void* C,
   constexpr int NTHREADS = 64 * WAVES_M * WAVES_N;
   constexpr size_t lds = 2 * (size_t)(OperandTile<AT, BM, NTHREADS, BK>::ELEMS + OperandTile<BT, BN, NTHREADS, BK>::ELEMS) * sizeof(bf16_t);
   // the attribute belongs to the (kernel, device) pair: set again when the current device changes
-  static int configured_dev = -1;
+  static std::atomic<int> configured_dev{-1};
   int dev = -1;
   (void)hipGetDevice(&dev);
-  if (dev != configured_dev) {
+  if (dev != configured_dev.load()) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, BK, TO, I8>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    configured_dev = dev;
+    configured_dev.store(dev);
   }
   const int tiles_m = M / BM, tiles_n = N / BN;
   if (g_launch_e0) {
@@ -376,8 +370,8 @@ static void gemm_launch(int dt, int a_t, int b_t, const void* A, int lda, const 
                         const Epilogue& e, hipStream_t st);
 
 void gemm(int dt, int a_t, int b_t, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
-          const Epilogue& e, hipStream_t st) {
-  if (!g_prof_on) {
+          const Epilogue& e, hipStream_t st, GemmProfile* prof) {
+  if (!prof || !prof->on) {
     gemm_launch(dt, a_t, b_t, A, lda, B, ldb, C, ldc, M, N, K, e, st);
     return;
   }
@@ -389,7 +383,7 @@ void gemm(int dt, int a_t, int b_t, const void* A, int lda, const void* B, int l
   g_launch_e1 = r.e1;
   gemm_launch(dt, a_t, b_t, A, lda, B, ldb, C, ldc, M, N, K, e, st);
   g_launch_e0 = g_launch_e1 = nullptr;
-  g_prof.push_back(r);
+  prof->recs.push_back(r);
 }
 
 bool gemm_i8_ok(const void* A, int lda, const void* B, int ldb, int M, int N, int K) {
@@ -426,8 +420,9 @@ static void gemm_i8_launch(const void* A, int lda, const void* B, int ldb, void*
   if (gemm_policy() == 0) { launch_mfma<128, 128, 2, 2, false, false, kRegBK, bf16_t, true>(A, lda / 2, B, ldb / 2, C, ldc, M, N, K / 2, e, st); return; }
   launch_dl_policy<false, false, bf16_t, true>(A, lda / 2, B, ldb / 2, C, ldc, M, N, K / 2, e, st, 1);
 }
-void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e, hipStream_t st) {
-  if (!g_prof_on) {
+void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e, hipStream_t st,
+             GemmProfile* prof) {
+  if (!prof || !prof->on) {
     gemm_i8_launch(A, lda, B, ldb, C, ldc, M, N, K, e, st);
     return;
   }
@@ -440,12 +435,12 @@ void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, i
   gemm_i8_launch(A, lda, B, ldb, C, ldc, M, N, K, e, st);
   g_launch_e0 = g_launch_e1 = nullptr;
   r.cls = 1;
-  g_prof.push_back(r);
+  prof->recs.push_back(r);
 }
 
 void gemm_nt(int dt, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
-             hipStream_t st) {
-  gemm(dt, 0, 0, A, lda, B, ldb, C, ldc, M, N, K, e, st);
+             hipStream_t st, GemmProfile* prof) {
+  gemm(dt, 0, 0, A, lda, B, ldb, C, ldc, M, N, K, e, st, prof);
 }
 
 // Tiles for at most half of the compute units and a long contraction (weight gradients of the

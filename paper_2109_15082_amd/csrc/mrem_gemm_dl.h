@@ -208,6 +208,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void gemm_dl_k(const 
     }
   }
   auto issue = [&](int stage_slot) {
+#ifdef MREM_DL_NOLOAD
+    if (K > 0) return;
+#endif
     unsigned char* dst = smem_dl + stage_slot * STAGE_BYTES + wave * (LPW * 1024);
 #pragma unroll
     for (int i = 0; i < LPW; ++i) {
@@ -232,6 +235,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void gemm_dl_k(const 
   const int lds0 = (int)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_dl;
 
   auto mfmas = [&](const typename OpA::frag_t (&af)[MT], const typename OpB::frag_t (&bf)[NT]) {
+#ifdef MREM_DL_NOMMA
+    if (K > 0) return;
+#endif
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -335,13 +341,13 @@ static void launch_dl(const void* A, int lda, const void* B, int ldb, void* C, i
                       hipStream_t st, int k_splits = 1) {
   constexpr int NTHREADS = 64 * WAVES_M * WAVES_N;
   constexpr size_t lds = (size_t)STAGES * (BM + BN) * RB;
-  static int configured_dev = -1;
+  static std::atomic<int> configured_dev{-1};
   int dev = -1;
   (void)hipGetDevice(&dev);
-  if (dev != configured_dev) {
+  if (dev != configured_dev.load()) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dl_k<BM, BN, WAVES_M, WAVES_N, AT, BT, STAGES, RB, TO, I8, MINB>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    configured_dev = dev;
+    configured_dev.store(dev);
   }
   const int tiles_m = M / BM, tiles_n = N / BN;
   if (g_launch_e0) {

@@ -7,6 +7,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 namespace mrem {
 
 enum { DT_BF16 = 0, DT_F32 = 1 };
@@ -38,25 +40,36 @@ struct Epilogue {
   float beta_alpha = 0.f;
 };
 
+// Timing of product launches with the pair of HIP events that a launch itself carries (measurement aid).
+// A context owns one; products launched with a profile whose `on` is set are recorded in it.
+struct GemmRecord {
+  hipEvent_t e0, e1;
+  double flops;
+  int cls = 0;  // 0: bf16 (or fp32) operands, 1: int8 operands
+};
+struct GemmProfile {
+  bool on = false;
+  std::vector<GemmRecord> recs;
+};
+void gemm_profile_begin(GemmProfile* p);
+int gemm_profile_end(GemmProfile* p, double ms[2], double flops[2], int64_t launches[2]);  // [0] bf16 operands, [1] int8 operands
+
 // C[M,N] = op(A) * op(B)^T.  a_t = 0: A is stored [M,K] (K contiguous); a_t = 1: A is stored
 // [K,M] (the contraction index is the slow one).  Same for B with N.  lda/ldb: row pitch.
 void gemm(int dt, int a_t, int b_t, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
-          const Epilogue& e, hipStream_t st);
+          const Epilogue& e, hipStream_t st, GemmProfile* prof = nullptr);
 // C[M,N] (bf16) = A[M,K] * B[N,K]^T on int8 codes with exact int32 accumulation; needs
 // gemm_i8_ok(...).  Same epilogue.
 bool gemm_i8_ok(const void* A, int lda, const void* B, int ldb, int M, int N, int K);
-void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e, hipStream_t st);
+void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e, hipStream_t st,
+             GemmProfile* prof = nullptr);
 // C[M,N] = A[M,K] * B[N,K]^T  (both operands contiguous along K)
 void gemm_nt(int dt, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
-             const Epilogue& e, hipStream_t st);
-
-// Timing of every gemm_nt launch with a pair of HIP events on its stream.
-void gemm_profile_begin();
-bool gemm_profile_active();
-int gemm_profile_end(double ms[2], double flops[2], int64_t launches[2]);  // [0] bf16 operands, [1] int8 operands
+             const Epilogue& e, hipStream_t st, GemmProfile* prof = nullptr);
 
 // ---- weights ------------------------------------------------------------------
-void weight_quantize_i8(const float* w, float* scale, int8_t* codes, int64_t N, int64_t K, int bits, int init_scale,
+// per_channel = 0: one step scale[0] for the whole tensor
+void weight_quantize_i8(const float* w, float* scale, int8_t* codes, int64_t N, int64_t K, int bits, int per_channel, int init_scale,
                         hipStream_t st);
 void weight_step_init(const float* w, float* scale, int64_t N, int64_t K, int bits, hipStream_t st);
 // scale[0..N) := max_n scale[n]  (one step for the whole matrix, kept as N equal entries)
@@ -80,6 +93,9 @@ void convert_f32(int dt, const float* src, void* dst, int64_t n, hipStream_t st)
 // ---- elementwise / normalisation ------------------------------------------------
 // codes8 (may be null): the same codes as int8, for the int8 products of the forward pass
 void act_quantize(int dt, const void* a, void* codes, int64_t n, QArg q, hipStream_t st, int8_t* codes8 = nullptr);
+// Eq. 4 in the same pass: mixed = round(wa * a + wb * b) is stored and quantized
+void mix_quantize(int dt, const void* a, const void* b, float wa, float wb, void* mixed, void* codes, int64_t n, QArg q, hipStream_t st,
+                  int8_t* codes8 = nullptr);
 // codes8 (may be null): codes - shift8 as int8 (the unsigned grid of the GELU output, recentred)
 void gelu_quantize(int dt, const void* u, void* codes, int64_t n, QArg q, hipStream_t st, int8_t* codes8 = nullptr, float shift8 = 0.f);
 // bf16/fp32 integer codes -> int8 (codes - shift); for producers without an int8 output of their own
@@ -121,7 +137,8 @@ struct ReduceJob {
 };
 constexpr int kMaxReduceJobs = 64;
 void reduce_jobs(const ReduceJob* jobs, int njobs, hipStream_t st);
-void loss_total(float* loss_out, int n_layers, hipStream_t st);
+// nonfinite_flag (device, may be null): set to 1 when the total is not finite
+void loss_total(float* loss_out, int n_layers, int* nonfinite_flag, hipStream_t st);
 void fill_f32(float* p, float v, int64_t n, hipStream_t st);
 // zeroes up to kMaxFillRegions regions in one launch
 constexpr int kMaxFillRegions = 64;

@@ -2,8 +2,8 @@
 parallel training with input queues (Section 4.2, Algorithm 1) on one GPU.
 
 Host-side orchestration only: every tensor operation is a call into the C library
-(`mrem_module_step`, `mrem_module_forward`, `mrem_mix_inputs`) or a plain device-to-device copy
-into a queue slot.  In the parallel schedule each module has its own HIP stream (default
+(`mrem_module_step` with its `lambda`, `mrem_module_forward`, the `mrem_queue_*` ring and the
+`mrem_schedule_*` formulas).  In the parallel schedule each module has its own HIP stream (default
 priority), context, parameters and workspace, so the kernels of different modules overlap on the
 device the way they would on separate devices; a step ends with an event barrier between the
 streams, which is the one message per step that neighbouring devices would exchange.
@@ -25,30 +25,49 @@ from . import binding as B
 
 
 def linear_decay_lr(lr0: float, t: int, total: int) -> float:
-    """Section 5.1.2: linearly decayed rate, t = 0 .. total-1."""
-    return lr0 * (1.0 - t / float(total))
+    """Section 5.1.2: linearly decayed rate, t = 0 .. total-1 (the library's mrem_schedule_lr)."""
+    return B.mrem_schedule_lr(lr0, t, total)
 
 
 def teacher_forcing_lambda(t: int, tf_steps: int) -> float:
-    """Section 4.2.1: lambda_t = max(1 - t/T0, 0); 0 when teacher forcing is off."""
-    return max(1.0 - t / float(tf_steps), 0.0) if tf_steps > 0 else 0.0
+    """Section 4.2.1: lambda_t = max(1 - t/T0, 0); 0 when teacher forcing is off (the library's mrem_schedule_lambda)."""
+    return B.mrem_schedule_lambda(t, tf_steps)
 
 
 class _Queue:
+    """Device memory for one mrem_queue and tensor views of the addresses it hands out; the ring
+    bookkeeping (write slot, publishing, entry of a given age) is the library's."""
+
     def __init__(self, depth: int, batch: int, seq: int, hidden: int, dtype, with_lengths: bool):
-        self.depth = depth                      # readable entries
-        self.fp = torch.empty((depth + 1, batch, seq, hidden), dtype=dtype, device="cuda")
-        self.q = torch.empty_like(self.fp)
-        self.lengths = torch.empty((depth + 1, batch), dtype=torch.int32, device="cuda") if with_lengths else None
-        self.pushed = 0                         # entries published so far
+        self.shape, self.dtype, self.batch = (batch, seq, hidden), dtype, batch
+        self.half_bytes = batch * seq * hidden * torch.empty(0, dtype=dtype).element_size()
+        self.len_bytes = batch * 4 if with_lengths else 0
+        self.mem = torch.empty(B.mrem_queue_bytes(depth, self.half_bytes, self.len_bytes), dtype=torch.uint8, device="cuda")
+        self.handle = B.mrem_queue_create(depth, self.half_bytes, self.len_bytes, self.mem)
 
-    def write_slot(self) -> int:
-        return self.pushed % (self.depth + 1)
+    def _views(self, addrs):
+        base = self.mem.data_ptr()
+        fp, qd, ln = addrs
+        out = [self.mem[a - base:a - base + self.half_bytes].view(self.dtype).reshape(self.shape) for a in (fp, qd)]
+        out.append(self.mem[ln - base:ln - base + self.len_bytes].view(torch.int32) if ln else None)
+        return out
 
-    def slot_of_age(self, age: int) -> int:
-        if not 0 <= age < min(self.pushed, self.depth):
-            raise ValueError(f"queue holds {min(self.pushed, self.depth)} entries, age {age} asked")
-        return (self.pushed - 1 - age) % (self.depth + 1)
+    def push(self, fp, qd, lengths):
+        B.mrem_queue_push(self.handle, fp, qd, lengths if self.len_bytes else None)
+
+    def written(self):
+        return self._views(B.mrem_queue_write_slot(self.handle))
+
+    def publish(self):
+        B.mrem_queue_publish(self.handle)
+
+    def entry(self, age: int):
+        return self._views(B.mrem_queue_entry(self.handle, age))
+
+    def close(self):
+        if self.handle:
+            B.mrem_queue_destroy(self.handle)
+            self.handle = None
 
 
 class ModulePipeline:
@@ -61,25 +80,17 @@ class ModulePipeline:
         m0 = self.modules[0]
         self.hidden, self.dtype = m0.hidden, m0.tdtype
         self.outs = [m.new_outputs(batch, seq) for m in self.modules]
-        self.mixed = [torch.empty((batch, seq, self.hidden), dtype=self.dtype, device="cuda") for _ in self.modules]
         self.streams = [torch.cuda.Stream() for _ in self.modules]
 
     # -- one module, one step, on the current stream ---------------------------------------
     def _step(self, n: int, x_fp, x_q, lengths, lr: float, lam: float, queue: Optional[_Queue], loss_row):
         mod = self.modules[n]
-        x_in = x_q
-        if n > 0 and lam > 0.0:
-            B.mrem_mix_inputs(mod.ctx, x_fp, x_q, lam, self.mixed[n], x_fp.numel())
-            x_in = self.mixed[n]
         out_fp, out_q = self.outs[n]
-        mod.step(x_fp, x_in, lr, lengths, out_fp, out_q)
+        # Eq. 4 is part of the step: the library mixes the two inputs in the kernel that quantizes the first layer's input
+        mod.step(x_fp, x_q, lr, lengths, out_fp, out_q, lam=lam if n > 0 else 0.0)
         loss_row[n].copy_(mod.loss[0], non_blocking=True)
         if queue is not None:
-            w = queue.write_slot()
-            queue.fp[w].copy_(out_fp[-1], non_blocking=True)
-            queue.q[w].copy_(out_q[-1], non_blocking=True)
-            if queue.lengths is not None:
-                queue.lengths[w].copy_(lengths, non_blocking=True)
+            queue.push(out_fp[-1], out_q[-1], lengths)
 
     def run_parallel(self, data: Sequence[torch.Tensor], lengths: Sequence[Optional[torch.Tensor]], slots, t0: int, total_steps: int,
                      lr0: float, tf_steps: int, concurrent: bool = True) -> torch.Tensor:
@@ -98,9 +109,8 @@ class ModulePipeline:
                 sl = lengths[t]
                 for n in range(N):
                     self._step(n, x_fp, x_q, sl, lr, lam, queues[n], losses[t])
-                    w = queues[n].write_slot()
-                    queues[n].pushed += 1
-                    x_fp, x_q = queues[n].fp[w], queues[n].q[w]
+                    x_fp, x_q, _ = queues[n].written()
+                    queues[n].publish()
                 continue
             # every module reads the queues as they were after step t-1
             start = torch.cuda.Event()
@@ -111,10 +121,7 @@ class ModulePipeline:
                     x_fp = x_q = data[t]
                     sl = lengths[t]
                 else:
-                    src = queues[n - 1]
-                    k = src.slot_of_age(int(slots[t][n]))
-                    x_fp, x_q = src.fp[k], src.q[k]
-                    sl = src.lengths[k] if src.lengths is not None else None
+                    x_fp, x_q, sl = queues[n - 1].entry(int(slots[t][n]))
                 stream = self.streams[n] if concurrent else main
                 with torch.cuda.stream(stream):
                     stream.wait_event(start)
@@ -125,8 +132,10 @@ class ModulePipeline:
             for ev in done:            # the barrier that ends the step
                 main.wait_event(ev)
             for qn in queues:          # publish: first in, first out
-                qn.pushed += 1
+                qn.publish()
         torch.cuda.synchronize()
+        for qn in queues:
+            qn.close()
         return losses.cpu()
 
     def run_sequential(self, data: Sequence[torch.Tensor], lengths: Sequence[Optional[torch.Tensor]], steps_per_module: int, lr0: float):

@@ -42,7 +42,7 @@ def elem_err(a, ref) -> float:
     return float((np.abs(a - ref) / (np.abs(ref) + top)).max())
 
 
-def conditioning(case: "Case", what: str = "forward"):
+def conditioning(case: "Case", what: str = "forward", xq=None):
     """How far accumulation-level noise is amplified on this case, measured by the oracle alone: the same
     pass with the products formed in fp32 instead of fp64 (Config.accumulate), compared with the reference
     pass.  A code that flips at a rounding tie moves an element by a whole quantization step, and such flips
@@ -53,13 +53,14 @@ def conditioning(case: "Case", what: str = "forward"):
     import dataclasses
     wl = case.wl
     xo = case.x.reshape(-1, wl.hidden).astype(np.float64)
+    xq = xo if xq is None else np.asarray(xq, dtype=np.float64).reshape(-1, wl.hidden)   # the quantized module's input
     cfg32 = dataclasses.replace(case.cfg, accumulate="f32")
     if what == "forward":
-        ref, _ = O.module_forward(xo, case.student, case.cfg, wl.batch, wl.seq, case.seqlens, quant=True)
-        alt, _ = O.module_forward(xo, case.student, cfg32, wl.batch, wl.seq, case.seqlens, quant=True)
+        ref, _ = O.module_forward(xq, case.student, case.cfg, wl.batch, wl.seq, case.seqlens, quant=True)
+        alt, _ = O.module_forward(xq, case.student, cfg32, wl.batch, wl.seq, case.seqlens, quant=True)
         return [rel_err(a, r) for a, r in zip(alt, ref)]
-    ref = O.module_grads(xo, xo, case.teacher, case.student, case.cfg, wl.batch, wl.seq, case.seqlens)
-    alt = O.module_grads(xo, xo, case.teacher, case.student, cfg32, wl.batch, wl.seq, case.seqlens)
+    ref = O.module_grads(xo, xq, case.teacher, case.student, case.cfg, wl.batch, wl.seq, case.seqlens)
+    alt = O.module_grads(xo, xq, case.teacher, case.student, cfg32, wl.batch, wl.seq, case.seqlens)
     fwd = [rel_err(a, r) for a, r in zip(alt.f_q, ref.f_q)]
     fields = [k for k in O.TRAINABLE_FIELDS if k != "s_a"]
     grads = [{k: (rel_err(ga[k], gr[k]) if np.linalg.norm(gr[k]) > 0 else 0.0) for k in fields} for ga, gr in zip(alt.grads, ref.grads)]

@@ -73,8 +73,8 @@ def test_entry_points_reject_bad_arguments_on_the_host(B):
     ctx = B.mrem_create(n_layers=1, hidden=64, n_heads=2, ffn=256, max_batch=4, max_seq=32)
     fake = ctypes.c_void_p(0x1000)      # aligned, never dereferenced on the host
     lib.mrem_module_step.restype = ctypes.c_int
-    args = lambda ws, nbytes, batch=4, seq=32, params=fake: B._lib.mrem_module_step(
-        ctx, params, fake, fake, 1, 1e-3, fake, fake, fake, fake, None, batch, seq, fake, fake, fake, None, ws, nbytes, None)
+    args = lambda ws, nbytes, batch=4, seq=32, params=fake, lam=0.0: B._lib.mrem_module_step(
+        ctx, params, fake, fake, 1, 1e-3, lam, fake, fake, fake, fake, None, batch, seq, fake, fake, fake, None, ws, nbytes, None)
     need = B.mrem_workspace_bytes(ctx, 4, 32)
     assert args(fake, need - 1) == B.MREM_EWORKSPACE and "workspace" in B.mrem_last_error(ctx)
     assert args(None, need) == B.MREM_EINVAL
@@ -82,9 +82,49 @@ def test_entry_points_reject_bad_arguments_on_the_host(B):
     assert args(fake, need, seq=33) == B.MREM_ESHAPE
     assert args(fake, need, params=None) == B.MREM_EINVAL
     assert args(fake, need, params=ctypes.c_void_p(0x1004)) == B.MREM_EINVAL
-    assert B._lib.mrem_quantize(None, 4, 8, 4, 1, fake, fake, None) == B.MREM_EINVAL
-    assert B._lib.mrem_quantize(fake, 4, 8, 1, 1, fake, fake, None) == B.MREM_EINVAL
+    assert args(fake, need, lam=1.5) == B.MREM_EINVAL and "lambda" in B.mrem_last_error(ctx)
+    assert B._lib.mrem_quantize(None, 4, 8, 4, 1, 1, fake, fake, None) == B.MREM_EINVAL
+    assert B._lib.mrem_quantize(fake, 4, 8, 1, 1, 1, fake, fake, None) == B.MREM_EINVAL
+    assert B._lib.mrem_quantize(fake, 4, 8, 4, 3, 1, fake, fake, None) == B.MREM_EINVAL
+    # no flag given: the check says so; a misaligned flag is refused
+    assert B._lib.mrem_check_nonfinite(ctx, None) == B.MREM_EINVAL
+    assert B._lib.mrem_set_nonfinite_flag(ctx, ctypes.c_void_p(0x1002)) == B.MREM_EINVAL
     B.mrem_destroy(ctx)
+
+
+def test_schedules_and_queue_bookkeeping_on_the_host(B):
+    """Section 5.1.2 / 4.2.1 schedules against their formulas, and the ring of Algorithm 1's input queue:
+    depth + 1 slots, first in first out, ages counted from the newest published entry (addresses only:
+    nothing is dereferenced, so this runs without a GPU)."""
+    import numpy as np
+    for t in range(0, 11):
+        assert B.mrem_schedule_lr(1e-4, t, 10) == 1e-4 * (1 - t / 10)
+        assert B.mrem_schedule_lambda(t, 4) == max(1 - t / 4, 0)
+    assert B.mrem_schedule_lambda(3, 0) == 0.0 and B.mrem_schedule_lr(1e-4, 0, 0) == 0.0
+    half, lens, depth = 1000, 12, 3
+    slot = 2 * 1024 + 256                                   # halves and lengths rounded up to 256 bytes
+    assert B.mrem_queue_bytes(depth, half, lens) == (depth + 1) * slot
+    base = 0x10000
+    q = ctypes.c_void_p()
+    assert B._lib.mrem_queue_create(depth, half, lens, ctypes.c_void_p(base), ctypes.byref(q)) == B.MREM_OK
+    assert B._lib.mrem_queue_create(0, half, lens, ctypes.c_void_p(base), ctypes.byref(ctypes.c_void_p())) == B.MREM_ESHAPE
+    q = q.value
+    assert B.mrem_queue_size(q) == 0
+    written = []
+    for i in range(6):
+        fp, qd, ln = B.mrem_queue_write_slot(q)
+        assert fp == base + (i % (depth + 1)) * slot and qd == fp + 1024 and ln == fp + 2048
+        written.append(fp)
+        B.mrem_queue_publish(q)
+        assert B.mrem_queue_size(q) == min(i + 1, depth)
+        for age in range(B.mrem_queue_size(q)):
+            assert B.mrem_queue_entry(q, age)[0] == written[i - age]          # newest first
+        with pytest.raises(B.MremError):
+            B.mrem_queue_entry(q, B.mrem_queue_size(q))
+        # the slot being written next is never one of the readable ones
+        nxt = B.mrem_queue_write_slot(q)[0]
+        assert all(B.mrem_queue_entry(q, age)[0] != nxt for age in range(B.mrem_queue_size(q)))
+    B.mrem_queue_destroy(q)
 
 
 def test_binding_refuses_to_import_without_the_library(B, tmp_path):

@@ -53,7 +53,7 @@ def test_quantize_codes_bit_exact(B, N, K, bits):
     wd = torch.from_numpy(w).cuda()
     scale = torch.zeros(N, dtype=torch.float32, device="cuda")
     codes = torch.zeros((N, K), dtype=torch.int8, device="cuda")
-    B.mrem_quantize(wd, N, K, bits, 1, scale, codes)
+    B.mrem_quantize(wd, N, K, bits, 1, 1, scale, codes)
     s_ref = O.weight_step_init(w, bits)
     s_ref[s_ref == 0] = np.finfo(np.float32).tiny
     assert np.array_equal(scale.cpu().numpy(), s_ref.astype(np.float32))
@@ -62,13 +62,20 @@ def test_quantize_codes_bit_exact(B, N, K, bits):
     # given steps (not the initial ones): some values clip
     s2 = (s_ref * rng.uniform(0.3, 1.7, size=N)).astype(np.float32)
     scale.copy_(torch.from_numpy(s2))
-    B.mrem_quantize(wd, N, K, bits, 0, scale, codes)
+    B.mrem_quantize(wd, N, K, bits, 1, 0, scale, codes)
     c_ref, _, _, _ = O.quantize_weight(w, s2.astype(np.float64), bits)
     got = codes.cpu().numpy().astype(np.int64)
     assert np.array_equal(got, c_ref)
     qp = 2 ** (bits - 1) - 1
     assert got.min() >= -qp and got.max() <= qp
     assert np.array_equal(scale.cpu().numpy(), s2)        # steps untouched without init
+    # one step for the whole tensor (Section 3.1's default granularity): scale[0] only
+    one = torch.zeros(1, dtype=torch.float32, device="cuda")
+    B.mrem_quantize(wd, N, K, bits, 0, 1, one, codes)
+    s_ref = O.weight_step_init(w, bits, per_channel=False)
+    assert one.item() == np.float32(s_ref[0]) or (s_ref[0] == 0 and one.item() == np.finfo(np.float32).tiny)
+    c_ref, _, _, _ = O.quantize_weight(w, np.full(N, max(s_ref[0], np.finfo(np.float32).tiny)), bits)
+    assert np.array_equal(codes.cpu().numpy().astype(np.int64), c_ref)
 
 
 def test_quantize_rejects_bad_arguments(B):
@@ -77,11 +84,14 @@ def test_quantize_rejects_bad_arguments(B):
     s = torch.zeros(4, dtype=torch.float32, device="cuda")
     c = torch.zeros((4, 8), dtype=torch.int8, device="cuda")
     with pytest.raises(B.MremError) as e:
-        B.mrem_quantize(w, 4, 8, 9, 1, s, c)
+        B.mrem_quantize(w, 4, 8, 9, 1, 1, s, c)
     assert e.value.status == B.MREM_EINVAL
     with pytest.raises(B.MremError) as e:
-        B.mrem_quantize(w, 0, 8, 4, 1, s, c)
+        B.mrem_quantize(w, 0, 8, 4, 1, 1, s, c)
     assert e.value.status == B.MREM_ESHAPE
+    with pytest.raises(B.MremError) as e:
+        B.mrem_quantize(w, 4, 8, 4, 2, 1, s, c)
+    assert e.value.status == B.MREM_EINVAL
 
 
 # --------------------------------------------------------------------------------
@@ -126,7 +136,7 @@ CASES_BF16 = {
 MID_F32 = W("mid_f32", 2, 128, 2, 512, 80, 3, act_dtype="f32", seqlen_lo=40, seqlen_hi=80)
 
 
-def _compare_step(B, wl, lr=1e-3, case=None, tol=None, tol_for=None, n_steps=1, **cfg_kw):
+def _compare_step(B, wl, lr=1e-3, case=None, tol=None, tol_for=None, n_steps=1, lam=0.0, **cfg_kw):
     """n_steps steps of Algorithm 2 on one batch (rate lr, linearly decayed when n_steps > 1), every quantity of
     every step against the oracle: layer outputs of both modules, losses, every gradient, and every updated
     parameter with both of its AdamW moments.  Tensors are judged twice: norm-wise (|d|_2 <= tol |ref|_2) and
@@ -142,6 +152,8 @@ def _compare_step(B, wl, lr=1e-3, case=None, tol=None, tol_for=None, n_steps=1, 
     xq = Hh.device_student_input(case, x)
     xo = case.x.reshape(-1, wl.hidden).astype(np.float64)
     xqo = xo if case.x_q is None else np.asarray(case.x_q, dtype=np.float64).reshape(-1, wl.hidden)
+    if lam > 0.0:   # Eq. 4: the device mixes inside the step; the oracle mixes, stores in the activation type, then steps
+        xqo = O.round_store(O.mix_inputs(xo, xqo, lam), "bf16" if wl.act_dtype == "bf16" else "f32")
     m, v = Hh.fresh_moments(case.student)
     grads = torch.zeros_like(mod.params)
     report = []
@@ -195,7 +207,7 @@ def _compare_step(B, wl, lr=1e-3, case=None, tol=None, tol_for=None, n_steps=1, 
         lr_t = O.linear_decay_lr(lr, t - 1, n_steps) if n_steps > 1 else lr
         lr_sum[0] += lr_t
         res = O.module_step(xo, xqo, case.teacher, case.student, m, v, t, lr_t, case.cfg, wl.batch, wl.seq, case.seqlens)
-        ofp, oq = mod.step(x, xq, lr_t, sl, grads_out=grads)
+        ofp, oq = mod.step(x, xq, lr_t, sl, grads_out=grads, lam=lam)
         torch.cuda.synchronize()
         loss = mod.loss.cpu().numpy()
         for l in range(wl.n_layers):
@@ -456,13 +468,14 @@ def _full_case(name):
     return copy.deepcopy(_FULL_CASES[name])
 
 
-def _w8_tolerances(case, tol=2e-2):
-    """Tolerances for a case whose gradients are ill-conditioned (8-bit weights with bf16 storage): the stated
+def _w8_tolerances(case, tol=2e-2, xq=None):
+    """Tolerances for a case whose gradients are ill-conditioned (8-bit weights with bf16 storage; chained
+    quantized layers with outlier channels whose input differs from the full-precision module's): the stated
     tolerance plus the distance that the oracle measures between its fp32-product and its fp64-product pass
     for that very quantity -- norm-wise for the norm-wise criterion, element-wise (with a factor 1.5 for the
     tail of a maximum over millions of elements) for the element-wise one."""
     wl = case.wl
-    fwd, gnorm, gelem = Hh.conditioning(case, "grads")
+    fwd, gnorm, gelem = Hh.conditioning(case, "grads", xq)
     print("oracle-measured conditioning: outputs", fwd, "gradients, worst per layer (norm-wise, element-wise)",
           [(max(a.values()), max(b.values())) for a, b in zip(gnorm, gelem)])
     tol_for = {f"f_q[{l}]": tol + fwd[l] for l in range(wl.n_layers)}
@@ -763,3 +776,56 @@ def test_w8a8_bf16_gradients_within_the_oracle_measured_conditioning(B):
     case = Hh.make_case(wl)
     tol_for = _w8_tolerances(case)
     _compare_step(B, wl, lr=1e-4, case=case, tol_for=tol_for)
+
+
+# --------------------------------------------------------------------------------
+# the rest of Algorithm 2's boundary: input mixing inside the step, non-finite detection
+# --------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["two_layer_f32", "aligned_bf16"])
+def test_step_with_input_mixing_matches_oracle(B, name):
+    """Eq. 4 as an argument of the step: the quantized module reads lambda x_fp + (1 - lambda) x_q, mixed by the
+    kernel that quantizes its first layer's input; whole step against the oracle (which mixes, then steps)."""
+    wl = {**CASES_BF16, **CASES_F32}[name]
+    case = Hh.make_case(wl)
+    other = synth.make_hidden_states(wl.batch, wl.seq, wl.hidden, 999, wl.act_dtype, wl.outlier_frac, wl.outlier_scale)
+    case.x_q = (0.9 * case.x + 0.1 * other).astype(np.float32)
+    case.x_q = synth.round_to_dtype(case.x_q, wl.act_dtype)
+    lam = float(O.teacher_forcing_lambda(3, 10))
+    if name == "two_layer_f32":
+        _compare_step(B, wl, case=case, lam=lam, tol=1e-2)          # fp32 without the margin guarantee (as mid_f32)
+    else:
+        xo = case.x.reshape(-1, wl.hidden).astype(np.float64)
+        mixed = O.round_store(O.mix_inputs(xo, case.x_q.reshape(-1, wl.hidden).astype(np.float64), lam), "bf16")
+        _compare_step(B, wl, case=case, lam=lam, tol_for=_w8_tolerances(case, xq=mixed))
+
+
+def test_non_finite_loss_sets_the_flag(B):
+    """A NaN or infinity anywhere in a layer output reaches Eq. 3; the step sets the caller's device flag and
+    mrem_check_nonfinite reports MREM_ENONFINITE.  The condition is forced from the host (an infinite input value);
+    every kernel runs to completion."""
+    torch = _torch()
+    wl = CASES_BF16["tiny_bf16"]
+    case = Hh.make_case(wl)
+    mod = Hh.device_module(case)
+    x, sl = Hh.device_inputs(case)
+    with pytest.raises(B.MremError) as e:
+        B.mrem_check_nonfinite(mod.ctx)                   # no flag given yet
+    assert e.value.status == B.MREM_EINVAL
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.mrem_set_nonfinite_flag(mod.ctx, flag)
+    mod.step(x, x, 1e-4, sl)
+    B.mrem_check_nonfinite(mod.ctx)                       # finite: passes
+    assert flag.item() == 0
+    bad = x.clone()
+    bad[1, 3, 5] = float("inf")
+    mod.step(bad, bad, 1e-4, sl)
+    with pytest.raises(B.MremError) as e:
+        B.mrem_check_nonfinite(mod.ctx)
+    assert e.value.status == B.MREM_ENONFINITE and flag.item() == 1
+    flag.zero_()
+    B.mrem_set_nonfinite_flag(mod.ctx, None)              # switched off: nothing is written any more
+    mod.step(bad, bad, 1e-4, sl)
+    torch.cuda.synchronize()
+    assert flag.item() == 0
+    mod.close()
