@@ -125,17 +125,18 @@ def run_parallel(modules: Sequence[ModuleState], data: Sequence[np.ndarray], seq
 
 
 def run_sequential(modules: Sequence[ModuleState], data: Sequence[np.ndarray], seqlens: Sequence[Optional[np.ndarray]],
-                   steps_per_module: int, lr0: float, batch: int, seq: int) -> Trace:
+                   steps_per_module: int, lr0: float, batch: int, seq: int, order=None) -> Trace:
     """Section 4.1: module n is trained for steps_per_module steps on the outputs of the
     finished modules 1..n-1 (full-precision chain for the teacher input, quantized chain
-    for the student input), batches visited in order, cyclically."""
+    for the student input).  order[n][t]: which batch module n sees at its step t (the caller's
+    draw, e.g. sampled with replacement); default: in order, cyclically."""
     trace = Trace()
     fp_in = [d for d in data]
     q_in = [d for d in data]
     for n, ms in enumerate(modules):
         losses = []
         for t in range(steps_per_module):
-            k = t % len(data)
+            k = t % len(data) if order is None else int(order[n][t])
             lr = O.linear_decay_lr(lr0, t, steps_per_module)
             loss, _ = _one_step(ms, fp_in[k], q_in[k], 0.0, lr, batch, seq, seqlens[k])
             losses.append(loss)
