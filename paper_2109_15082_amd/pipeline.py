@@ -138,8 +138,10 @@ class ModulePipeline:
             qn.close()
         return losses.cpu()
 
-    def run_sequential(self, data: Sequence[torch.Tensor], lengths: Sequence[Optional[torch.Tensor]], steps_per_module: int, lr0: float):
-        """Section 4.1: module n is trained on the outputs of the finished modules 1..n-1.  Returns
+    def run_sequential(self, data: Sequence[torch.Tensor], lengths: Sequence[Optional[torch.Tensor]], steps_per_module: int, lr0: float,
+                       order=None):
+        """Section 4.1: module n is trained on the outputs of the finished modules 1..n-1; order[n][t] is the
+        batch module n sees at its step t (the caller's draw; default: in order, cyclically).  Returns
         (losses [N, steps_per_module] on the host, final full-precision chain outputs, final quantized chain outputs)."""
         N = len(self.modules)
         losses = torch.zeros((N, steps_per_module), dtype=torch.float32, device="cuda")
@@ -147,7 +149,7 @@ class ModulePipeline:
         q_in = list(data)
         for n, mod in enumerate(self.modules):
             for t in range(steps_per_module):
-                k = t % len(data)
+                k = t % len(data) if order is None else int(order[n][t])
                 self._step(n, fp_in[k], q_in[k], lengths[k], linear_decay_lr(lr0, t, steps_per_module), 0.0, None, losses[:, t])
             nxt_fp, nxt_q = [], []
             for k in range(len(data)):

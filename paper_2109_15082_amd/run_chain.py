@@ -80,7 +80,9 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     if args.schedule == "sequential":
-        losses, _, _ = pipe.run_sequential(data, lengths, args.steps, args.lr)
+        # every module's batches are sampled with replacement from the calibration set (seeded per module)
+        order = [np.random.default_rng(4321 + n).integers(0, n_batches, size=args.steps).tolist() for n in range(N)]
+        losses, _, _ = pipe.run_sequential(data, lengths, args.steps, args.lr, order)
         first, last = losses[:, 0].tolist(), losses[:, -1].tolist()
     else:
         rng = np.random.default_rng(99)
