@@ -21,10 +21,22 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 MFMA_INT8_PEAK_TOPS = 5000.0
-# HBM bytes per matrix-product launch (read + written), from two rocprofv3 --pmc runs (FETCH_SIZE, then
-# WRITE_SIZE), each scaled by what the counter reads for a 256 MiB device copy; summary with the commands in
-# profiles/module_step_bert_large_6l_hbm_traffic.md.  Only for the workload it was measured on.
-MEASURED_GEMM_TRAFFIC_BYTES = {"bert_large_6l": 81.1e6}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "module_step_bert_large_6l_hbm_traffic.md")
+
+
+def measured_gemm_traffic(workload):
+    """HBM bytes per matrix-product launch (read + written) as the committed rocprofv3 --pmc summary states them
+    (FETCH_SIZE and WRITE_SIZE runs, each scaled by what the counter reads for a 256 MiB device copy): the line
+    'traffic_bytes_per_launch: <workload> <bytes>' of profiles/module_step_bert_large_6l_hbm_traffic.md.  Counters
+    cannot be read from inside this process, so the figure comes from that file or is null."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            parts = line.strip().strip("`").split()
+            if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch:" and parts[1] == workload:
+                return float(parts[2])
+    except OSError:
+        pass
+    return None
 
 
 def step_flops(wl):
@@ -130,6 +142,13 @@ def main():
     torch.cuda.synchronize()
     dt_events = time.perf_counter() - t1
     (gemm_ms, gemm_flops, gemm_launches), (i8_ms, i8_ops, i8_launches) = B.mrem_profile_gemm_end(mod.ctx)
+    # the bandwidth-bound kernels of the same pass: algorithmic bytes over the kernel's own duration, against HBM's 8 TB/s
+    hbm_kernels = {}
+    for name, (ms, nbytes, launches) in sorted(B.mrem_profile_kernels(mod.ctx).items()):
+        gbs = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        hbm_kernels[name] = {"launches_per_step": launches / args.steps, "algorithmic_bytes_per_launch": nbytes / max(launches, 1),
+                             "us_per_launch": ms * 1e3 / max(launches, 1), "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": gbs / HBM_PEAK_GBS}
     losses = mod.loss.cpu().numpy()
     assert np.isfinite(losses).all(), losses
 
@@ -147,10 +166,11 @@ def main():
         "config": {"workload": wl.name, "n_layers": wl.n_layers, "hidden": wl.hidden, "n_heads": wl.n_heads, "ffn": wl.ffn,
                    "seq_len": wl.seq, "batch": wl.batch, "w_bits": wl.w_bits, "a_bits": wl.a_bits,
                    "tokens_per_step": wl.tokens, "step_tflop": flops_total / 1e12, "loss_last_step": float(losses[0])},
-        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_k on bf16 operands (teacher forward, input and weight gradients)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_dl_k on bf16 operands (teacher forward, input and weight gradients)",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(wl.name),
-                     "traffic_unit": "bytes/launch",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_gemm_traffic(wl.name),
+                     "traffic_unit": "bytes/launch", "traffic_source": "profiles/module_step_bert_large_6l_hbm_traffic.md (rocprofv3 --pmc)",
+                     "hbm_kernels": hbm_kernels,
                      "launches_per_step": gemm_launches / args.steps,
                      "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
                      "gemm_ms_per_step": gemm_ms / args.steps,

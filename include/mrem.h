@@ -310,6 +310,15 @@ mrem_status mrem_queue_entry(const mrem_queue* q, int32_t age, void** fp, void**
  */
 mrem_status mrem_profile_gemm_begin(mrem_ctx* ctx);
 mrem_status mrem_profile_gemm_end(mrem_ctx* ctx, double ms[2] /*host*/, double flops[2] /*host*/, int64_t launches[2] /*host*/);
+/*
+ * The same timed interval also records the bandwidth-bound kernels (LayerNorm, quantizer, GELU, weight-code and
+ * update kernels), each launch with its algorithmic bytes: what it must read and write at least.  After
+ * mrem_profile_gemm_end: mrem_profile_kernel_count entries, each a kernel name (copied into name[name_bytes]),
+ * the summed kernel time in milliseconds, the summed algorithmic bytes and the number of launches.
+ */
+int32_t mrem_profile_kernel_count(const mrem_ctx* ctx);
+mrem_status mrem_profile_kernel_get(const mrem_ctx* ctx, int32_t i, char* name /*host*/, int32_t name_bytes, double* ms /*host*/,
+                                    double* bytes /*host*/, int64_t* launches /*host*/);
 
 #ifdef __cplusplus
 }

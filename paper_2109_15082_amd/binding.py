@@ -30,7 +30,7 @@ EXPORTS = ("mrem_create", "mrem_destroy", "mrem_last_error", "mrem_param_count",
            "mrem_param_offset", "mrem_param_size", "mrem_workspace_bytes", "mrem_workspace_offset", "mrem_teacher_cache_bytes",
            "mrem_quantize", "mrem_module_init_steps", "mrem_teacher_prepare", "mrem_module_calibrate",
            "mrem_module_forward", "mrem_module_forward_static", "mrem_static_scratch_bytes", "mrem_module_step", "mrem_mix_inputs", "mrem_profile_gemm_begin",
-           "mrem_profile_gemm_end", "mrem_set_nonfinite_flag", "mrem_check_nonfinite", "mrem_schedule_lr", "mrem_schedule_lambda",
+           "mrem_profile_gemm_end", "mrem_profile_kernel_count", "mrem_profile_kernel_get", "mrem_set_nonfinite_flag", "mrem_check_nonfinite", "mrem_schedule_lr", "mrem_schedule_lambda",
            "mrem_queue_bytes", "mrem_queue_create", "mrem_queue_destroy", "mrem_queue_size", "mrem_queue_write_slot", "mrem_queue_push",
            "mrem_queue_publish", "mrem_queue_entry")
 
@@ -89,6 +89,10 @@ _lib.mrem_profile_gemm_begin.argtypes = [_vp]
 _lib.mrem_profile_gemm_begin.restype = C.c_int
 _lib.mrem_profile_gemm_end.argtypes = [_vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i64)]
 _lib.mrem_profile_gemm_end.restype = C.c_int
+_lib.mrem_profile_kernel_count.argtypes = [_vp]
+_lib.mrem_profile_kernel_count.restype = _i32
+_lib.mrem_profile_kernel_get.argtypes = [_vp, _i32, C.c_char_p, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i64)]
+_lib.mrem_profile_kernel_get.restype = C.c_int
 _lib.mrem_set_nonfinite_flag.argtypes = [_vp, _vp]
 _lib.mrem_set_nonfinite_flag.restype = C.c_int
 _lib.mrem_check_nonfinite.argtypes = [_vp, _vp]
@@ -250,6 +254,17 @@ def mrem_profile_gemm_end(ctx):
     ms, fl, n = (C.c_double * 2)(), (C.c_double * 2)(), (_i64 * 2)()
     _check(_lib.mrem_profile_gemm_end(ctx, ms, fl, n), ctx)
     return (ms[0], fl[0], n[0]), (ms[1], fl[1], n[1])
+
+
+def mrem_profile_kernels(ctx):
+    """{kernel name: (ms, algorithmic bytes, launches)} of the bandwidth-bound kernels of the last timed interval."""
+    out = {}
+    for i in range(_lib.mrem_profile_kernel_count(ctx)):
+        name = C.create_string_buffer(64)
+        ms, nb, n = C.c_double(), C.c_double(), _i64()
+        _check(_lib.mrem_profile_kernel_get(ctx, i, name, 64, C.byref(ms), C.byref(nb), C.byref(n)), ctx)
+        out[name.value.decode()] = (ms.value, nb.value, n.value)
+    return out
 
 
 def mrem_set_nonfinite_flag(ctx, flag) -> None:

@@ -225,6 +225,22 @@ struct Run {
   int8_t* at8(size_t off) const { return i8() ? reinterpret_cast<int8_t*>(ws + off) : nullptr; }
 };
 
+// One launch of a bandwidth-bound kernel; while a context's timing is on, the launch carries an event pair and
+// is recorded with its algorithmic bytes (what the kernel must read and write at least) under `label`.
+template <class F>
+void timed(const Run& r, const char* label, double bytes, F&& launch) {
+  if (!r.prof || !r.prof->on) { launch(); return; }
+  GemmRecord rec;
+  rec.flops = bytes; rec.cls = 2; rec.label = label;
+  (void)hipEventCreate(&rec.e0);
+  (void)hipEventCreate(&rec.e1);
+  tl_launch_events.e0 = rec.e0;
+  tl_launch_events.e1 = rec.e1;
+  launch();
+  tl_launch_events = LaunchEvents();
+  r.prof->recs.push_back(rec);
+}
+
 // Second-stage reductions of a backward pass, collected while the first-stage kernels are enqueued.
 struct Reductions {
   std::vector<ReduceJob> jobs;
@@ -298,7 +314,11 @@ void prepare_weights(const Run& r, const float* params) {
       jobs.push_back(j);
     }
   }
-  weight_prepare(c->dt, jobs.data(), (int)jobs.size(), c->cfg.w_bits, r.st);
+  double nw = 0;
+  for (const WeightJob& j : jobs) nw += (double)j.N * j.K;
+  // fp32 master in; codes (int8, or the storage type) and the dequantized copy out
+  timed(r, "weight_codes_k", nw * (4 + (r.i8() ? 1 : dt_size(c->dt)) + dt_size(c->dt)),
+        [&] { weight_prepare(c->dt, jobs.data(), (int)jobs.size(), c->cfg.w_bits, r.st); });
 }
 
 // Layers [l0, l1) of the quantized module (l1 < 0: to the last layer).
@@ -321,10 +341,12 @@ void student_forward(const Run& r, const float* params, const void* x_q, void* p
     if (l == 0 && mix_fp)
       mix_quantize(c->dt, mix_fp, mix_in, lambda, 1.f - lambda, const_cast<void*>(x), r.at(w.xcodes), (int64_t)T * H, make_q(c, params, l, 0), r.st,
                    r.at8(w.xcodes8));
-    else if (l == 0) act_quantize(c->dt, x, r.at(w.xcodes), (int64_t)T * H, make_q(c, params, l, 0), r.st, r.at8(w.xcodes8));
+    else if (l == 0)
+      timed(r, "act_quantize_k", (double)T * H * (2 * es + (r.i8() ? 1 : 0)),
+            [&] { act_quantize(c->dt, x, r.at(w.xcodes), (int64_t)T * H, make_q(c, params, l, 0), r.st, r.at8(w.xcodes8)); });
     student_linear(r, params, l, 0, r.at(w.xcodes), r.at8(w.xcodes8), r.at(w.qkv));
     const AttnQ aq = make_attn_q(c, params, l, true);
-    qkv_quantize(c->dt, r.at(w.qkv), r.at(w.qkvcodes), T, H, aq.q, aq.k, aq.v, r.st);
+    timed(r, "qkv_quantize_k", (double)T * 3 * H * 2 * es, [&] { qkv_quantize(c->dt, r.at(w.qkv), r.at(w.qkvcodes), T, H, aq.q, aq.k, aq.v, r.st); });
     if (attn_mfma_ok(c->dt, r.S, c->d)) {
       attn_fwd_mfma(r.at(w.qkvcodes), r.at(w.ctx), r.at(w.ctxcodes), aq, r.seqlens, r.B, r.S, c->nh, nullptr, r.at<float>(w.stat_m),
                     r.at<float>(w.stat_l), r.st, r.at8(w.ctxcodes8));
@@ -333,22 +355,30 @@ void student_forward(const Run& r, const float* params, const void* x_q, void* p
       if (r.i8()) codes_to_i8(c->dt, r.at(w.ctxcodes), r.at8(w.ctxcodes8), (int64_t)T * H, 0.f, r.st);
     }
     student_linear(r, params, l, 1, r.at(w.ctxcodes), r.at8(w.ctxcodes8), r.at(w.o));
-    ln_fwd(c->dt, x, r.at(w.o), base + c->foff[MREM_F_LN1_G], base + c->foff[MREM_F_LN1_B], r.at(w.x1), r.at(w.x1codes),
-           make_q(c, params, l, 6), r.at<float>(w.mu1), r.at<float>(w.rstd1), T, H, c->cfg.ln_eps, r.st, r.at8(w.x1codes8));
+    const double ln_q_bytes = (double)T * H * (4 * es + (r.i8() ? 1 : 0));  // x, r in; y and its codes (and int8 codes) out
+    timed(r, "ln_fwd_k", ln_q_bytes, [&] {
+      ln_fwd(c->dt, x, r.at(w.o), base + c->foff[MREM_F_LN1_G], base + c->foff[MREM_F_LN1_B], r.at(w.x1), r.at(w.x1codes),
+             make_q(c, params, l, 6), r.at<float>(w.mu1), r.at<float>(w.rstd1), T, H, c->cfg.ln_eps, r.st, r.at8(w.x1codes8));
+    });
     student_linear(r, params, l, 2, r.at(w.x1codes), r.at8(w.x1codes8), r.at(w.u));
     {
       const QArg qg = make_q(c, params, l, 7);
-      gelu_quantize(c->dt, r.at(w.u), r.at(w.gcodes), (int64_t)T * F, qg, r.st, r.at8(w.gcodes8), 0.5f * (qg.qp + 1.f));
+      timed(r, "gelu_quantize_k", (double)T * F * (2 * es + (r.i8() ? 1 : 0)),
+            [&] { gelu_quantize(c->dt, r.at(w.u), r.at(w.gcodes), (int64_t)T * F, qg, r.st, r.at8(w.gcodes8), 0.5f * (qg.qp + 1.f)); });
     }
     student_linear(r, params, l, 3, r.at(w.gcodes), r.at8(w.gcodes8), r.at(w.y));
     if (l + 1 < c->L) {
       // the layer output and, in the same pass, its codes under the next layer's input quantizer
       const LayerWs& wn = r.p.lw[l + 1];
-      ln_fwd(c->dt, r.at(w.x1), r.at(w.y), base + c->foff[MREM_F_LN2_G], base + c->foff[MREM_F_LN2_B], f, r.at(wn.xcodes),
-             make_q(c, params, l + 1, 0), r.at<float>(w.mu2), r.at<float>(w.rstd2), T, H, c->cfg.ln_eps, r.st, r.at8(wn.xcodes8));
+      timed(r, "ln_fwd_k", ln_q_bytes, [&] {
+        ln_fwd(c->dt, r.at(w.x1), r.at(w.y), base + c->foff[MREM_F_LN2_G], base + c->foff[MREM_F_LN2_B], f, r.at(wn.xcodes),
+               make_q(c, params, l + 1, 0), r.at<float>(w.mu2), r.at<float>(w.rstd2), T, H, c->cfg.ln_eps, r.st, r.at8(wn.xcodes8));
+      });
     } else {
-      ln_fwd(c->dt, r.at(w.x1), r.at(w.y), base + c->foff[MREM_F_LN2_G], base + c->foff[MREM_F_LN2_B], f, nullptr, QArg(),
-             r.at<float>(w.mu2), r.at<float>(w.rstd2), T, H, c->cfg.ln_eps, r.st);
+      timed(r, "ln_fwd_k", (double)T * H * 3 * es, [&] {
+        ln_fwd(c->dt, r.at(w.x1), r.at(w.y), base + c->foff[MREM_F_LN2_G], base + c->foff[MREM_F_LN2_B], f, nullptr, QArg(),
+               r.at<float>(w.mu2), r.at<float>(w.rstd2), T, H, c->cfg.ln_eps, r.st);
+      });
     }
   }
 }
@@ -399,8 +429,10 @@ void teacher_forward(const Run& r, const float* teacher, const void* cache, cons
     }
     e.bias = base + c->foff[MREM_F_B_O];
     gemm_nt(c->dt, r.at(r.p.t_ctx), H, W(1), H, r.at(r.p.t_o), H, T, H, H, e, r.st, r.prof);
-    ln_fwd(c->dt, x, r.at(r.p.t_o), base + c->foff[MREM_F_LN1_G], base + c->foff[MREM_F_LN1_B], r.at(r.p.t_x1), nullptr, QArg(),
-           r.at<float>(r.p.t_mu), r.at<float>(r.p.t_rstd), T, H, c->cfg.ln_eps, r.st);
+    timed(r, "ln_fwd_k", (double)T * H * 3 * es, [&] {
+      ln_fwd(c->dt, x, r.at(r.p.t_o), base + c->foff[MREM_F_LN1_G], base + c->foff[MREM_F_LN1_B], r.at(r.p.t_x1), nullptr, QArg(),
+             r.at<float>(r.p.t_mu), r.at<float>(r.p.t_rstd), T, H, c->cfg.ln_eps, r.st);
+    });
     if (calib_params) calib(l, 6, r.at(r.p.t_x1), c->dt, T, H, H, 0, 0);
     e.bias = base + c->foff[MREM_F_B_1];
     if (calib_params) {
@@ -415,8 +447,10 @@ void teacher_forward(const Run& r, const float* teacher, const void* cache, cons
     }
     e.bias = base + c->foff[MREM_F_B_2];
     gemm_nt(c->dt, r.at(r.p.t_g), F, W(3), F, r.at(r.p.t_y), H, T, H, F, e, r.st, r.prof);
-    ln_fwd(c->dt, r.at(r.p.t_x1), r.at(r.p.t_y), base + c->foff[MREM_F_LN2_G], base + c->foff[MREM_F_LN2_B], f, nullptr, QArg(),
-           r.at<float>(r.p.t_mu), r.at<float>(r.p.t_rstd), T, H, c->cfg.ln_eps, r.st);
+    timed(r, "ln_fwd_k", (double)T * H * 3 * es, [&] {
+      ln_fwd(c->dt, r.at(r.p.t_x1), r.at(r.p.t_y), base + c->foff[MREM_F_LN2_G], base + c->foff[MREM_F_LN2_B], f, nullptr, QArg(),
+             r.at<float>(r.p.t_mu), r.at<float>(r.p.t_rstd), T, H, c->cfg.ln_eps, r.st);
+    });
   }
 }
 
@@ -513,9 +547,14 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       const int wd = 3 * H + 2;
       float* parts = red.take((size_t)ln_bwd_parts(T) * wd);
       before_overwrite(3);
-      const int n = ln_bwd(c->dt, top ? nullptr : r.at(r.p.dr1), nullptr, top ? nullptr : r.at(r.p.dxh), fq, q_above, r.at(w.x1), r.at(w.y),
-                           r.at<float>(w.mu2), r.at<float>(w.rstd2), base + c->foff[MREM_F_LN2_G], r.at(r.p.dr2), parts, T, H, r.st,
-                           in_loss ? ffp : nullptr, scale);
+      int n = 0;
+      // in: layer output, the two LayerNorm inputs, the full-precision output (loss), above the top layer also the two
+      // gradients from above; out: the gradient of the LayerNorm input
+      timed(r, "ln_bwd_k", (double)T * H * es * ((top ? 4 : 6) + (in_loss ? 1 : 0)), [&] {
+        n = ln_bwd(c->dt, top ? nullptr : r.at(r.p.dr1), nullptr, top ? nullptr : r.at(r.p.dxh), fq, q_above, r.at(w.x1), r.at(w.y),
+                   r.at<float>(w.mu2), r.at<float>(w.rstd2), base + c->foff[MREM_F_LN2_G], r.at(r.p.dr2), parts, T, H, r.st,
+                   in_loss ? ffp : nullptr, scale);
+      });
       red.add(parts, n, wd, 0, H, g + c->foff[MREM_F_LN2_G]);
       red.add(parts, n, wd, H, H, g + c->foff[MREM_F_LN2_B]);
       red.add(parts, n, wd, 2 * H, H, g + c->foff[MREM_F_B_2]);
@@ -532,7 +571,9 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       float* parts = red.take(2048);
       float* cols = red.take((size_t)kColMaxParts * F);
       before_overwrite(2);
-      const ColGrid cg = gelu_quant_bwd(c->dt, r.at(r.p.dgh), r.at(w.u), r.at(r.p.du), T, F, make_q(c, params, l, 7), parts, cols, r.st);
+      ColGrid cg{};
+      timed(r, "gelu_quant_bwd_k", (double)T * F * 3 * es,
+            [&] { cg = gelu_quant_bwd(c->dt, r.at(r.p.dgh), r.at(w.u), r.at(r.p.du), T, F, make_q(c, params, l, 7), parts, cols, r.st); });
       red.add(parts, cg.gx * cg.gy, 1, 0, 1, g + c->foff[MREM_F_S_A] + 7);
       red.add(cols, cg.gy, F, 0, F, g + c->foff[MREM_F_B_1]);
     }
@@ -543,8 +584,11 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
     {
       float* parts = red.take((size_t)ln_bwd_parts(T) * (3 * H + 2));
       before_overwrite(1);
-      const int n = ln_bwd(c->dt, r.at(r.p.dr2), nullptr, r.at(r.p.dx1h), r.at(w.x1), make_q(c, params, l, 6), x, r.at(w.o),
-                           r.at<float>(w.mu1), r.at<float>(w.rstd1), base + c->foff[MREM_F_LN1_G], r.at(r.p.dr1), parts, T, H, r.st);
+      int n = 0;
+      timed(r, "ln_bwd_k", (double)T * H * es * 6, [&] {
+        n = ln_bwd(c->dt, r.at(r.p.dr2), nullptr, r.at(r.p.dx1h), r.at(w.x1), make_q(c, params, l, 6), x, r.at(w.o),
+                   r.at<float>(w.mu1), r.at<float>(w.rstd1), base + c->foff[MREM_F_LN1_G], r.at(r.p.dr1), parts, T, H, r.st);
+      });
       const int wd = 3 * H + 2;
       red.add(parts, n, wd, 0, H, g + c->foff[MREM_F_LN1_G]);
       red.add(parts, n, wd, H, H, g + c->foff[MREM_F_LN1_B]);
@@ -556,7 +600,9 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
     dgrad(r, l, 1, r.at(r.p.dr1), r.at(r.p.dch));
     {
       float* parts = red.take(2048);
-      const int n = quant_bwd(c->dt, r.at(r.p.dch), r.at(w.ctx), r.at(r.p.dc), numel, make_q(c, params, l, 5), parts, r.st);
+      int n = 0;
+      timed(r, "quant_bwd_k", (double)numel * 3 * es,
+            [&] { n = quant_bwd(c->dt, r.at(r.p.dch), r.at(w.ctx), r.at(r.p.dc), numel, make_q(c, params, l, 5), parts, r.st); });
       red.add(parts, n, 1, 0, 1, g + c->foff[MREM_F_S_A] + 5);
     }
     // attention
@@ -577,7 +623,9 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       float* parts = red.take(2048 * 3);
       float* cols = red.take((size_t)kColMaxParts * 3 * H);
       before_overwrite(0);
-      const ColGrid cg = qkv_quant_bwd(c->dt, r.at(r.p.dqkvh), r.at(w.qkv), r.at(r.p.dqkv), T, H, aq.q, aq.k, aq.v, parts, cols, r.st);
+      ColGrid cg{};
+      timed(r, "qkv_quant_bwd_k", (double)T * 3 * H * 3 * es,
+            [&] { cg = qkv_quant_bwd(c->dt, r.at(r.p.dqkvh), r.at(w.qkv), r.at(r.p.dqkv), T, H, aq.q, aq.k, aq.v, parts, cols, r.st); });
       const int n = cg.gx * cg.gy;
       red.add(parts, n, 3, 0, 1, g + c->foff[MREM_F_S_A] + 1);
       red.add(parts, n, 3, 1, 1, g + c->foff[MREM_F_S_A] + 2);
@@ -638,7 +686,13 @@ void update_matrices(const Run& r, const Update& u, float* grads, int l, hipStre
     j.db = zterm ? grads + o + c->foff[MREM_F_B_2] : nullptr;
     j.N = c->wN[i]; j.K = c->wK[i];
   }
-  adam_matrix(jobs, 4, c->cfg.w_bits, u.a, u.write_grads, c->cfg.per_channel ? 0 : 1, st);
+  double nw = 0;
+  for (int i = 0; i < 4; ++i) nw += (double)c->wN[i] * c->wK[i];
+  Run rs = r;
+  rs.st = st;
+  // parameter, gradient and both moments in; parameter and both moments out (the masked gradient too when it is exported)
+  timed(rs, "adam_matrix_k", nw * (28 + (u.write_grads ? 4 : 0)),
+        [&] { adam_matrix(jobs, 4, c->cfg.w_bits, u.a, u.write_grads, c->cfg.per_channel ? 0 : 1, st); });
 }
 // AdamW (no decay) on everything that is not a matrix: biases, LayerNorm parameters, activation steps
 void update_vectors(const Run& r, const Update& u, float* grads) {
@@ -926,6 +980,17 @@ extern "C" mrem_status mrem_profile_gemm_begin(mrem_ctx* ctx) {
 extern "C" mrem_status mrem_profile_gemm_end(mrem_ctx* ctx, double* ms, double* flops, int64_t* launches) {
   if (!ctx || !ms || !flops || !launches) return fail(ctx, MREM_EINVAL, "mrem_profile_gemm_end: null argument");
   return gemm_profile_end(&ctx->prof, ms, flops, launches) == 0 ? MREM_OK : fail(ctx, MREM_EHIP, "mrem_profile_gemm_end: event query failed");
+}
+
+extern "C" int32_t mrem_profile_kernel_count(const mrem_ctx* ctx) { return ctx ? (int32_t)ctx->prof.stats.size() : -1; }
+extern "C" mrem_status mrem_profile_kernel_get(const mrem_ctx* ctx, int32_t i, char* name, int32_t name_bytes, double* ms, double* bytes,
+                                               int64_t* launches) {
+  if (!ctx || !name || name_bytes < 1 || !ms || !bytes || !launches) return fail(ctx, MREM_EINVAL, "mrem_profile_kernel_get: null argument");
+  if (i < 0 || i >= (int32_t)ctx->prof.stats.size()) return fail(ctx, MREM_EINVAL, "mrem_profile_kernel_get: no such entry");
+  const KernelStat& k = ctx->prof.stats[(size_t)i];
+  snprintf(name, (size_t)name_bytes, "%s", k.label);
+  *ms = k.ms; *bytes = k.bytes; *launches = k.launches;
+  return MREM_OK;
 }
 
 extern "C" mrem_status mrem_set_nonfinite_flag(mrem_ctx* ctx, int32_t* device_flag) {

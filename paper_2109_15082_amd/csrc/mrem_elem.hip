@@ -119,7 +119,7 @@ __global__ void act_quantize_k(const T* __restrict__ a, T* __restrict__ codes, i
   }
 }
 void act_quantize(int dt, const void* a, void* codes, int64_t n, QArg q, hipStream_t st, int8_t* codes8) {
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(act_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)a, (T*)codes, n / 8, q, codes8));
+  MREM_DISPATCH(dt, MREM_LAUNCH(act_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)a, (T*)codes, n / 8, q, codes8));
 }
 // Eq. 4 folded into the input quantizer of a module's first layer: mixed = wa * a + wb * b is stored (the
 // layer's residual path and its backward pass read it) and quantized in the same pass.
@@ -144,7 +144,7 @@ __global__ void mix_quantize_k(const T* __restrict__ a, const T* __restrict__ b,
 }
 void mix_quantize(int dt, const void* a, const void* b, float wa, float wb, void* mixed, void* codes, int64_t n, QArg q, hipStream_t st,
                   int8_t* codes8) {
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(mix_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)a, (const T*)b, wa, wb, (T*)mixed,
+  MREM_DISPATCH(dt, MREM_LAUNCH(mix_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)a, (const T*)b, wa, wb, (T*)mixed,
                                        (T*)codes, n / 8, q, codes8));
 }
 template <class T>
@@ -156,7 +156,7 @@ __global__ void codes_to_i8_k(const T* __restrict__ codes, int8_t* __restrict__ 
   }
 }
 void codes_to_i8(int dt, const void* codes, int8_t* codes8, int64_t n, float shift, hipStream_t st) {
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(codes_to_i8_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)codes, codes8, n / 8, shift));
+  MREM_DISPATCH(dt, MREM_LAUNCH(codes_to_i8_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)codes, codes8, n / 8, shift));
 }
 
 // Three column sections of qkv[T,3H] with their own quantizers.  A thread owns one 8-element
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(kQkvThreads) void qkv_quantize_k(const T* __restric
 }
 void qkv_quantize(int dt, const void* qkv, void* codes, int T_, int H, QArg q, QArg k, QArg v, hipStream_t st) {
   const QkvGrid g = qkv_grid(T_, H);
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(qkv_quantize_k<T>, dim3(g.gx, g.gy), dim3(kQkvThreads), 0, st, (const T*)qkv, (T*)codes, T_,
+  MREM_DISPATCH(dt, MREM_LAUNCH(qkv_quantize_k<T>, dim3(g.gx, g.gy), dim3(kQkvThreads), 0, st, (const T*)qkv, (T*)codes, T_,
                                        H / 8, q, k, v));
 }
 
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(kQkvThreads) void qkv_quant_bwd_k(const T* __restri
 ColGrid qkv_quant_bwd(int dt, const void* d_qkvh, const void* qkv, void* d_qkv, int T_, int H, QArg q, QArg k, QArg v,
                       float* partials, float* colparts, hipStream_t st) {
   const ColGrid g = col_grid(T_, 3 * H);
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(qkv_quant_bwd_k<T>, dim3(g.gx, g.gy), dim3(kQkvThreads), 0, st, (const T*)d_qkvh, (const T*)qkv,
+  MREM_DISPATCH(dt, MREM_LAUNCH(qkv_quant_bwd_k<T>, dim3(g.gx, g.gy), dim3(kQkvThreads), 0, st, (const T*)d_qkvh, (const T*)qkv,
                                        (T*)d_qkv, T_, H / 8, q, k, v, partials, colparts));
   return g;
 }
@@ -307,7 +307,7 @@ __global__ void quant_bwd_k(const T* __restrict__ dq, const T* __restrict__ a, T
 }
 int quant_bwd(int dt, const void* d_q, const void* a, void* d_out, int64_t n, QArg q, float* partials, hipStream_t st) {
   const int g = ew_grid(n);
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(quant_bwd_k<T>, dim3(g), dim3(256), 0, st, (const T*)d_q, (const T*)a, (T*)d_out,
+  MREM_DISPATCH(dt, MREM_LAUNCH(quant_bwd_k<T>, dim3(g), dim3(256), 0, st, (const T*)d_q, (const T*)a, (T*)d_out,
                                        n / 8, q, partials));
   return g;
 }
@@ -335,7 +335,7 @@ __global__ void gelu_quantize_k(const T* __restrict__ u, T* __restrict__ codes, 
   }
 }
 void gelu_quantize(int dt, const void* u, void* codes, int64_t n, QArg q, hipStream_t st, int8_t* codes8, float shift8) {
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(gelu_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)u, (T*)codes, n / 8, q, codes8,
+  MREM_DISPATCH(dt, MREM_LAUNCH(gelu_quantize_k<T>, dim3(ew_grid(n)), dim3(256), 0, st, (const T*)u, (T*)codes, n / 8, q, codes8,
                                        shift8));
 }
 
@@ -388,7 +388,7 @@ __global__ __launch_bounds__(kQkvThreads) void gelu_quant_bwd_k(const T* __restr
 ColGrid gelu_quant_bwd(int dt, const void* dgh, const void* u, void* du, int T_, int C, QArg q, float* partials, float* colparts,
                        hipStream_t st) {
   const ColGrid g = col_grid(T_, C);
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(gelu_quant_bwd_k<T>, dim3(g.gx, g.gy), dim3(kQkvThreads), 0, st, (const T*)dgh, (const T*)u, (T*)du,
+  MREM_DISPATCH(dt, MREM_LAUNCH(gelu_quant_bwd_k<T>, dim3(g.gx, g.gy), dim3(kQkvThreads), 0, st, (const T*)dgh, (const T*)u, (T*)du,
                                        T_, C / 8, q, partials, colparts));
   return g;
 }
@@ -458,7 +458,7 @@ __global__ void ln_fwd_k(const T* __restrict__ x, const T* __restrict__ r, const
 }
 void ln_fwd(int dt, const void* x, const void* r, const float* gamma, const float* beta, void* y, void* ycodes, QArg q,
             float* mu, float* rstd, int T_, int H, float eps, hipStream_t st, int8_t* ycodes8) {
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(ln_fwd_k<T>, dim3((T_ + 3) / 4), dim3(256), 0, st, (const T*)x, (const T*)r, gamma, beta,
+  MREM_DISPATCH(dt, MREM_LAUNCH(ln_fwd_k<T>, dim3((T_ + 3) / 4), dim3(256), 0, st, (const T*)x, (const T*)r, gamma, beta,
                                        (T*)y, (T*)ycodes, q, mu, rstd, T_, H, eps, ycodes8));
 }
 
@@ -643,7 +643,7 @@ int ln_bwd(int dt, const void* d_a, const void* d_b, const void* d_q, const void
 #define MREM_LN_BWD(NCH)                                                                                                        \
   MREM_DISPATCH(dt, if (lds > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ln_bwd_k<T, NCH>),                   \
                                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);            \
-                    hipLaunchKernelGGL((ln_bwd_k<T, NCH>), dim3(g), dim3(64 * kLnBwdWaves), lds, st, (const T*)d_a, (const T*)d_b, \
+                    MREM_LAUNCH((ln_bwd_k<T, NCH>), dim3(g), dim3(64 * kLnBwdWaves), lds, st, (const T*)d_a, (const T*)d_b, \
                                        (const T*)d_q, (const T*)a_q, q, (const T*)x, (const T*)r, mu, rstd, gamma, (T*)dr, partials, T_, H, \
                                        (const T*)loss_ref, loss_scale))
   if (H <= 512) MREM_LN_BWD(1);
@@ -711,7 +711,7 @@ void reduce_jobs(const ReduceJob* jobs, int njobs, hipStream_t st) {
       units += t.j[i].len == 1 ? 1 : (t.j[i].len + 15) / 16;
     }
     t.unit_start[t.n] = units;
-    hipLaunchKernelGGL(reduce_jobs_k, dim3(units), dim3(256), 0, st, t);
+    MREM_LAUNCH(reduce_jobs_k, dim3(units), dim3(256), 0, st, t);
   }
 }
 
@@ -725,7 +725,7 @@ __global__ void loss_total_k(float* loss_out, int n_layers, int* nonfinite_flag)
   }
 }
 void loss_total(float* loss_out, int n_layers, int* nonfinite_flag, hipStream_t st) {
-  hipLaunchKernelGGL(loss_total_k, dim3(1), dim3(64), 0, st, loss_out, n_layers, nonfinite_flag);
+  MREM_LAUNCH(loss_total_k, dim3(1), dim3(64), 0, st, loss_out, n_layers, nonfinite_flag);
 }
 
 __global__ void fill_k(float* p, float v, int64_t n) {
@@ -735,7 +735,7 @@ void fill_f32(float* p, float v, int64_t n, hipStream_t st) {
   int g = (int)((n + 255) / 256);
   if (g > 4096) g = 4096;
   if (g < 1) g = 1;
-  hipLaunchKernelGGL(fill_k, dim3(g), dim3(256), 0, st, p, v, n);
+  MREM_LAUNCH(fill_k, dim3(g), dim3(256), 0, st, p, v, n);
 }
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 struct FillTable {
@@ -765,7 +765,7 @@ void zero_regions(const FillRegion* regions, int count, hipStream_t st) {
     int gx = (int)((longest / 4 + 255) / 256);
     if (gx > 2048) gx = 2048;
     if (gx < 1) gx = 1;
-    hipLaunchKernelGGL(zero_regions_k, dim3(gx, nr), dim3(256), 0, st, t);
+    MREM_LAUNCH(zero_regions_k, dim3(gx, nr), dim3(256), 0, st, t);
   }
 }
 
@@ -779,7 +779,7 @@ void axpby(int dt, const void* a, const void* b, float wa, float wb, void* out, 
   int g = (int)((n + 255) / 256);
   if (g > 4096) g = 4096;
   if (g < 1) g = 1;
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(axpby_k<T>, dim3(g), dim3(256), 0, st, (const T*)a, (const T*)b, wa, wb, (T*)out, n));
+  MREM_DISPATCH(dt, MREM_LAUNCH(axpby_k<T>, dim3(g), dim3(256), 0, st, (const T*)a, (const T*)b, wa, wb, (T*)out, n));
 }
 
 template <class T>
@@ -790,7 +790,7 @@ void convert_f32(int dt, const float* src, void* dst, int64_t n, hipStream_t st)
   int g = (int)((n + 255) / 256);
   if (g > 8192) g = 8192;
   if (g < 1) g = 1;
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(convert_k<T>, dim3(g), dim3(256), 0, st, src, (T*)dst, n));
+  MREM_DISPATCH(dt, MREM_LAUNCH(convert_k<T>, dim3(g), dim3(256), 0, st, src, (T*)dst, n));
 }
 
 // ------------------------------------------------------------------------------
@@ -842,14 +842,14 @@ void weight_quantize_i8(const float* w, float* scale, int8_t* codes, int64_t N, 
                         hipStream_t st) {
   const float qp = (float)((1 << (bits - 1)) - 1);
   if (per_channel) {
-    hipLaunchKernelGGL(weight_quantize_i8_k, dim3((unsigned)N), dim3(256), 0, st, w, scale, codes, K, qp, init_scale);
+    MREM_LAUNCH(weight_quantize_i8_k, dim3((unsigned)N), dim3(256), 0, st, w, scale, codes, K, qp, init_scale);
     return;
   }
   const int64_t n = N * K;
-  if (init_scale) hipLaunchKernelGGL(tensor_step_init_k, dim3(1), dim3(1024), 0, st, w, scale, n, qp);
+  if (init_scale) MREM_LAUNCH(tensor_step_init_k, dim3(1), dim3(1024), 0, st, w, scale, n, qp);
   int g = (int)((n + 255) / 256);
   if (g > 8192) g = 8192;
-  hipLaunchKernelGGL(tensor_quantize_i8_k, dim3(g), dim3(256), 0, st, w, (const float*)scale, codes, n, qp);
+  MREM_LAUNCH(tensor_quantize_i8_k, dim3(g), dim3(256), 0, st, w, (const float*)scale, codes, n, qp);
 }
 
 __global__ void weight_step_init_k(const float* __restrict__ w, float* __restrict__ scale, int64_t K, float qp) {
@@ -859,7 +859,7 @@ __global__ void weight_step_init_k(const float* __restrict__ w, float* __restric
 }
 void weight_step_init(const float* w, float* scale, int64_t N, int64_t K, int bits, hipStream_t st) {
   const float qp = (float)((1 << (bits - 1)) - 1);
-  hipLaunchKernelGGL(weight_step_init_k, dim3((unsigned)N), dim3(256), 0, st, w, scale, K, qp);
+  MREM_LAUNCH(weight_step_init_k, dim3((unsigned)N), dim3(256), 0, st, w, scale, K, qp);
 }
 
 __global__ void tie_steps_max_k(float* __restrict__ scale, int64_t N) {
@@ -869,7 +869,7 @@ __global__ void tie_steps_max_k(float* __restrict__ scale, int64_t N) {
   m = block_max(m, red);
   for (int64_t i = threadIdx.x; i < N; i += blockDim.x) scale[i] = m;
 }
-void tie_steps_max(float* scale, int64_t N, hipStream_t st) { hipLaunchKernelGGL(tie_steps_max_k, dim3(1), dim3(256), 0, st, scale, N); }
+void tie_steps_max(float* scale, int64_t N, hipStream_t st) { MREM_LAUNCH(tie_steps_max_k, dim3(1), dim3(256), 0, st, scale, N); }
 
 // codes (integer-valued, storage type), dequantized weights s*code (same layout), and
 // zcorr[n] = s[n] * sum_k code (sum_k of the stored weight when the quantizers are off); one block per output channel, all matrices of a table in one launch
@@ -919,7 +919,7 @@ void weight_prepare(int dt, const WeightJob* jobs, int njobs, int bits, hipStrea
     for (int j = 0; j < tab.njobs; ++j) { tab.job[j] = jobs[j0 + j]; tab.first_row[j] = rows; rows += jobs[j0 + j].N; }
     tab.first_row[tab.njobs] = rows;
     if (rows == 0) continue;
-    MREM_DISPATCH(dt, hipLaunchKernelGGL(weight_codes_k<T>, dim3(rows), dim3(128), 0, st, tab, qp, on));
+    MREM_DISPATCH(dt, MREM_LAUNCH(weight_codes_k<T>, dim3(rows), dim3(128), 0, st, tab, qp, on));
   }
 }
 
@@ -953,7 +953,7 @@ int absminmax(int dt, const void* a, int rows, int cols, int ld, int gelu, float
   int g = (int)((n + 255) / 256);
   if (g > 1024) g = 1024;
   if (g < 1) g = 1;
-  MREM_DISPATCH(dt, hipLaunchKernelGGL(absminmax_k<T>, dim3(g), dim3(256), 0, st, (const T*)a, rows, cols, ld, gelu, partials));
+  MREM_DISPATCH(dt, MREM_LAUNCH(absminmax_k<T>, dim3(g), dim3(256), 0, st, (const T*)a, rows, cols, ld, gelu, partials));
   return g;
 }
 __global__ void calib_finalize_k(const float* __restrict__ partials, int nparts, int mode, float qp, float* s_out, float* z_out) {
@@ -978,7 +978,7 @@ __global__ void calib_finalize_k(const float* __restrict__ partials, int nparts,
   }
 }
 void calib_finalize(const float* partials, int nparts, int mode, float qp, float* s_out, float* z_out, hipStream_t st) {
-  hipLaunchKernelGGL(calib_finalize_k, dim3(1), dim3(256), 0, st, partials, nparts, mode, qp, s_out, z_out);
+  MREM_LAUNCH(calib_finalize_k, dim3(1), dim3(256), 0, st, partials, nparts, mode, qp, s_out, z_out);
 }
 
 // ------------------------------------------------------------------------------
@@ -1091,8 +1091,8 @@ void adam_matrix(const AdamJob* jobs, int njobs, int bits, AdamArg a, int write_
     for (int j = 0; j < tab.njobs; ++j) { tab.job[j] = jobs[j0 + j]; tab.first_row[j] = rows; rows += jobs[j0 + j].N; }
     tab.first_row[tab.njobs] = rows;
     if (rows == 0) continue;
-    hipLaunchKernelGGL(adam_matrix_k, dim3(rows), dim3(256), 0, st, tab, qp, on, a, write_grads, (on && tied) ? 1 : 0);
-    if (on && tied) hipLaunchKernelGGL(adam_tied_steps_k, dim3(tab.njobs), dim3(256), 0, st, tab, a);
+    MREM_LAUNCH(adam_matrix_k, dim3(rows), dim3(256), 0, st, tab, qp, on, a, write_grads, (on && tied) ? 1 : 0);
+    if (on && tied) MREM_LAUNCH(adam_tied_steps_k, dim3(tab.njobs), dim3(256), 0, st, tab, a);
   }
 }
 
@@ -1120,7 +1120,7 @@ void adam_vector(float* p, const float* g, float* m, float* v, const VecJob* job
     for (int j = 0; j < nj; ++j) { tab.job[j] = jobs[j0 + j]; if (jobs[j0 + j].n > longest) longest = jobs[j0 + j].n; }
     int gx = (int)((longest + 255) / 256);
     if (gx > 1024) gx = 1024;
-    hipLaunchKernelGGL(adam_vector_k, dim3(gx, nj), dim3(256), 0, st, p, g, m, v, tab, a);
+    MREM_LAUNCH(adam_vector_k, dim3(gx, nj), dim3(256), 0, st, p, g, m, v, tab, a);
   }
 }
 

@@ -8,6 +8,7 @@
 #include <hip/hip_ext.h>
 
 #include <atomic>
+#include <string>
 #include <cstdlib>
 #include <type_traits>
 
@@ -19,16 +20,12 @@ namespace mrem {
 // The records live in a GemmProfile that the caller (a context) owns.  Return codes of event calls are
 // not looked at here: the runtime keeps the last error, and every entry point of the library ends by
 // reading it (hipGetLastError).
-namespace {
-// While a timed launch is being issued on this thread: the event pair that the launch itself carries (the
-// runtime stamps them with the kernel's own begin and end, so no packet is added to the queue and the
-// elapsed time is the kernel's duration).
-thread_local hipEvent_t g_launch_e0 = nullptr, g_launch_e1 = nullptr;
-}  // namespace
+thread_local LaunchEvents tl_launch_events;
 
 void gemm_profile_begin(GemmProfile* p) {
   for (auto& r : p->recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
   p->recs.clear();
+  p->stats.clear();
   p->on = true;
 }
 int gemm_profile_end(GemmProfile* p, double ms[2], double flops[2], int64_t launches[2]) {
@@ -39,9 +36,19 @@ int gemm_profile_end(GemmProfile* p, double ms[2], double flops[2], int64_t laun
   for (auto& r : p->recs) {
     float e = 0.f;
     if (hipEventSynchronize(r.e1) != hipSuccess || hipEventElapsedTime(&e, r.e0, r.e1) != hipSuccess) rc = -1;
-    ms[r.cls] += e;
-    flops[r.cls] += r.flops;
-    launches[r.cls] += 1;
+    if (r.cls < 2) {
+      ms[r.cls] += e;
+      flops[r.cls] += r.flops;
+      launches[r.cls] += 1;
+    } else {
+      KernelStat* ks = nullptr;
+      for (auto& k : p->stats)
+        if (k.label == r.label || std::string(k.label) == r.label) ks = &k;
+      if (!ks) { p->stats.push_back(KernelStat{r.label, 0.0, 0.0, 0}); ks = &p->stats.back(); }
+      ks->ms += e;
+      ks->bytes += r.flops;
+      ks->launches += 1;
+    }
     (void)hipEventDestroy(r.e0);
     (void)hipEventDestroy(r.e1);
   }
@@ -351,9 +358,9 @@ static void launch_mfma(const void* A, int lda, const void* B, int ldb, void* C,
     configured_dev.store(dev);
   }
   const int tiles_m = M / BM, tiles_n = N / BN;
-  if (g_launch_e0) {
+  if (tl_launch_events.e0) {
     hipExtLaunchKernelGGL((gemm_mfma_k<BM, BN, WAVES_M, WAVES_N, AT, BT, BK, TO, I8>), dim3(tiles_m * tiles_n, k_splits), dim3(NTHREADS),
-                          lds, st, g_launch_e0, g_launch_e1, 0, (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (TO*)C, ldc, M, N, K, e,
+                          lds, st, tl_launch_events.e0, tl_launch_events.e1, 0, (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (TO*)C, ldc, M, N, K, e,
                           tiles_m, tiles_n);
     return;
   }
@@ -379,10 +386,10 @@ void gemm(int dt, int a_t, int b_t, const void* A, int lda, const void* B, int l
   r.flops = 2.0 * (double)M * (double)N * (double)K;
   (void)hipEventCreate(&r.e0);
   (void)hipEventCreate(&r.e1);
-  g_launch_e0 = r.e0;
-  g_launch_e1 = r.e1;
+  tl_launch_events.e0 = r.e0;
+  tl_launch_events.e1 = r.e1;
   gemm_launch(dt, a_t, b_t, A, lda, B, ldb, C, ldc, M, N, K, e, st);
-  g_launch_e0 = g_launch_e1 = nullptr;
+  tl_launch_events = LaunchEvents();
   prof->recs.push_back(r);
 }
 
@@ -430,10 +437,10 @@ void gemm_i8(const void* A, int lda, const void* B, int ldb, void* C, int ldc, i
   r.flops = 2.0 * (double)M * (double)N * (double)K;
   (void)hipEventCreate(&r.e0);
   (void)hipEventCreate(&r.e1);
-  g_launch_e0 = r.e0;
-  g_launch_e1 = r.e1;
+  tl_launch_events.e0 = r.e0;
+  tl_launch_events.e1 = r.e1;
   gemm_i8_launch(A, lda, B, ldb, C, ldc, M, N, K, e, st);
-  g_launch_e0 = g_launch_e1 = nullptr;
+  tl_launch_events = LaunchEvents();
   r.cls = 1;
   prof->recs.push_back(r);
 }
@@ -484,7 +491,7 @@ static void gemm_launch(int dt, int a_t, int b_t, const void* A, int lda, const 
     return;
   }
   dim3 g((N + 63) / 64, (M + 63) / 64);
-  const hipEvent_t t0 = g_launch_e0, t1 = g_launch_e1;  // the fallback kernels are timed by recorded events
+  const hipEvent_t t0 = tl_launch_events.e0, t1 = tl_launch_events.e1;  // the fallback kernels are timed by recorded events
   if (t0) (void)hipEventRecord(t0, st);
   if (dt == DT_BF16) {
     if (e.out_f32)

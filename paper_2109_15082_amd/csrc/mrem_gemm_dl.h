@@ -350,9 +350,9 @@ static void launch_dl(const void* A, int lda, const void* B, int ldb, void* C, i
     configured_dev.store(dev);
   }
   const int tiles_m = M / BM, tiles_n = N / BN;
-  if (g_launch_e0) {
+  if (tl_launch_events.e0) {
     hipExtLaunchKernelGGL((gemm_dl_k<BM, BN, WAVES_M, WAVES_N, AT, BT, STAGES, RB, TO, I8, MINB>), dim3(tiles_m * tiles_n, k_splits),
-                          dim3(NTHREADS), lds, st, g_launch_e0, g_launch_e1, 0, (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (TO*)C, ldc, M, N,
+                          dim3(NTHREADS), lds, st, tl_launch_events.e0, tl_launch_events.e1, 0, (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (TO*)C, ldc, M, N,
                           K, e, tiles_m, tiles_n);
     return;
   }

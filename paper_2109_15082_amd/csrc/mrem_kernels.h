@@ -4,6 +4,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -44,13 +45,34 @@ struct Epilogue {
 // A context owns one; products launched with a profile whose `on` is set are recorded in it.
 struct GemmRecord {
   hipEvent_t e0, e1;
-  double flops;
-  int cls = 0;  // 0: bf16 (or fp32) operands, 1: int8 operands
+  double flops;             // 2 M N K of a product; algorithmic bytes of a bandwidth-bound kernel
+  int cls = 0;              // 0: product on bf16 (or fp32) operands, 1: product on int8 operands, 2: bandwidth-bound kernel
+  const char* label = "";   // cls 2: which kernel (a string literal)
+};
+struct KernelStat {
+  const char* label;
+  double ms, bytes;
+  int64_t launches;
 };
 struct GemmProfile {
   bool on = false;
   std::vector<GemmRecord> recs;
+  std::vector<KernelStat> stats;  // per label, filled by gemm_profile_end from the cls-2 records
 };
+// While a timed launch is being issued on this thread: the event pair that the launch itself carries (the
+// runtime stamps them with the kernel's own begin and end, so no packet is added to the queue and the
+// elapsed time is the kernel's duration).  Launch sites that can be timed go through MREM_LAUNCH.
+struct LaunchEvents {
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+};
+extern thread_local LaunchEvents tl_launch_events;
+#define MREM_LAUNCH(kern, grid, block, lds, st, ...)                                                                        \
+  do {                                                                                                                      \
+    if (::mrem::tl_launch_events.e0)                                                                                        \
+      hipExtLaunchKernelGGL(kern, grid, block, lds, st, ::mrem::tl_launch_events.e0, ::mrem::tl_launch_events.e1, 0, __VA_ARGS__); \
+    else                                                                                                                    \
+      hipLaunchKernelGGL(kern, grid, block, lds, st, __VA_ARGS__);                                                          \
+  } while (0)
 void gemm_profile_begin(GemmProfile* p);
 int gemm_profile_end(GemmProfile* p, double ms[2], double flops[2], int64_t launches[2]);  // [0] bf16 operands, [1] int8 operands
 
