@@ -1,7 +1,8 @@
 // Matrix-product kernel with operands moved global -> LDS by the direct-to-LDS load (no
 // registers in between) ahead of the MFMAs.  Included by mrem_gemm.hip only.
 //
-//   C[M,N] = op(A) * op(B)^T, fused epilogue as in gemm_mfma_k.
+//   C[M,N] = op(A) * op(B)^T with the fused epilogue
+//   out = acc * (alpha * col_scale[n]) + beta * (col_vec[n] + row_vec[m]) + bias[n]  (optional GELU, bf16 or fp32 out).
 //
 // Block tile BM x BN x BK with BK = RB / 2 bf16 values (RB = bytes of k per tile row and stage,
 // 64 or 128; int8 codes: RB values), WAVES_M x WAVES_N wavefronts, each owning
@@ -173,7 +174,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void gemm_dl_k(const 
   static_assert(!I8 || (!AT && !BT), "int8 operands are read along k only");
   static_assert(STAGES >= 2, "double buffering at least");
 
-  // tile order: as in gemm_mfma_k (a contiguous range of tiles per XCD, groups of 8 tile rows)
+  // Tile order: consecutive block ids land on different XCDs (8 of them, each with its own L2), so each XCD
+  // gets a contiguous range of tiles, walked in groups of 8 tile rows so that concurrently running blocks
+  // share operand panels in that L2.
   const int nblocks = tiles_m * tiles_n;
   int pid = blockIdx.x;
   if ((nblocks & 7) == 0) pid = (pid & 7) * (nblocks >> 3) + (pid >> 3);
@@ -208,9 +211,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void gemm_dl_k(const 
     }
   }
   auto issue = [&](int stage_slot) {
-#ifdef MREM_DL_NOLOAD
-    if (K > 0) return;
-#endif
     unsigned char* dst = smem_dl + stage_slot * STAGE_BYTES + wave * (LPW * 1024);
 #pragma unroll
     for (int i = 0; i < LPW; ++i) {
@@ -235,9 +235,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void gemm_dl_k(const 
   const int lds0 = (int)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_dl;
 
   auto mfmas = [&](const typename OpA::frag_t (&af)[MT], const typename OpB::frag_t (&bf)[NT]) {
-#ifdef MREM_DL_NOMMA
-    if (K > 0) return;
-#endif
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
