@@ -15,6 +15,7 @@ Pre-trained Language Models"):
                             softmax probabilities and the GELU output (asymmetric);
                             LayerNorm, skip connections and biases stay full precision.
 * Section 3.1.1          -- straight-through estimator for the rounding.
+* Section 3.2, Eq. 2     -- reconstruction of a single matrix product (rem_grads, rem_step).
 * Section 4.1, Eq. 3     -- the module objective: sum over the module's layers of the
                             squared distance between quantized and full-precision
                             layer outputs; variables are the module's parameters and
@@ -640,6 +641,44 @@ def module_step(x_fp, x_q, teacher, student, adam_m, adam_v, t: int, lr: float, 
             if name in STEP_NAMES or name == "s_a":
                 lp[name] = np.maximum(lp[name], cfg.step_floor)
     return res
+
+
+# ----------------------------------------------------------------------------
+# REM: reconstruction of a single matrix product (Section 3.2, Eq. 2)
+# ----------------------------------------------------------------------------
+
+def rem_grads(a_fp, a_q, w_fp, w, s_w, s_a: float, cfg: Config):
+    """Eq. 2 for one product: y = a w_fp^T against y^ = Q(a_q) Q(w)^T, symmetric quantizers (one step s_a
+    for the activations, one step per output channel -- or per matrix -- for the weights), no bias.
+    Returns (loss, y, y_hat, {'w', 's_w', 's_a'} straight-through gradients)."""
+    R = lambda t: round_store(t, cfg.act_round)
+    a_fp, a_q, w_fp, w = (np.asarray(t, dtype=np.float64) for t in (a_fp, a_q, w_fp, w))
+    y = R(a_fp @ w_fp.T)
+    qn, qp = sym_range(cfg.a_bits)
+    a_hat, qa, va, ina = fake_quant_forward(a_q, s_a, qn, qp, 0.0, cfg.act_round is not None)
+    codes, w_hat, vw, inw = quantize_weight(w, s_w, cfg.w_bits)
+    y_hat = R(a_hat @ w_hat.T)
+    diff = y_hat - y
+    scale = 1.0 / diff.size if cfg.loss_mean else 1.0
+    loss = float((diff * diff).sum() * scale)
+    dy = 2.0 * diff * scale
+    dw, dsw = fake_quant_backward(dy.T @ a_hat, codes, vw, inw, reduce_axes=1)
+    if not cfg.per_channel:
+        dsw = np.full_like(dsw, dsw.sum())
+    _, dsa = fake_quant_backward(dy @ w_hat, qa, va, ina)
+    return loss, y, y_hat, {"w": dw, "s_w": dsw, "s_a": float(dsa)}
+
+
+def rem_step(a_fp, a_q, w_fp, p: Dict[str, np.ndarray], m: Dict[str, np.ndarray], v: Dict[str, np.ndarray], t: int, lr: float, cfg: Config):
+    """One update of Eq. 2's variables (w and all step sizes): p, m, v are dicts with keys 'w' [N,K],
+    's_w' [N], 's_a' (array of one value), updated in place.  Returns (loss, y, y_hat, grads)."""
+    loss, y, y_hat, g = rem_grads(a_fp, a_q, w_fp, p["w"], p["s_w"], float(p["s_a"][0]), cfg)
+    for name in ("w", "s_w", "s_a"):
+        grad = np.asarray(g[name], dtype=np.float64).reshape(np.shape(p[name]))
+        p[name], m[name], v[name] = adamw_update(p[name], grad, m[name], v[name], t, lr, cfg, decay=(name == "w"))
+        if name != "w":
+            p[name] = np.maximum(p[name], cfg.step_floor)
+    return loss, y, y_hat, g
 
 
 # ----------------------------------------------------------------------------

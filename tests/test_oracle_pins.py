@@ -875,3 +875,64 @@ def test_fp32_accumulation_mode_is_the_same_forward_pass():
         assert 0 < e < 1e-5
     with pytest.raises(ValueError):
         O.module_forward(x, teacher, tiny_cfg(accumulate="f16"), 2, 6, quant=False)
+
+
+def test_rem_single_product_vs_autograd_and_adamw():
+    """Eq. 2: gradients of the single-product reconstruction objective against torch fp64 autograd of the
+    frozen-residual surrogate (clipped weights and activations included), the loss against its definition
+    written out with loops, and one update against torch.optim.AdamW."""
+    rng = np.random.default_rng(21)
+    T, N, K = 6, 5, 7
+    a = rng.standard_normal((T, K)); a_q = a + 0.05 * rng.standard_normal((T, K))
+    w0 = rng.standard_normal((N, K)) * 0.3
+    w = w0 + 0.01 * rng.standard_normal((N, K))
+    s_w = (np.abs(w).max(axis=1) / 7 * rng.uniform(0.5, 1.0, size=N)).astype(np.float32).astype(np.float64)   # some weights clip
+    s_a = float(np.abs(a_q).max() / 127 * 0.7)                            # some activations clip
+    for loss_mean in (True, False):
+        cfg = O.Config(n_layers=1, hidden=8, n_heads=1, ffn=8, w_bits=4, a_bits=8, loss_mean=loss_mean)
+        loss, y, y_hat, g = O.rem_grads(a, a_q, w0, w, s_w, s_a, cfg)
+        # the definition, index by index
+        want = 0.0
+        _, a_hat_q, _, _ = O.fake_quant_forward(a_q, s_a, -127, 127, 0.0, False)
+        wq, w_hat, _, _ = O.quantize_weight(w, s_w, 4)
+        for t in range(T):
+            for n in range(N):
+                yq = sum(s_a * a_hat_q[t, k] * s_w[n] * wq[n, k] for k in range(K))
+                yf = sum(a[t, k] * w0[n, k] for k in range(K))
+                want += (yq - yf) ** 2
+        assert np.isclose(loss, want / (T * N) if loss_mean else want, rtol=1e-12, atol=0)
+        # autograd of the surrogate x^ = s (clamp(x / s) + kappa), kappa frozen
+        ta, tw = torch.tensor(a_q), torch.tensor(w, requires_grad=True)
+        tsa = torch.tensor(s_a, requires_grad=True, dtype=torch.float64)
+        tsw = torch.tensor(s_w, requires_grad=True)
+        ca = torch.clamp(ta / tsa, -127, 127)
+        ah = tsa * (ca + (torch.round(ca) - ca).detach())
+        cw = torch.clamp(tw / tsw[:, None], -7, 7)
+        wh = tsw[:, None] * (cw + (torch.round(cw) - cw).detach())
+        d = ah @ wh.T - torch.tensor(a @ w0.T)
+        L = (d * d).mean() if loss_mean else (d * d).sum()
+        L.backward()
+        assert np.isclose(loss, L.item(), rtol=1e-12, atol=0)
+        np.testing.assert_allclose(g["w"], tw.grad.numpy(), rtol=1e-9, atol=1e-14)
+        # the weight ratio w / s is an fp32 value in the oracle (it decides the code): 6e-8 relative on v in q - v
+        np.testing.assert_allclose(g["s_w"], tsw.grad.numpy(), rtol=1e-5, atol=1e-9)
+        np.testing.assert_allclose(g["s_a"], tsa.grad.item(), rtol=1e-9)
+    # per-matrix step: the gradient is the sum over rows, repeated
+    cfg1 = O.Config(n_layers=1, hidden=8, n_heads=1, ffn=8, w_bits=4, a_bits=8, per_channel=False)
+    s1 = np.full(N, s_w.max())
+    _, _, _, g1 = O.rem_grads(a, a_q, w0, w, s1, s_a, cfg1)
+    _, _, _, gp = O.rem_grads(a, a_q, w0, w, s1, s_a, O.Config(n_layers=1, hidden=8, n_heads=1, ffn=8, w_bits=4, a_bits=8))
+    assert np.allclose(g1["s_w"], gp["s_w"].sum()) and np.all(g1["s_w"] == g1["s_w"][0])
+    # one update vs torch.optim.AdamW (decay on w only)
+    cfg = O.Config(n_layers=1, hidden=8, n_heads=1, ffn=8, w_bits=4, a_bits=8)
+    p = {"w": w.copy(), "s_w": s_w.copy(), "s_a": np.array([s_a])}
+    m = {k: np.zeros_like(x) for k, x in p.items()}
+    v = {k: np.zeros_like(x) for k, x in p.items()}
+    _, _, _, g = O.rem_step(a, a_q, w0, p, m, v, 1, 1e-3, cfg)
+    for name, wd in (("w", 0.01), ("s_w", 0.0), ("s_a", 0.0)):
+        start = {"w": w, "s_w": s_w, "s_a": np.array([s_a])}[name]
+        tp = torch.tensor(start.copy(), requires_grad=True)
+        opt = torch.optim.AdamW([tp], lr=1e-3, betas=(0.9, 0.999), eps=1e-8, weight_decay=wd)
+        tp.grad = torch.tensor(np.asarray(g[name], dtype=np.float64).reshape(start.shape))
+        opt.step()
+        np.testing.assert_allclose(p[name], np.maximum(tp.detach().numpy(), 1e-8) if name != "w" else tp.detach().numpy(), rtol=1e-10)
