@@ -253,6 +253,25 @@ mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* adam_m, float*
                              void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * mrem_rem_step -- reconstruction error minimisation of ONE matrix product (Section 3.2, Eq. 2; the baseline
+ * that module-wise reconstruction generalises): with a^ = Q(a_q) (symmetric, one step s_a) and w^ = Q(w) (one
+ * step per output channel, or one per matrix with per_channel = 0),
+ *   y = a_fp w_fp^T,  y^ = a^ w^^T,  loss = mean (or sum, loss_mean = 0) of (y^ - y)^2,
+ * straight-through gradients for w, s_w and s_a, one AdamW update (decay on w only; steps kept >= step_floor).
+ * Bit widths, activation type and optimiser constants are the context's; no bias, as in Eq. 2.
+ *   vec, adam_m, adam_v  device fp32 [mrem_rem_vector_count(N, K)] (in/out): w [N,K], then s_w [N], then s_a [1], zero padding
+ *   w_fp     device fp32 [N,K]        the frozen original weights
+ *   a_fp,a_q device act_dtype [T,K]   inputs of the full-precision and of the quantized product (may alias)
+ *   loss_out device fp32 [1]; y_fp, y_q device act_dtype [T,N] (out); grads_out device fp32 like vec, or NULL
+ * T, N, K positive multiples of 8.  Workspace: mrem_rem_workspace_bytes(ctx, T, N, K).
+ */
+int64_t mrem_rem_vector_count(int64_t N, int64_t K);
+size_t mrem_rem_workspace_bytes(const mrem_ctx* ctx, int64_t T, int64_t N, int64_t K);
+mrem_status mrem_rem_step(mrem_ctx* ctx, int64_t T, int64_t N, int64_t K, float* vec, float* adam_m, float* adam_v, int64_t step_index,
+                          float lr, const float* w_fp, const void* a_fp, const void* a_q, float* loss_out, void* y_fp, void* y_q,
+                          float* grads_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * mrem_mix_inputs -- annealed teacher forcing, Eq. 4: out = lambda * x_fp + (1 - lambda) * x_q,
  * elementwise over n values of act_dtype (device). out may alias x_q.
  */

@@ -29,7 +29,7 @@ FIELD_ID = {n: i for i, n in enumerate(FIELDS)}
 EXPORTS = ("mrem_create", "mrem_destroy", "mrem_last_error", "mrem_param_count", "mrem_teacher_count",
            "mrem_param_offset", "mrem_param_size", "mrem_workspace_bytes", "mrem_workspace_offset", "mrem_teacher_cache_bytes",
            "mrem_quantize", "mrem_module_init_steps", "mrem_teacher_prepare", "mrem_module_calibrate",
-           "mrem_module_forward", "mrem_module_forward_static", "mrem_static_scratch_bytes", "mrem_module_step", "mrem_mix_inputs", "mrem_profile_gemm_begin",
+           "mrem_module_forward", "mrem_module_forward_static", "mrem_static_scratch_bytes", "mrem_module_step", "mrem_rem_vector_count", "mrem_rem_workspace_bytes", "mrem_rem_step", "mrem_mix_inputs", "mrem_profile_gemm_begin",
            "mrem_profile_gemm_end", "mrem_profile_kernel_count", "mrem_profile_kernel_get", "mrem_set_nonfinite_flag", "mrem_check_nonfinite", "mrem_schedule_lr", "mrem_schedule_lambda",
            "mrem_queue_bytes", "mrem_queue_create", "mrem_queue_destroy", "mrem_queue_size", "mrem_queue_write_slot", "mrem_queue_push",
            "mrem_queue_publish", "mrem_queue_entry")
@@ -81,6 +81,12 @@ _lib.mrem_static_scratch_bytes.restype = _sz
 _lib.mrem_module_step.argtypes = [_vp, _vp, _vp, _vp, _i64, _f32, _f32, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp,
                                   _vp, _vp, _sz, _vp]
 _lib.mrem_module_step.restype = C.c_int
+_lib.mrem_rem_vector_count.argtypes = [_i64, _i64]
+_lib.mrem_rem_vector_count.restype = _i64
+_lib.mrem_rem_workspace_bytes.argtypes = [_vp, _i64, _i64, _i64]
+_lib.mrem_rem_workspace_bytes.restype = _sz
+_lib.mrem_rem_step.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.mrem_rem_step.restype = C.c_int
 _lib.mrem_mix_inputs.argtypes = [_vp, _vp, _vp, _f32, _vp, _i64, _vp]
 _lib.mrem_mix_inputs.restype = C.c_int
 
@@ -239,6 +245,21 @@ def mrem_module_step(ctx, params, adam_m, adam_v, step_index, lr, lam, teacher, 
                                  _ptr(teacher_cache), _ptr(x_fp), _ptr(x_q), _ptr(seqlens), batch, seq, _ptr(loss_out),
                                  _ptr(per_layer_fp), _ptr(per_layer_q), _ptr(grads_out), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream(stream)), ctx)
+
+
+def mrem_rem_vector_count(N: int, K: int) -> int:
+    return _lib.mrem_rem_vector_count(N, K)
+
+
+def mrem_rem_workspace_bytes(ctx, T: int, N: int, K: int) -> int:
+    return _lib.mrem_rem_workspace_bytes(ctx, T, N, K)
+
+
+def mrem_rem_step(ctx, T, N, K, vec, adam_m, adam_v, step_index, lr, w_fp, a_fp, a_q, loss_out, y_fp, y_q, grads_out, workspace,
+                  stream=None) -> None:
+    _check(_lib.mrem_rem_step(ctx, T, N, K, _ptr(vec), _ptr(adam_m), _ptr(adam_v), step_index, lr, _ptr(w_fp), _ptr(a_fp), _ptr(a_q),
+                              _ptr(loss_out), _ptr(y_fp), _ptr(y_q), _ptr(grads_out), _ptr(workspace),
+                              workspace.numel() * workspace.element_size(), _stream(stream)), ctx)
 
 
 def mrem_mix_inputs(ctx, x_fp, x_q, lam, out, n, stream=None) -> None:

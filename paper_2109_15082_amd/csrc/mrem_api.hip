@@ -4,6 +4,7 @@
 #include "../../include/mrem.h"
 #include "mrem_kernels.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -958,6 +959,98 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
   student_backward(r, params, x_in, per_layer_fp, per_layer_q, grads, loss_out, up);
   update_vectors(r, up, grads);
   return finish(ctx, "mrem_module_step");
+}
+
+// ------------------------------------------------------------------------------
+// REM: the reconstruction step of ONE matrix product (Section 3.2, Eq. 2)
+// ------------------------------------------------------------------------------
+namespace {
+struct RemPlan {
+  size_t wt, wcodes, what, zcorr, xcodes, dy, dxh, partials, grads, total;
+  int64_t n_vec;  // length of the flat vector [w | s_w | s_a, padded]
+};
+RemPlan rem_plan(int dt, int64_t T, int64_t N, int64_t K) {
+  RemPlan p;
+  Bump b;
+  const size_t es = dt_size(dt);
+  p.n_vec = ((N * K + N + 1 + 3) / 4) * 4;
+  p.wt = b.take((size_t)N * K * es); p.wcodes = b.take((size_t)N * K * es); p.what = b.take((size_t)N * K * es);
+  p.zcorr = b.take((size_t)N * 4);
+  p.xcodes = b.take((size_t)T * K * es); p.dy = b.take((size_t)T * N * es); p.dxh = b.take((size_t)T * K * es);
+  p.partials = b.take(2 * 2048 * 4);
+  p.grads = b.take((size_t)p.n_vec * 4);
+  p.total = b.off;
+  return p;
+}
+}  // namespace
+
+extern "C" int64_t mrem_rem_vector_count(int64_t N, int64_t K) { return (N < 1 || K < 1) ? -1 : ((N * K + N + 1 + 3) / 4) * 4; }
+extern "C" size_t mrem_rem_workspace_bytes(const mrem_ctx* ctx, int64_t T, int64_t N, int64_t K) {
+  if (!ctx || T < 1 || N < 1 || K < 1) return 0;
+  return rem_plan(ctx->dt, T, N, K).total;
+}
+
+extern "C" mrem_status mrem_rem_step(mrem_ctx* ctx, int64_t T, int64_t N, int64_t K, float* vec, float* adam_m, float* adam_v,
+                                     int64_t step_index, float lr, const float* w_fp, const void* a_fp, const void* a_q, float* loss_out,
+                                     void* y_fp, void* y_q, float* grads_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const char* who = "mrem_rem_step";
+  if (!ctx) return fail(nullptr, MREM_EINVAL, std::string(who) + ": null context");
+  if (T < 1 || N < 1 || K < 1 || T % 8 || N % 8 || K % 8 || T * std::max(N, K) > 0x7fffffff || N * K > 0x7fffffff)
+    return fail(ctx, MREM_ESHAPE, std::string(who) + ": T, N, K must be positive multiples of 8 (products below 2^31)");
+  if (ctx->cfg.w_bits == 0 || ctx->cfg.a_bits == 0) return fail(ctx, MREM_EINVAL, std::string(who) + ": both quantizer families must be on");
+  if (step_index < 1) return fail(ctx, MREM_EINVAL, std::string(who) + ": step_index is 1-based");
+  REQUIRE_PTR(vec, who); REQUIRE_PTR(adam_m, who); REQUIRE_PTR(adam_v, who); REQUIRE_PTR(w_fp, who); REQUIRE_PTR(a_fp, who);
+  REQUIRE_PTR(a_q, who); REQUIRE_PTR(loss_out, who); REQUIRE_PTR(y_fp, who); REQUIRE_PTR(y_q, who); REQUIRE_PTR(workspace, who);
+  if (grads_out && !aligned16(grads_out)) return fail(ctx, MREM_EINVAL, std::string(who) + ": grads_out misaligned");
+  const RemPlan p = rem_plan(ctx->dt, T, N, K);
+  if (workspace_bytes < p.total) return fail(ctx, MREM_EWORKSPACE, std::string(who) + ": workspace too small");
+  const int dt = ctx->dt;
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  float* w = vec;
+  float* sw = vec + N * K;
+  float* sa = vec + N * K + N;
+  float* grads = grads_out ? grads_out : reinterpret_cast<float*>(ws + p.grads);
+  float* parts = reinterpret_cast<float*>(ws + p.partials);
+  GemmProfile* prof = &ctx->prof;
+  // full-precision product  y = a W^T  on the original weights
+  convert_f32(dt, w_fp, ws + p.wt, N * K, st);
+  gemm_nt(dt, a_fp, (int)K, ws + p.wt, (int)K, y_fp, (int)N, (int)T, (int)N, (int)K, Epilogue(), st, prof);
+  // quantized product  y^ = Q(a) Q(w)^T: codes of both operands, the two steps in the epilogue
+  WeightJob wj;
+  wj.w = w; wj.sw = sw; wj.codes = ws + p.wcodes; wj.what = ws + p.what; wj.zcorr = reinterpret_cast<float*>(ws + p.zcorr); wj.codes8 = nullptr;
+  wj.N = (int)N; wj.K = (int)K;
+  weight_prepare(dt, &wj, 1, ctx->cfg.w_bits, st);
+  QArg qa;
+  qa.on = 1; qa.s = sa; qa.qp = (float)((1 << (ctx->cfg.a_bits - 1)) - 1); qa.qn = -qa.qp;
+  act_quantize(dt, a_q, ws + p.xcodes, T * K, qa, st);
+  Epilogue e;
+  e.alpha = sa; e.col_scale = sw;
+  gemm_nt(dt, ws + p.xcodes, (int)K, ws + p.wcodes, (int)K, y_q, (int)N, (int)T, (int)N, (int)K, e, st, prof);
+  // Eq. 2 and its gradient with respect to y^
+  const float scale = ctx->cfg.loss_mean ? 1.0f / (float)((double)T * (double)N) : 1.0f;
+  const int nl = mse_grad(dt, y_q, y_fp, ws + p.dy, T * N, scale, parts, st);
+  // straight-through backward: d w^ = dy^T a^ (the update kernel applies the mask and forms ds_w), d a^ = dy W^ for ds_a
+  Epilogue ew;
+  ew.alpha = sa; ew.out_f32 = 1;
+  gemm(dt, 1, 1, ws + p.dy, (int)N, ws + p.xcodes, (int)K, grads, (int)K, (int)N, (int)K, (int)T, ew, st, prof);
+  gemm(dt, 0, 1, ws + p.dy, (int)N, ws + p.what, (int)K, ws + p.dxh, (int)K, (int)T, (int)K, (int)N, Epilogue(), st, prof);
+  const int ns = quant_bwd_reduce(dt, ws + p.dxh, a_q, T * K, qa, parts + 2048, st);
+  ReduceJob jobs[2];
+  jobs[0].partials = parts; jobs[0].nparts = nl; jobs[0].width = 1; jobs[0].begin = 0; jobs[0].len = 1; jobs[0].out = loss_out; jobs[0].scale = scale;
+  jobs[1].partials = parts + 2048; jobs[1].nparts = ns; jobs[1].width = 1; jobs[1].begin = 0; jobs[1].len = 1; jobs[1].out = grads + N * K + N;
+  reduce_jobs(jobs, 2, st);
+  // AdamW on w (decay) and s_w, then on s_a (no decay, floor)
+  const AdamArg a = adam_arg(ctx, step_index, lr);
+  AdamJob aj;
+  aj.w = w; aj.sw = sw; aj.g_w = grads; aj.g_sw = grads + N * K; aj.m_w = adam_m; aj.v_w = adam_v; aj.m_sw = adam_m + N * K; aj.v_sw = adam_v + N * K;
+  aj.z_in = nullptr; aj.db = nullptr; aj.N = (int)N; aj.K = (int)K;
+  adam_matrix(&aj, 1, ctx->cfg.w_bits, a, grads_out != nullptr, ctx->cfg.per_channel ? 0 : 1, st);
+  AdamArg nodecay = a;
+  nodecay.wd = 0.f;
+  const VecJob vj{N * K + N, 1, 1};
+  adam_vector(vec, grads, adam_m, adam_v, &vj, 1, nodecay, st);
+  return finish(ctx, who);
 }
 
 extern "C" mrem_status mrem_mix_inputs(mrem_ctx* ctx, const void* x_fp, const void* x_q, float lambda, void* out, int64_t n,

@@ -769,6 +769,34 @@ void zero_regions(const FillRegion* regions, int count, hipStream_t st) {
   }
 }
 
+// Squared distance of two stored tensors and its gradient (the reconstruction objective of a single matrix
+// product, Section 3.2, Eq. 2): dy = 2 * scale * (yq - yfp), partials[block] = sum (yq - yfp)^2
+template <class T>
+__global__ void mse_grad_k(const T* __restrict__ yq, const T* __restrict__ yfp, T* __restrict__ dy, int64_t nchunks, float scale,
+                           float* __restrict__ partials) {
+  __shared__ float red[17];
+  float acc = 0.f;
+  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
+    float a[8], b[8];
+    load8(yq + c * 8, a);
+    load8(yfp + c * 8, b);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float d = a[j] - b[j];
+      acc += d * d;
+      a[j] = 2.0f * d * scale;
+    }
+    store8(dy + c * 8, a);
+  }
+  acc = block_sum(acc, red);
+  if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+}
+int mse_grad(int dt, const void* yq, const void* yfp, void* dy, int64_t n, float scale, float* partials, hipStream_t st) {
+  const int g = ew_grid(n);
+  MREM_DISPATCH(dt, MREM_LAUNCH(mse_grad_k<T>, dim3(g), dim3(256), 0, st, (const T*)yq, (const T*)yfp, (T*)dy, n / 8, scale, partials));
+  return g;
+}
+
 // Eq. 4: out = wa * a + wb * b
 template <class T>
 __global__ void axpby_k(const T* __restrict__ a, const T* __restrict__ b, float wa, float wb, T* __restrict__ out, int64_t n) {

@@ -170,6 +170,8 @@ void zero_regions(const FillRegion* regions, int count, hipStream_t st);
 // k-slices, 1 if it is written
 int gemm_f32_k_slices(int dt, int M, int N, int K);
 void axpby(int dt, const void* a, const void* b, float wa, float wb, void* out, int64_t n, hipStream_t st);
+// dy = 2 * scale * (yq - yfp) over n values (multiple of 8); partials[returned count]: sums of (yq - yfp)^2
+int mse_grad(int dt, const void* yq, const void* yfp, void* dy, int64_t n, float scale, float* partials, hipStream_t st);
 
 // ---- attention -----------------------------------------------------------------
 struct AttnQ {

@@ -829,3 +829,65 @@ def test_non_finite_loss_sets_the_flag(B):
     torch.cuda.synchronize()
     assert flag.item() == 0
     mod.close()
+
+
+# --------------------------------------------------------------------------------
+# REM: reconstruction of a single matrix product (Section 3.2, Eq. 2)
+# --------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dt,T,N,K,w_bits,per_channel", [("f32", 40, 24, 72, 4, 1), ("f32", 64, 32, 64, 2, 0), ("bf16", 256, 384, 128, 4, 1),
+                                                         ("bf16", 136, 72, 200, 4, 1)])
+def test_rem_step_matches_oracle(B, dt, T, N, K, w_bits, per_channel):
+    """One step of Eq. 2 on one product (ragged and tile-aligned shapes, per-channel and per-matrix steps): both
+    outputs, the loss, the gradients of w, s_w and s_a, and the updated variables with their moments, two steps."""
+    torch = _torch()
+    rng = np.random.default_rng(T + N + K)
+    td = torch.float32 if dt == "f32" else torch.bfloat16
+    tol = 1e-3 if dt == "f32" else 2e-2          # fp32 without a tie margin (as mid_f32)
+    a = synth.round_to_dtype(rng.standard_normal((T, K)).astype(np.float32), dt)
+    a_q = synth.round_to_dtype((a + 0.05 * rng.standard_normal((T, K))).astype(np.float32), dt)
+    w0 = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    cfg = O.Config(n_layers=1, hidden=8, n_heads=1, ffn=8, w_bits=w_bits, a_bits=8, act_round=dt, per_channel=bool(per_channel))
+    p = {"w": w0.astype(np.float64), "s_w": O.weight_step_init(w0, w_bits, bool(per_channel)) * 0.8,
+         "s_a": np.array([np.float64(np.float32(np.abs(a_q).max() / 127 * 0.9))])}
+    p["s_w"] = p["s_w"].astype(np.float32).astype(np.float64)
+    m = {k: np.zeros_like(x) for k, x in p.items()}
+    v = {k: np.zeros_like(x) for k, x in p.items()}
+    w_teacher = synth.round_to_dtype(w0, dt).astype(np.float64)           # the library stores the frozen weights in the activation type
+    ctx = B.mrem_create(n_layers=1, hidden=64, n_heads=2, ffn=128, max_batch=1, max_seq=8, act_dtype=B.MREM_FP32 if dt == "f32" else B.MREM_BF16,
+                        w_bits=w_bits, a_bits=8, per_channel=per_channel)
+    n_vec = B.mrem_rem_vector_count(N, K)
+    flat = np.zeros(n_vec, dtype=np.float32)
+    flat[:N * K] = w0.reshape(-1); flat[N * K:N * K + N] = p["s_w"]; flat[N * K + N] = p["s_a"][0]
+    vec = torch.from_numpy(flat).cuda()
+    dm, dv, dg = torch.zeros_like(vec), torch.zeros_like(vec), torch.zeros_like(vec)
+    ws = torch.empty(B.mrem_rem_workspace_bytes(ctx, T, N, K), dtype=torch.uint8, device="cuda")
+    da, daq = (torch.from_numpy(t).cuda().to(td).contiguous() for t in (a, a_q))
+    dw0 = torch.from_numpy(w0).cuda()
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    y_fp, y_q = torch.empty((T, N), dtype=td, device="cuda"), torch.empty((T, N), dtype=td, device="cuda")
+    for t in (1, 2):
+        ref_loss, ref_y, ref_yh, g = O.rem_step(a.astype(np.float64), a_q.astype(np.float64), w_teacher, p, m, v, t, 1e-3, cfg)
+        B.mrem_rem_step(ctx, T, N, K, vec, dm, dv, t, 1e-3, dw0, da, daq, loss, y_fp, y_q, dg, ws)
+        torch.cuda.synchronize()
+        assert Hh.rel_err(y_fp.float().cpu().numpy(), ref_y) <= tol and Hh.elem_err(y_fp.float().cpu().numpy(), ref_y) <= tol
+        assert Hh.rel_err(y_q.float().cpu().numpy(), ref_yh) <= tol and Hh.elem_err(y_q.float().cpu().numpy(), ref_yh) <= tol
+        assert abs(loss.item() / ref_loss - 1) <= tol, (loss.item(), ref_loss)
+        got = dg.cpu().numpy().astype(np.float64)
+        gw, gsw, gsa = got[:N * K].reshape(N, K), got[N * K:N * K + N], got[N * K + N]
+        gtol = tol * (2 if t == 2 else 1)        # the second step starts from parameters that differ at the tolerance
+        assert Hh.rel_err(gw, g["w"]) <= gtol, (t, Hh.rel_err(gw, g["w"]))
+        if t == 1:   # element-wise at the first step only: afterwards the two weight sets differ by up to twice the rate (0.3 of a
+            #          weight step here), so a weight next to its clip bound can carry the mask on one side and not on the other
+            assert Hh.elem_err(gw, g["w"]) <= gtol, Hh.elem_err(gw, g["w"])
+        assert Hh.rel_err(gsw, g["s_w"]) <= gtol, (t, Hh.rel_err(gsw, g["s_w"]))
+        assert abs(gsa - g["s_a"]) <= gtol * max(abs(g["s_a"]), 1e-3 * np.abs(g["s_w"]).max()), (t, gsa, g["s_a"])
+        cur = vec.cpu().numpy().astype(np.float64)
+        assert Hh.rel_err(cur[:N * K].reshape(N, K), p["w"]) <= tol
+        assert Hh.rel_err(cur[N * K:N * K + N], p["s_w"]) <= tol + 4 * gtol * 2e-3 / float(np.sqrt(np.mean(p["s_w"] ** 2)))
+        assert abs(cur[N * K + N] - p["s_a"][0]) <= 2.1e-3 * t
+        mom = dm.cpu().numpy().astype(np.float64)
+        assert Hh.rel_err(mom[:N * K].reshape(N, K), m["w"]) <= gtol
+        if not per_channel:
+            assert np.all(cur[N * K:N * K + N] == cur[N * K])           # the one step stays one step
+    B.mrem_destroy(ctx)
