@@ -46,15 +46,19 @@ PIPE_F32 = synth.Workload("pipe_f32", 1, 64, 2, 128, 24, 2, act_dtype="f32", seq
 PIPE_BF16 = synth.Workload("pipe_bf16", 2, 128, 2, 256, 64, 4, act_dtype="bf16")
 
 
-@pytest.mark.parametrize("wl,tol_early,tol", [(PIPE_F32, 1e-2, 5e-2), (PIPE_BF16, 5e-2, 1.5e-1)], ids=["f32", "bf16"])
-def test_parallel_schedule_matches_oracle(B, wl, tol_early, tol):
+@pytest.mark.parametrize("wl,tol_first,tol_early,tol", [(PIPE_F32, 1e-3, 5e-3, 2e-2), (PIPE_BF16, 2e-2, 4e-2, 6e-2)], ids=["f32", "bf16"])
+def test_parallel_schedule_matches_oracle(B, wl, tol_first, tol_early, tol):
     """Three modules, queue depth 2, 6 steps with annealed teacher forcing over the first 4:
     per-step, per-module losses against the oracle run on the same sampled queue entries.
     Differences grow with the step count (measured in fp32: 1e-7, 9e-4, ..., 1e-2 at step 5):
     the first AdamW updates move every parameter by about the learning rate in the direction of
     its gradient's sign, so rounding-level differences in near-zero gradients become
     learning-rate-sized differences in parameters.  The first module, whose inputs are the data,
-    stays within 3e-4 throughout.  That the device schedule reads exactly the stated entries is
+    stays within the mode's tolerance throughout (1e-3 in fp32 without a tie margin, 2e-2 in bf16: measured 3e-4 and
+    3e-3); the later modules within 5e-3 / 4e-2 over the first three steps and 2e-2 / 6e-2 afterwards (measured
+    1.0e-2 and 3.7e-2 at most).  The oracle's own second run with fp32 products drifts less than the device does
+    (1e-4 and 8e-3): the device also stores gradients in the activation type and runs AdamW in fp32, so that run
+    is reported here but is not the bound.  That the device schedule reads exactly the stated entries is
     the subject of test_parallel_schedule_equals_list_based_fifo (bit-exact), that it is race-free
     the subject of the determinism test."""
     from paper_2109_15082_amd.pipeline import ModulePipeline
@@ -68,10 +72,17 @@ def test_parallel_schedule_matches_oracle(B, wl, tol_early, tol):
     got = pipe.run_parallel(data, dl, slots, t0, T, 1e-4, tf).numpy()
     want = np.array(ref.loss)
     assert got.shape == want.shape == (T, N)
+    import dataclasses
+    alt_cases = copy.deepcopy(cases)
+    for c in alt_cases:
+        c.cfg = dataclasses.replace(c.cfg, accumulate="f32")
+    alt = np.array(P.run_parallel(_states(alt_cases), data64, lens, slots, t0, T, 1e-4, tf, wl.batch, wl.seq).loss)
+    drift = np.maximum.accumulate(np.abs(alt / want - 1).max(axis=1))      # worst module, up to that step
     err = np.abs(got - want) / np.maximum(np.abs(want), 1e-30)
+    print("relative loss errors per step and module:", err, "oracle's own drift so far:", drift)
+    assert (err[:, 0] <= tol_first).all() and (err[0] <= tol_first).all(), (err, got, want)
     assert (err[:3] <= tol_early).all(), (err, got, want)
     assert (err <= tol).all(), (err, got, want)
-    assert (err[:, 0] <= (1e-3 if wl.act_dtype == "f32" else tol_early)).all(), (err, got, want)
     for m in mods:
         m.close()
 
