@@ -179,14 +179,20 @@ bool gemm_i8_ok(const void* A, int lda, const void* B, int ldb, int M, int N, in
 //   256 x 256 (8 wavefronts of 64 x 128, two stages of 128-byte rows, one block per compute unit) when the
 //     output has at least 192 such tiles -- the query/key/value and first feed-forward projections and
 //     the input gradient of the second one at 4096 tokens: half the operand bytes per flop of the small tile;
-//   128 x 128 (4 wavefronts of 64 x 64, four stages of 64-byte rows, two blocks per compute unit) otherwise:
-//     the depth of four stages hides the latency of operands that the previous kernel has just written or
-//     that come from HBM, and the second block fills the barrier and epilogue gaps of the first.
+//   128 x 128 with 8 wavefronts (two groups of 4; each group multiplies every other 16-deep k-substep of a
+//     stage and the groups' partial sums meet in LDS before the epilogue), four stages of 128-byte rows, one
+//     block per compute unit, when the output has at most 256 such tiles -- one tile per compute unit, so the
+//     second wavefront on each SIMD is what overlaps fragment reads, barriers and MFMA issue;
+//   128 x 128 with 4 wavefronts of 64 x 64, four stages of 64-byte rows, two blocks per compute unit, otherwise:
+//     the second block fills the barrier and epilogue gaps of the first.
+//   Four stages hide the latency of operands that the previous kernel has just written or that come from HBM.
 template <bool AT, bool BT, class TO, bool I8>
 static void launch_dl_tiles(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
                             hipStream_t st, int splits) {
   if (splits == 1 && M % 256 == 0 && N % 256 == 0 && (M / 256) * (N / 256) >= 192)
     return launch_dl<256, 256, 4, 2, AT, BT, 2, 128, TO, I8, 1>(A, lda, B, ldb, C, ldc, M, N, K, e, st);
+  if ((M / 128) * (N / 128) <= 256)
+    return launch_dl<128, 128, 2, 2, AT, BT, 4, 128, TO, I8, 1, 2>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
   return launch_dl<128, 128, 2, 2, AT, BT, 4, 64, TO, I8, 2>(A, lda, B, ldb, C, ldc, M, N, K, e, st, splits);
 }
 static void gemm_i8_launch(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,

@@ -74,13 +74,15 @@ __device__ __forceinline__ i32x2_t lds_read_tr16_b64(int addr) {
   return v;
 }
 
-// One operand (ROWS tile rows) of the product.  T fragments of 32 rows each per wavefront.
-template <bool TR, int ROWS, int RB, int T>
+// One operand (ROWS tile rows) of the product.  T fragments of 32 rows each per wavefront.  KG: wavefront groups
+// that share a stage's k-substeps (group g multiplies substeps g, g + KG, ...).
+template <bool TR, int ROWS, int RB, int T, int KG = 1>
 struct DlOperand {
   static constexpr int KK = RB / 32;               // k-substeps (one MFMA deep) per stage
+  static constexpr int KKW = KK / KG;              // ... of them per wavefront
   static constexpr int BYTES = ROWS * RB;          // per stage
   static constexpr int LOADS = BYTES / 1024;       // direct loads (1 KiB each) per stage
-  static constexpr int NADDR = TR ? T : KK;        // per-lane LDS addresses kept in registers (per fragment / per k-substep)
+  static constexpr int NADDR = TR ? T : KKW;       // per-lane LDS addresses kept in registers (per fragment / per k-substep)
   // byte offset, from the operand's first element of a k-step (row tile0, column k0), of the 16
   // bytes that belong at byte position p of the stage; ld in elements of 2 bytes
   static __device__ __forceinline__ size_t src_offset(int p, int ld) {
@@ -94,7 +96,8 @@ struct DlOperand {
     return ((size_t)r * ld + c * 8) * 2;
   }
   // per-lane byte addresses inside a stage for the fragments of the wavefront whose rows start at row0
-  static __device__ __forceinline__ void lane_addr(int (&a)[NADDR], int row0, int lane) {
+  // (kg: this wavefront's group; its j-th substep is kg + KG j)
+  static __device__ __forceinline__ void lane_addr(int (&a)[NADDR], int row0, int lane, int kg) {
     if constexpr (TR) {
       // the swizzle term is not additive in the fragment index: one address per fragment
       const int g = lane >> 4, s = lane & 15;
@@ -103,12 +106,12 @@ struct DlOperand {
       for (int i = 0; i < T; ++i) {
         const int col = row0 + 32 * i + 16 * (g & 1) + 4 * (s & 3);
         const int slot = (col >> 3) ^ ((krow & 3) << 2) ^ (((krow >> 3) & 1) << 1);
-        a[i] = krow * (2 * ROWS) + slot * 16 + (col & 7) * 2;
+        a[i] = (krow + 16 * kg) * (2 * ROWS) + slot * 16 + (col & 7) * 2;   // 16 k-rows per substep: the swizzle term is unchanged
       }
     } else {
       const int r = row0 + (lane & 31), x = RB == 128 ? (r >> 1) & 7 : (r >> 2) & 3;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) a[kk] = r * RB + (((2 * kk + (lane >> 5)) ^ x) << 4);
+      for (int j = 0; j < KKW; ++j) a[j] = r * RB + (((2 * (kg + KG * j) + (lane >> 5)) ^ x) << 4);
     }
   }
   // A fragment in registers: four VGPRs (one 16-byte read), or two pairs (two transposing 8-byte reads;
@@ -127,13 +130,13 @@ struct DlOperand {
       else asm volatile("" : "+v"(f[i]));
     }
   }
-  // issue the reads of k-substep KKI of the stage at byte address `stage` (fragment i: rows + 32 i)
+  // issue the reads of this wavefront's KKI-th k-substep of the stage at byte address `stage` (fragment i: rows + 32 i)
   template <int KKI>
   static __device__ __forceinline__ void read(frag_t (&f)[T], const int (&a)[NADDR], int stage) {
     if constexpr (TR) {
-      // k-rows 16 KKI (+ 4 for the second half) further down: multiples of 4, the swizzle term is unchanged
+      // k-rows 16 KG KKI (+ 4 for the second half) further down: multiples of 4, the swizzle term is unchanged
       static_for<T>([&](auto i) {
-        constexpr int off = KKI * 16 * (2 * ROWS);
+        constexpr int off = KG * KKI * 16 * (2 * ROWS);
         const int addr = a[i.value] + stage;
         f[i.value].lo = lds_read_tr16_b64<off>(addr);
         f[i.value].hi = lds_read_tr16_b64<off + 4 * (2 * ROWS)>(addr);
@@ -154,18 +157,19 @@ __device__ __forceinline__ void wait_frags(typename OpA::frag_t (&a)[TA], typena
   OpB::tie(b);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, int STAGES, int RB, class TO, bool I8, int MINB>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void gemm_dl_k(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B,
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, int STAGES, int RB, class TO, bool I8, int MINB, int KG>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG, MINB) void gemm_dl_k(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B,
                                                                          int ldb, TO* __restrict__ C, int ldc, int M, int N, int K, Epilogue e,
                                                                          int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_dl[];
-  constexpr int NW = WAVES_M * WAVES_N;
+  constexpr int NW = WAVES_M * WAVES_N * KG;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int MT = WM / 32, NT = WN / 32;
   constexpr int BK = RB / 2;  // in 2-byte elements
-  typedef DlOperand<AT, BM, RB, MT> OpA;
-  typedef DlOperand<BT, BN, RB, NT> OpB;
-  constexpr int KK = RB / 32;
+  typedef DlOperand<AT, BM, RB, MT, KG> OpA;
+  typedef DlOperand<BT, BN, RB, NT, KG> OpB;
+  constexpr int KK = RB / 32 / KG;  // k-substeps of a stage that this wavefront multiplies
+  static_assert((RB / 32) % KG == 0 && MT % KG == 0, "k-substeps and tile rows divide over the wavefront groups");
   constexpr int STAGE_BYTES = OpA::BYTES + OpB::BYTES;
   constexpr int LOADS = OpA::LOADS + OpB::LOADS;
   static_assert(LOADS % NW == 0, "loads of a stage divide evenly over the wavefronts");
@@ -191,7 +195,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void gemm_dl_k(const 
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int kg = wave / (WAVES_M * WAVES_N), wpos = wave % (WAVES_M * WAVES_N);  // k-group, position in the tile
+  const int wm = wpos / WAVES_N, wn = wpos % WAVES_N;
 
   const int KT = K / BK / (int)gridDim.y;  // gridDim.y > 1: k-slices, added into a zeroed fp32 C
   const int kbase = (int)blockIdx.y * KT * BK;
@@ -230,8 +235,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void gemm_dl_k(const 
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
   int a_addr[OpA::NADDR], b_addr[OpB::NADDR];
-  OpA::lane_addr(a_addr, wm * WM, lane);
-  OpB::lane_addr(b_addr, wn * WN, lane);
+  OpA::lane_addr(a_addr, wm * WM, lane, kg);
+  OpB::lane_addr(b_addr, wn * WN, lane, kg);
   const int lds0 = (int)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_dl;
 
   auto mfmas = [&](const typename OpA::frag_t (&af)[MT], const typename OpB::frag_t (&bf)[NT]) {
@@ -286,6 +291,36 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void gemm_dl_k(const 
     slot = next_slot;
   }
 
+  if constexpr (KG > 1) {
+    // The KG wavefronts at one tile position hold partial sums over disjoint k-substeps.  Each finalises the MFMA
+    // tile rows i with i % KG == kg: it leaves its other tile rows in LDS (the stages are free now) and adds what
+    // its partners left for its own rows, in group order (fixed, so results do not depend on timing).
+    static_assert(KG == 2, "two groups");
+    typedef typename std::conditional<I8, int, float>::type acc_e;
+    acc_e* xch = reinterpret_cast<acc_e*>(smem_dl);
+    __syncthreads();  // every wavefront is done reading operand stages
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      if (i % KG == kg) continue;
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) xch[(((wpos * MT + i) * NT + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      if (i % KG != kg) continue;
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const acc_e other = xch[(((wpos * MT + i) * NT + j) * 16 + r) * 64 + lane];
+          acc[i][j][r] = kg == 0 ? acc[i][j][r] + other : other + acc[i][j][r];  // always group 0's part first
+        }
+    }
+  }
+
   // epilogue: out = acc * (alpha * col_scale[n]) + beta * (col_vec[n] + row_vec[m]) + bias[n]
   const float alpha = e.alpha ? *e.alpha : 1.f;
   const float beta = (e.beta ? *e.beta : 0.f) + e.beta_alpha * alpha;
@@ -299,6 +334,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void gemm_dl_k(const 
       if (e.beta && e.col_vec && lead) cb += beta * e.col_vec[n];
 #pragma unroll
       for (int i = 0; i < MT; ++i) {
+        if (KG > 1 && i % KG != kg) continue;  // a partner wavefront writes this tile row
         const int mb = m0 + wm * WM + i * 32 + 4 * (lane >> 5);
         TO* __restrict__ out = C + (size_t)mb * ldc + n;
 #pragma unroll
@@ -333,27 +369,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void gemm_dl_k(const 
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, int STAGES, int RB, class TO, bool I8 = false, int MINB = 1>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool AT, bool BT, int STAGES, int RB, class TO, bool I8 = false, int MINB = 1, int KG = 1>
 static void launch_dl(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, const Epilogue& e,
                       hipStream_t st, int k_splits = 1) {
-  constexpr int NTHREADS = 64 * WAVES_M * WAVES_N;
+  constexpr int NTHREADS = 64 * WAVES_M * WAVES_N * KG;
   constexpr size_t lds = (size_t)STAGES * (BM + BN) * RB;
+  static_assert(KG == 1 || (size_t)BM * BN * 4 <= lds, "the partial sums of a k-group fit the stages");
   static std::atomic<int> configured_dev{-1};
   int dev = -1;
   (void)hipGetDevice(&dev);
   if (dev != configured_dev.load()) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dl_k<BM, BN, WAVES_M, WAVES_N, AT, BT, STAGES, RB, TO, I8, MINB>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dl_k<BM, BN, WAVES_M, WAVES_N, AT, BT, STAGES, RB, TO, I8, MINB, KG>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     configured_dev.store(dev);
   }
   const int tiles_m = M / BM, tiles_n = N / BN;
   if (tl_launch_events.e0) {
-    hipExtLaunchKernelGGL((gemm_dl_k<BM, BN, WAVES_M, WAVES_N, AT, BT, STAGES, RB, TO, I8, MINB>), dim3(tiles_m * tiles_n, k_splits),
+    hipExtLaunchKernelGGL((gemm_dl_k<BM, BN, WAVES_M, WAVES_N, AT, BT, STAGES, RB, TO, I8, MINB, KG>), dim3(tiles_m * tiles_n, k_splits),
                           dim3(NTHREADS), lds, st, tl_launch_events.e0, tl_launch_events.e1, 0, (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (TO*)C, ldc, M, N,
                           K, e, tiles_m, tiles_n);
     return;
   }
-  hipLaunchKernelGGL((gemm_dl_k<BM, BN, WAVES_M, WAVES_N, AT, BT, STAGES, RB, TO, I8, MINB>), dim3(tiles_m * tiles_n, k_splits), dim3(NTHREADS),
+  hipLaunchKernelGGL((gemm_dl_k<BM, BN, WAVES_M, WAVES_N, AT, BT, STAGES, RB, TO, I8, MINB, KG>), dim3(tiles_m * tiles_n, k_splits), dim3(NTHREADS),
                      lds, st, (const bf16_t*)A, lda, (const bf16_t*)B, ldb, (TO*)C, ldc, M, N, K, e, tiles_m, tiles_n);
 }
 
