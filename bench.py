@@ -21,13 +21,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 MFMA_INT8_PEAK_TOPS = 5000.0
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "module_step_bert_large_6l_hbm_traffic.md")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "module_step_bert_large_6l_hbm_traffic.txt")
 
 
 def measured_gemm_traffic(workload):
     """HBM bytes per matrix-product launch (read + written) as the committed rocprofv3 --pmc summary states them
     (FETCH_SIZE and WRITE_SIZE runs, each scaled by what the counter reads for a 256 MiB device copy): the line
-    'traffic_bytes_per_launch: <workload> <bytes>' of profiles/module_step_bert_large_6l_hbm_traffic.md.  Counters
+    'traffic_bytes_per_launch: <workload> <bytes>' of profiles/module_step_bert_large_6l_hbm_traffic.txt.  Counters
     cannot be read from inside this process, so the figure comes from that file or is null."""
     try:
         for line in open(TRAFFIC_FILE):
@@ -169,7 +169,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "gemm_dl_k on bf16 operands (teacher forward, input and weight gradients)",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_gemm_traffic(wl.name),
-                     "traffic_unit": "bytes/launch", "traffic_source": "profiles/module_step_bert_large_6l_hbm_traffic.md (rocprofv3 --pmc)",
+                     "traffic_unit": "bytes/launch", "traffic_source": "profiles/module_step_bert_large_6l_hbm_traffic.txt (rocprofv3 --pmc)",
                      "hbm_kernels": hbm_kernels,
                      "launches_per_step": gemm_launches / args.steps,
                      "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
