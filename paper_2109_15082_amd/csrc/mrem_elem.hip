@@ -287,26 +287,40 @@ __global__ void quant_bwd_k(const T* __restrict__ dq, const T* __restrict__ a, T
   __shared__ float red[17];
   const QuantParam q = load_q(qa);
   float acc = 0.f;
-  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunks; c += (int64_t)gridDim.x * blockDim.x) {
-    float g[8], x[8];
-    load8(dq + c * 8, g);
-    if (q.on) {
-      load8(a + c * 8, x);
+  // two chunks per thread and round, both fetched before the first is used
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t c0 = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c0 < nchunks; c0 += 2 * stride) {
+    const int64_t c1 = c0 + stride;
+    const bool two = c1 < nchunks;
+    Raw8<T> graw[2], xraw[2];
+    graw[0].load(dq + c0 * 8);
+    if (q.on) xraw[0].load(a + c0 * 8);
+    if (two) {
+      graw[1].load(dq + c1 * 8);
+      if (q.on) xraw[1].load(a + c1 * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      if (i == 1 && !two) break;
+      float g[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const float v = q_ratio_t<T>(x[j], q);
-        const bool in = q_inside(v, q);
-        acc += g[j] * (q_code(v, q) - (in ? v : 0.f));
-        g[j] = in ? g[j] : 0.f;
+        g[j] = graw[i].get(j);
+        if (q.on) {
+          const float v = q_ratio_t<T>(xraw[i].get(j), q);
+          const bool in = q_inside(v, q);
+          acc += g[j] * (q_code(v, q) - (in ? v : 0.f));
+          g[j] = in ? g[j] : 0.f;
+        }
       }
+      if (dout) store8(dout + (i ? c1 : c0) * 8, g);
     }
-    if (dout) store8(dout + c * 8, g);
   }
   const float t = block_sum(acc, red);
   if (threadIdx.x == 0) partials[blockIdx.x] = t;
 }
 int quant_bwd(int dt, const void* d_q, const void* a, void* d_out, int64_t n, QArg q, float* partials, hipStream_t st) {
-  const int g = ew_grid(n);
+  const int g = ew_grid((n + 1) / 2);
   MREM_DISPATCH(dt, MREM_LAUNCH(quant_bwd_k<T>, dim3(g), dim3(256), 0, st, (const T*)d_q, (const T*)a, (T*)d_out,
                                        n / 8, q, partials));
   return g;
@@ -396,10 +410,11 @@ ColGrid gelu_quant_bwd(int dt, const void* dgh, const void* u, void* du, int T_,
 // ------------------------------------------------------------------------------
 // residual + LayerNorm: one wavefront per token row, 8-element chunks per lane
 // ------------------------------------------------------------------------------
-constexpr int kLnMaxChunks = 4;  // hidden <= 64 lanes * 8 * 4 = 2048
+// hidden <= 64 lanes * 8 values * 4 chunks = 2048 (checked when the context is created)
 
-template <class T>
-__global__ void ln_fwd_k(const T* __restrict__ x, const T* __restrict__ r, const float* __restrict__ gamma,
+// NCH: 8-element chunks per lane (hidden <= 512 * NCH)
+template <class T, int NCH>
+__global__ __launch_bounds__(256) void ln_fwd_k(const T* __restrict__ x, const T* __restrict__ r, const float* __restrict__ gamma,
                          const float* __restrict__ beta, T* __restrict__ y, T* __restrict__ ycodes, QArg qa,
                          float* __restrict__ mu_out, float* __restrict__ rstd_out, int T_, int H, float eps,
                          int8_t* __restrict__ ycodes8) {
@@ -408,23 +423,40 @@ __global__ void ln_fwd_k(const T* __restrict__ x, const T* __restrict__ r, const
   const int row = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
   if (row >= T_) return;
   const int nch = H / 8;
-  float v[kLnMaxChunks][8];
+  float v[NCH][8];
   float sum = 0.f;
+  Raw8<T> ra[NCH], rb[NCH];
+  Raw8<float> rg[NCH], rbeta[NCH];
+  // every load of the row goes out before the first value is used: the gain and shift vectors (cache hits) arrive
+  // under the two reductions instead of after them
 #pragma unroll
-  for (int i = 0; i < kLnMaxChunks; ++i) {
+  for (int i = 0; i < NCH; ++i) {
     const int c = lane + 64 * i;
     if (c < nch) {
-      float a[8], b[8];
-      load8(x + (size_t)row * H + c * 8, a);
-      load8(r + (size_t)row * H + c * 8, b);
+      ra[i].load(x + (size_t)row * H + c * 8);
+      rb[i].load(r + (size_t)row * H + c * 8);
+    }
+  }
 #pragma unroll
-      for (int j = 0; j < 8; ++j) { v[i][j] = a[j] + b[j]; sum += v[i][j]; }
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nch) {
+      rg[i].load(gamma + c * 8);
+      rbeta[i].load(beta + c * 8);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nch) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { v[i][j] = ra[i].get(j) + rb[i].get(j); sum += v[i][j]; }
     }
   }
   const float mean = wave_sum(sum) / (float)H;
   float sq = 0.f;
 #pragma unroll
-  for (int i = 0; i < kLnMaxChunks; ++i) {
+  for (int i = 0; i < NCH; ++i) {
     const int c = lane + 64 * i;
     if (c < nch) {
 #pragma unroll
@@ -435,14 +467,12 @@ __global__ void ln_fwd_k(const T* __restrict__ x, const T* __restrict__ r, const
   const float rstd = 1.0f / sqrtf(var + eps);
   if (lane == 0) { mu_out[row] = mean; rstd_out[row] = rstd; }
 #pragma unroll
-  for (int i = 0; i < kLnMaxChunks; ++i) {
+  for (int i = 0; i < NCH; ++i) {
     const int c = lane + 64 * i;
     if (c < nch) {
-      float g[8], b[8], o[8];
-      load8(gamma + c * 8, g);
-      load8(beta + c * 8, b);
+      float o[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) o[j] = (v[i][j] - mean) * rstd * g[j] + b[j];
+      for (int j = 0; j < 8; ++j) o[j] = (v[i][j] - mean) * rstd * rg[i].get(j) + rbeta[i].get(j);
       store8(y + (size_t)row * H + c * 8, o);
       if (ycodes) {
 #pragma unroll
@@ -458,8 +488,13 @@ __global__ void ln_fwd_k(const T* __restrict__ x, const T* __restrict__ r, const
 }
 void ln_fwd(int dt, const void* x, const void* r, const float* gamma, const float* beta, void* y, void* ycodes, QArg q,
             float* mu, float* rstd, int T_, int H, float eps, hipStream_t st, int8_t* ycodes8) {
-  MREM_DISPATCH(dt, MREM_LAUNCH(ln_fwd_k<T>, dim3((T_ + 3) / 4), dim3(256), 0, st, (const T*)x, (const T*)r, gamma, beta,
-                                       (T*)y, (T*)ycodes, q, mu, rstd, T_, H, eps, ycodes8));
+#define MREM_LN_FWD(NCH)                                                                                                      \
+  MREM_DISPATCH(dt, MREM_LAUNCH((ln_fwd_k<T, NCH>), dim3((T_ + 3) / 4), dim3(256), 0, st, (const T*)x, (const T*)r, gamma, beta, \
+                                (T*)y, (T*)ycodes, q, mu, rstd, T_, H, eps, ycodes8))
+  if (H <= 512) MREM_LN_FWD(1);
+  else if (H <= 1024) MREM_LN_FWD(2);
+  else MREM_LN_FWD(4);
+#undef MREM_LN_FWD
 }
 
 constexpr int kLnBwdWaves = 8;       // wavefronts per block
