@@ -552,7 +552,7 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       // in: layer output, the two LayerNorm inputs, the full-precision output (loss), above the top layer also the two
       // gradients from above; out: the gradient of the LayerNorm input
       timed(r, "ln_bwd_k", (double)T * H * es * ((top ? 4 : 6) + (in_loss ? 1 : 0)), [&] {
-        n = ln_bwd(c->dt, top ? nullptr : r.at(r.p.dr1), nullptr, top ? nullptr : r.at(r.p.dxh), fq, q_above, r.at(w.x1), r.at(w.y),
+        n = ln_bwd(c->dt, top ? nullptr : r.at(r.p.dr1), top ? nullptr : r.at(r.p.dxh), fq, q_above, r.at(w.x1), r.at(w.y),
                    r.at<float>(w.mu2), r.at<float>(w.rstd2), base + c->foff[MREM_F_LN2_G], r.at(r.p.dr2), parts, T, H, r.st,
                    in_loss ? ffp : nullptr, scale);
       });
@@ -587,7 +587,7 @@ void student_backward(const Run& r, const float* params, const void* x_q, const 
       before_overwrite(1);
       int n = 0;
       timed(r, "ln_bwd_k", (double)T * H * es * 6, [&] {
-        n = ln_bwd(c->dt, r.at(r.p.dr2), nullptr, r.at(r.p.dx1h), r.at(w.x1), make_q(c, params, l, 6), x, r.at(w.o),
+        n = ln_bwd(c->dt, r.at(r.p.dr2), r.at(r.p.dx1h), r.at(w.x1), make_q(c, params, l, 6), x, r.at(w.o),
                    r.at<float>(w.mu1), r.at<float>(w.rstd1), base + c->foff[MREM_F_LN1_G], r.at(r.p.dr1), parts, T, H, r.st);
       });
       const int wd = 3 * H + 2;

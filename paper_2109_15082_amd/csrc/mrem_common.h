@@ -48,10 +48,23 @@ __device__ __forceinline__ float q_code(float v, const QuantParam& q) { return r
 __device__ __forceinline__ bool q_inside(float v, const QuantParam& q) { return v >= q.qn && v <= q.qp; }
 
 // ---- reductions --------------------------------------------------------------
+// Sum over the 64 lanes with data-parallel-primitive moves (no trip through the LDS crossbar): four steps inside
+// each row of 16 lanes (neighbour, pair, mirrored half row, mirrored row) leave every lane with its row's sum; two
+// row broadcasts carry the sums of rows 0 and 2 into rows 1 and 3 and that of rows 0..1 into rows 2..3, so the last
+// lane holds the total, which is read back as a wavefront-uniform value.  Fixed order: deterministic.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_term(float v) {
+  // lanes of rows outside ROW_MASK receive 0
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-  return v;
+  v += dpp_term<0xB1, 0xF>(v);   // quad_perm [1,0,3,2]
+  v += dpp_term<0x4E, 0xF>(v);   // quad_perm [2,3,0,1]
+  v += dpp_term<0x141, 0xF>(v);  // row_half_mirror
+  v += dpp_term<0x140, 0xF>(v);  // row_mirror
+  v += dpp_term<0x142, 0xA>(v);  // row_bcast15 into rows 1 and 3
+  v += dpp_term<0x143, 0xC>(v);  // row_bcast31 into rows 2 and 3
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll

@@ -508,8 +508,11 @@ int ln_bwd_parts(int T_) { return (T_ + kLnBwdRows - 1) / kLnBwdRows; }
 // [3H + 2] (the last two values are the step-size gradient of the quantizer in front of the next layer
 // and the squared-error sum of this layer's term of Eq. 3).
 // NCH: 8-element chunks per lane (hidden <= 512 * NCH)
-template <class T, int NCH>
-__global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict__ d_a, const T* __restrict__ d_b, const T* __restrict__ d_q,
+// HAS_A, HAS_Q, HAS_L: which of the optional inputs exist (gradient from above d_a, gradient d_q through the
+// quantizer of a_q, full-precision output loss_ref for the layer's loss term): decided per instantiation, so the
+// per-element code has no tests on them.
+template <class T, int NCH, bool HAS_A, bool HAS_Q, bool HAS_L>
+__global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict__ d_a, const T* __restrict__ d_q,
                                                              const T* __restrict__ a_q, QArg qa, const T* __restrict__ x, const T* __restrict__ r,
                                                              const float* __restrict__ mu, const float* __restrict__ rstd_in,
                                                              const float* __restrict__ gamma, T* __restrict__ dr, float* __restrict__ partials,
@@ -546,11 +549,10 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict
         const int c = lane + 64 * i;
         if (live && c < nch) {
           const size_t off = (size_t)row * H + c * 8;
-          if (d_a) t_a[k][i].load(d_a + off);
-          if (loss_ref) t_b[k][i].load(loss_ref + off);
-          else if (d_b) t_b[k][i].load(d_b + off);
-          if (d_q) t_q[k][i].load(d_q + off);
-          if ((d_q && q.on) || loss_ref) t_v[k][i].load(a_q + off);
+          if constexpr (HAS_A) t_a[k][i].load(d_a + off);
+          if constexpr (HAS_L) t_b[k][i].load(loss_ref + off);
+          if constexpr (HAS_Q) t_q[k][i].load(d_q + off);
+          if ((HAS_Q && q.on) || HAS_L) t_v[k][i].load(a_q + off);
           t_x[k][i].load(x + off);
           t_r[k][i].load(r + off);
         }
@@ -568,16 +570,14 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             float d = 0.f;
-            if (d_a) d += t_a[k][i].get(j);
-            if (loss_ref) {
+            if constexpr (HAS_A) d += t_a[k][i].get(j);
+            if constexpr (HAS_L) {
               // Eq. 3 term of this layer: a_q holds the quantized module's output, loss_ref the full-precision one
               const float diff = t_v[k][i].get(j) - t_b[k][i].get(j);
               loss_acc += diff * diff;
               d += 2.0f * diff * loss_scale;
-            } else if (d_b) {
-              d += t_b[k][i].get(j);
             }
-            if (d_q) {
+            if constexpr (HAS_Q) {
               float t = t_q[k][i].get(j);
               if (q.on) {
                 const float v = q_ratio_t<T>(t_v[k][i].get(j), q);
@@ -670,21 +670,36 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_k(const T* __restrict
     out[3 * H + 1] = tl;
   }
 }
-int ln_bwd(int dt, const void* d_a, const void* d_b, const void* d_q, const void* a_q, QArg q, const void* x, const void* r,
+int ln_bwd(int dt, const void* d_a, const void* d_q, const void* a_q, QArg q, const void* x, const void* r,
            const float* mu, const float* rstd, const float* gamma, void* dr, float* partials, int T_, int H, hipStream_t st,
            const void* loss_ref, float loss_scale) {
   const int g = ln_bwd_parts(T_);
   const size_t lds = ((size_t)(kLnBwdWaves / 2) * 3 * H + 2 * kLnBwdWaves) * sizeof(float);
-#define MREM_LN_BWD(NCH)                                                                                                        \
-  MREM_DISPATCH(dt, if (lds > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ln_bwd_k<T, NCH>),                   \
-                                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);            \
-                    MREM_LAUNCH((ln_bwd_k<T, NCH>), dim3(g), dim3(64 * kLnBwdWaves), lds, st, (const T*)d_a, (const T*)d_b, \
-                                       (const T*)d_q, (const T*)a_q, q, (const T*)x, (const T*)r, mu, rstd, gamma, (T*)dr, partials, T_, H, \
+#define MREM_LN_BWD_V(NCH, A, Q, L)                                                                                                 \
+  MREM_DISPATCH(dt, if (lds > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ln_bwd_k<T, NCH, A, Q, L>),              \
+                                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                \
+                    MREM_LAUNCH((ln_bwd_k<T, NCH, A, Q, L>), dim3(g), dim3(64 * kLnBwdWaves), lds, st, (const T*)d_a, (const T*)d_q,    \
+                                       (const T*)a_q, q, (const T*)x, (const T*)r, mu, rstd, gamma, (T*)dr, partials, T_, H,              \
                                        (const T*)loss_ref, loss_scale))
+#define MREM_LN_BWD(NCH)                                                 \
+  do {                                                                   \
+    const int v = (d_a ? 1 : 0) | (d_q ? 2 : 0) | (loss_ref ? 4 : 0);    \
+    switch (v) {                                                         \
+      case 0: MREM_LN_BWD_V(NCH, false, false, false); break;            \
+      case 1: MREM_LN_BWD_V(NCH, true, false, false); break;             \
+      case 2: MREM_LN_BWD_V(NCH, false, true, false); break;             \
+      case 3: MREM_LN_BWD_V(NCH, true, true, false); break;              \
+      case 4: MREM_LN_BWD_V(NCH, false, false, true); break;             \
+      case 5: MREM_LN_BWD_V(NCH, true, false, true); break;              \
+      case 6: MREM_LN_BWD_V(NCH, false, true, true); break;              \
+      default: MREM_LN_BWD_V(NCH, true, true, true); break;              \
+    }                                                                    \
+  } while (0)
   if (H <= 512) MREM_LN_BWD(1);
   else if (H <= 1024) MREM_LN_BWD(2);
   else MREM_LN_BWD(4);
 #undef MREM_LN_BWD
+#undef MREM_LN_BWD_V
   return g;
 }
 

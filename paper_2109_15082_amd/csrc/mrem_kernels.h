@@ -139,11 +139,11 @@ int quant_bwd_reduce(int dt, const void* d_q, const void* a, int64_t n, QArg q, 
 // y = LN(x + r) * gamma + beta ; optional codes of y ; mean/rstd saved
 void ln_fwd(int dt, const void* x, const void* r, const float* gamma, const float* beta, void* y, void* ycodes, QArg q,
             float* mu, float* rstd, int T, int H, float eps, hipStream_t st, int8_t* ycodes8 = nullptr);
-// dy = d_a + d_b + d_q * inside(a_q)   (any of the three may be null).  With loss_ref != null the
-// d_b term is the gradient of the squared-error term of Eq. 3 instead: 2 * loss_scale * (a_q - loss_ref),
-// and the sum of (a_q - loss_ref)^2 is returned in the partials.
+// dy = d_a + d_q * inside(a_q) + 2 * loss_scale * (a_q - loss_ref)   (each of d_a, d_q, loss_ref may be null; the
+// last term is the gradient of the squared-error term of Eq. 3, and the sum of (a_q - loss_ref)^2 is returned in
+// the partials).
 // dr = LN backward of dy through LN(x + r); partials[nparts][3H+2]: dgamma, dbeta, colsum(dr), ds, squared error
-int ln_bwd(int dt, const void* d_a, const void* d_b, const void* d_q, const void* a_q, QArg q, const void* x,
+int ln_bwd(int dt, const void* d_a, const void* d_q, const void* a_q, QArg q, const void* x,
            const void* r, const float* mu, const float* rstd, const float* gamma, void* dr, float* partials, int T,
            int H, hipStream_t st, const void* loss_ref = nullptr, float loss_scale = 0.f);
 int ln_bwd_parts(int T);

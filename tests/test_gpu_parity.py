@@ -183,11 +183,18 @@ def _compare_step(B, wl, lr=1e-3, case=None, tol=None, tol_for=None, n_steps=1, 
         got, ref, g_ref = (np.asarray(t, dtype=np.float64).reshape(-1) for t in (got, ref, g_ref))
         rms = max(float(np.sqrt(np.mean(ref * ref))), 1e-30)
         report.append((name, Hh.rel_err(got, ref)))
-        tol_for.setdefault(name, tol + min(2.0, 4.0 * g_tol) * lr_sum[0] / rms)
         top_g = np.abs(g_ref).max() if g_ref.size else 0.0
         slack = g_tol * (np.abs(g_ref) + top_g)
         if allowance is not None:
             slack = slack + np.asarray(allowance, dtype=np.float64).reshape(-1)
+        first = 0.0
+        if first_step[0]:
+            # what the first update can move by when its gradient moves by `slack` (see the element-wise rule below),
+            # as a norm relative to the parameter's
+            eps = case.cfg.adam_eps
+            move = np.minimum(lr_sum[0] * slack * eps / (np.maximum(np.abs(g_ref) - slack, 0.0) + eps) ** 2, 2.0 * lr_sum[0])
+            first = float(np.linalg.norm(move)) / max(float(np.linalg.norm(ref)), 1e-30)
+        tol_for.setdefault(name, tol + min(2.0, 4.0 * g_tol) * lr_sum[0] / rms + first)
         loose_elems[key] = loose_elems.get(key, np.zeros(ref.shape, dtype=bool)) | (np.abs(g_ref) <= slack)
         well = ~loose_elems[key]
         scale = np.abs(ref) + np.abs(ref).max()
