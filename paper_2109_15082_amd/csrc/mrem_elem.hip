@@ -497,7 +497,7 @@ void ln_fwd(int dt, const void* x, const void* r, const float* gamma, const floa
 #undef MREM_LN_FWD
 }
 
-constexpr int kLnBwdWaves = 8;       // wavefronts per block
+constexpr int kLnBwdWaves = 4;       // wavefronts per block (256 threads: such a block still fits beside another stream's product block)
 constexpr int kLnBwdRowsPerWave = 2;  // token rows per wavefront, both in flight when registers allow
 constexpr int kLnBwdRows = kLnBwdWaves * kLnBwdRowsPerWave;  // token rows per block
 int ln_bwd_parts(int T_) { return (T_ + kLnBwdRows - 1) / kLnBwdRows; }
