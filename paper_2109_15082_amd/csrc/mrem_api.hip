@@ -27,6 +27,7 @@ struct mrem_ctx {
   // device that is current then; default priority) and the two events of its fork and join
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  hipEvent_t ev_codes = nullptr;     // the side stream has prepared the weights of the layers above the first
   std::vector<hipEvent_t> ev_layer;  // "the backward pass of layer l is enqueued", one per layer
   std::vector<hipEvent_t> ev_ready;  // [4 * l + i]: the output gradient of linear layer i of layer l is written
   std::vector<hipEvent_t> ev_done;   // [4 * l + i]: its weight-gradient product has read it
@@ -81,7 +82,7 @@ extern "C" mrem_status mrem_create(const mrem_config* cfg, mrem_ctx** out) {
 // a creation that failed half way).
 static void release_side(mrem_ctx* ctx) {
   if (ctx->side) (void)hipStreamSynchronize(ctx->side);
-  for (hipEvent_t* e : {&ctx->ev_fork, &ctx->ev_join}) {
+  for (hipEvent_t* e : {&ctx->ev_fork, &ctx->ev_join, &ctx->ev_codes}) {
     if (*e) (void)hipEventDestroy(*e);
     *e = nullptr;
   }
@@ -98,7 +99,8 @@ static void release_side(mrem_ctx* ctx) {
 static bool create_side(mrem_ctx* ctx, int dev) {
   bool ok = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess &&
             hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) == hipSuccess &&
-            hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) == hipSuccess;
+            hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&ctx->ev_codes, hipEventDisableTiming) == hipSuccess;
   ctx->ev_layer.assign((size_t)ctx->L, nullptr);
   ctx->ev_ready.assign((size_t)ctx->L * 4, nullptr);
   ctx->ev_done.assign((size_t)ctx->L * 4, nullptr);
@@ -299,11 +301,14 @@ void student_linear(const Run& r, const float* params, int l, int i, const void*
   gemm_nt(c->dt, in_codes, c->wK[i], r.at(r.p.lw[l].wcodes[i]), c->wK[i], out, c->wN[i], r.T, c->wN[i], c->wK[i], e, r.st, r.prof);
 }
 
-void prepare_weights(const Run& r, const float* params) {
+// (layers [l0, l1); l1 < 0: to the last layer)
+void prepare_weights(const Run& r, const float* params, int l0 = 0, int l1 = -1) {
   const mrem_ctx* c = r.c;
+  if (l1 < 0) l1 = c->L;
+  if (l0 >= l1) return;
   std::vector<WeightJob> jobs;
-  jobs.reserve((size_t)c->L * 4);
-  for (int l = 0; l < c->L; ++l) {
+  jobs.reserve((size_t)(l1 - l0) * 4);
+  for (int l = l0; l < l1; ++l) {
     const float* base = params + c->layer_stride * l;
     for (int i = 0; i < 4; ++i) {
       WeightJob j;
@@ -939,11 +944,19 @@ extern "C" mrem_status mrem_module_step(mrem_ctx* ctx, float* params, float* ada
     (void)hipEventRecord(ctx->ev_fork, r.st);
     (void)hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
     zero_gradient_slots(r, grads);
-    prepare_weights(r, params);
+    // Only the first layer's weights are prepared on this stream; those of the layers above are prepared on the side
+    // stream ahead of the teacher's pass (which has slack before the loss needs it), so the quantized pass starts after
+    // one layer's worth of that work instead of the whole module's.
+    prepare_weights(r, params, 0, 1);
+    if (ctx->L > 1) {
+      prepare_weights(rt, params, 1, ctx->L);
+      (void)hipEventRecord(ctx->ev_codes, ctx->side);
+    }
     // the two passes are enqueued layer by layer in turn, so that both streams have work from the
     // start also when the caller's queue was empty
     for (int l = 0; l < ctx->L; ++l) {
       teacher_forward(rt, teacher, teacher_cache, x_fp, per_layer_fp, nullptr, l, l + 1);
+      if (l == 1) (void)hipStreamWaitEvent(r.st, ctx->ev_codes, 0);
       student_forward(r, params, x_in, per_layer_q, l, l + 1, mix_fp, x_q, lambda);
     }
     (void)hipEventRecord(ctx->ev_join, ctx->side);
