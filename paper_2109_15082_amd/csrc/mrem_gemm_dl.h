@@ -215,15 +215,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG, MINB) void gemm_dl_k(c
       src[i] = base + OpB::src_offset((gi - OpA::LOADS) * 1024 + lane * 16, ldb);
     }
   }
-  auto issue = [&](int stage_slot) {
+  auto issue_range = [&](int stage_slot, auto first, auto count) {
     unsigned char* dst = smem_dl + stage_slot * STAGE_BYTES + wave * (LPW * 1024);
 #pragma unroll
-    for (int i = 0; i < LPW; ++i) {
+    for (int i = decltype(first)::value; i < decltype(first)::value + decltype(count)::value; ++i) {
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src[i],
                                        (__attribute__((address_space(3))) void*)(dst + i * 1024), 16, 0, 0);
       src[i] += (wave * LPW + i < OpA::LOADS) ? adv_a : adv_b;
     }
   };
+  auto issue = [&](int stage_slot) { issue_range(stage_slot, std::integral_constant<int, 0>{}, std::integral_constant<int, LPW>{}); };
+  // With three or more stages a stage's loads have k-steps to spare, and they go out in KK parts: the first right
+  // behind the barrier, the others ahead of the following k-substeps, so the wavefronts of a SIMD do not queue up all
+  // their loads at once while the matrix pipe waits.  (With two stages every load is needed one k-step later: all at once.)
+  constexpr bool SPREAD = STAGES >= 3 && LPW % KK == 0;
+  constexpr int LPP = SPREAD ? LPW / KK : LPW;
+  bool pend = false;
+  int pslot = 0;
 
   typedef typename std::conditional<I8, i32x16_t, f32x16_t>::type acc_t;
   acc_t acc[MT][NT];
@@ -264,6 +272,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG, MINB) void gemm_dl_k(c
     // k-substeps 0 .. KK-2: fetch the fragments of the next substep, multiply the current one
     static_for<KK - 1>([&](auto kk) {
       constexpr int cur = kk.value & 1, nxt = cur ^ 1;
+      if constexpr (SPREAD) {
+        if (pend) issue_range(pslot, std::integral_constant<int, (kk.value + 1) * LPP>{}, std::integral_constant<int, LPP>{});
+      }
       OpA::template read<kk.value + 1>(fa[nxt], a_addr, stage);
       OpB::template read<kk.value + 1>(fb[nxt], b_addr, stage + OpA::BYTES);
       __builtin_amdgcn_s_setprio(1);
@@ -279,7 +290,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG, MINB) void gemm_dl_k(c
       const int beyond = KT - kt - 2;  // stages after kt + 1 that exist
       wait_vmcnt_stages<LPW, STAGES - 2>(beyond < STAGES - 2 ? beyond : STAGES - 2);
       __builtin_amdgcn_s_barrier();  // stage kt + 1 has landed for everybody; everybody is done reading stage kt
-      if (kt + STAGES < KT) issue(slot);
+      pend = kt + STAGES < KT;
+      pslot = slot;
+      if (pend) issue_range(pslot, std::integral_constant<int, 0>{}, std::integral_constant<int, LPP>{});
       const int nstage = lds0 + next_slot * STAGE_BYTES;
       OpA::template read<0>(fa[last ^ 1], a_addr, nstage);
       OpB::template read<0>(fb[last ^ 1], b_addr, nstage + OpA::BYTES);
